@@ -1,0 +1,179 @@
+/*
+ * libeeverify -- server-side target-model verification pass with early exits
+ * for speculative edge-cloud decoding, for AMD MI355X (gfx950).
+ *
+ * One call of ee_verify runs ONE forward pass of a Llama-style decoder over the
+ * rows [pending, draft_1 .. draft_gamma] (the gamma drafted tokens plus one).
+ * After each requested intermediate layer an exit head (RMSNorm with that
+ * exit's gain, then the shared LM head) yields the argmax token of every row
+ * and that exit's accept length; these are written to pinned host memory and a
+ * hipEvent is recorded, so the caller can read them while the pass is still
+ * running.  After the last layer the final head gives the accept length, the
+ * correction/bonus token and the KV-cache rollback.
+ *
+ * Paper passages the operations follow:
+ *   - Verify: Background, Eq. 2 (target accepts delta <= gamma drafts and
+ *     produces one more token; the prefix then grows by delta+1).
+ *   - Layer recurrence h^(l) = f^(l)(h^(l-1)) and per-layer LM head
+ *     z^(l) = LMHead(h^(l)): Background "Early Exit in LLMs", Eq. 3.
+ *   - Every exit verifies the drafts on its own logits: Methodology Step 2, Eq. 5.
+ *   - Exit results leave the server as soon as they exist: Methodology Step 3;
+ *     Appendix "System Design", server LISTENER/SENDER (Algorithm 2).
+ * Verification is greedy exact-match (the temperature-0 case of the paper's
+ * criterion): draft j is accepted iff it equals the argmax at row j-1 and all
+ * earlier drafts were accepted.  Argmax ties go to the lowest token id.
+ * The KV cache and its rollback are this library's (the paper's server is
+ * handed the whole prefix every round).
+ *
+ * Conventions
+ *   - All pointers in the signatures are HOST pointers.  Device memory is owned
+ *     by the library.  Input arrays belong to the caller and are copied before
+ *     the call returns.
+ *   - Every function returns an int status: EE_OK (0) or a negative EE_E* code;
+ *     ee_last_error() gives a thread-local message for the last failure.
+ *     Nothing throws, nothing aborts.
+ *   - A session is not thread-safe.  A model may be shared by sessions used
+ *     from different threads, but passes of sessions of one model must not
+ *     overlap in time on the GPU unless they run in one ee_verify_batch call.
+ *   - Arithmetic: bf16 weights and KV cache, bf16 MFMA operands with fp32
+ *     accumulation, fp32 residual stream / norms / softmax.
+ */
+#ifndef EE_H
+#define EE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EE_MAX_M 16      /* rows per session and pass: gamma + 1 <= EE_MAX_M          */
+#define EE_MAX_EXITS 16  /* exit heads per pass                                       */
+#define EE_MAX_BATCH 16  /* sessions per ee_verify_batch                              */
+#define EE_MAX_ROWS 48   /* rows per pass over all sessions of a batch                */
+
+#define EE_OK 0
+#define EE_NOT_READY 1        /* ee_query_*: the result is not there yet               */
+#define EE_EINVAL (-1)        /* bad argument                                          */
+#define EE_ESTATE (-2)        /* call not allowed in this state                        */
+#define EE_ECAPACITY (-3)     /* kv_len + gamma + 1 would exceed max_ctx               */
+#define EE_EIO (-4)           /* model file cannot be read                             */
+#define EE_EFORMAT (-5)       /* model file is not in the expected format              */
+#define EE_EDEVICE (-6)       /* HIP error or device-side failure (see ee_last_error)  */
+
+/* ee_prefill flags */
+#define EE_HOLD_LAST 1u       /* cache n-1 tokens, pending = tokens[n-1], no logits     */
+/* ee_session_create flags */
+#define EE_KEEP_LOGITS 1u     /* keep every head's logits of the last pass (debug)      */
+#define EE_NO_AUTOCOMMIT 2u   /* final accept does not move kv_len / pending            */
+#define EE_PHASE_LAUNCHES 4u  /* debug: one kernel launch per phase instead of one
+                                 persistent launch per segment; same results           */
+
+typedef struct ee_model ee_model;     /* opaque; immutable after load                   */
+typedef struct ee_session ee_session; /* opaque; one KV cache, one stream               */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    int32_t n_exits;                       /* exit gains stored in the model            */
+    int32_t exit_layers[EE_MAX_EXITS];     /* 1-based: exit e sits after layer e        */
+    float rope_base, rms_eps;
+    int32_t max_rows;                      /* rows per pass this instance was laid out for */
+    int32_t n_workgroups;                  /* persistent grid size (= compute units)    */
+} ee_model_config;
+
+/* Result block of one pass; lives in pinned host memory owned by the session and
+   stays valid until the next ee_verify / ee_verify_batch / ee_prefill on it.
+   exit_tokens[e], exit_accept_len[e]: readable after ee_wait_exit(e) or
+   ee_query_exit(e) == EE_OK.  The other fields: after ee_wait_final.
+   The paper's exit message x^(e)_{t:t+delta^(e)+1} is
+   draft[0 .. delta^(e)-1] followed by exit_tokens[e][delta^(e)]. */
+typedef struct {
+    int32_t gamma, n_exits;
+    int32_t accept_len;                             /* delta in [0, gamma]              */
+    int32_t next_token;                             /* final_tokens[accept_len]         */
+    int32_t final_tokens[EE_MAX_M];                 /* final-head argmax, rows 0..gamma */
+    int32_t exit_accept_len[EE_MAX_EXITS];          /* delta^(e)                        */
+    int32_t exit_tokens[EE_MAX_EXITS][EE_MAX_M];    /* exit-head argmax, rows 0..gamma  */
+    int32_t device_status;                          /* 0, or != 0 if a device-side wait
+                                                       gave up (pass result invalid)    */
+    int32_t reserved[15];
+} ee_verify_result;
+
+const char *ee_last_error(void);
+
+/* Reads a model file (header + row-major bf16 tensors, see the generator's
+   format description), uploads it to GPU `device` and re-lays the weight
+   matrices out in the tile order the kernels stream.  max_rows (1..EE_MAX_ROWS)
+   is the largest number of rows a pass will carry; ee_model_load uses 16.
+   Cold path; synchronous. */
+int ee_model_load(const char *path, int device, ee_model **out);
+int ee_model_load_ex(const char *path, int device, int max_rows, ee_model **out);
+int ee_model_free(ee_model *m);
+int ee_model_info(const ee_model *m, ee_model_config *out);
+
+/* A session owns a paged bf16 KV cache for up to max_ctx positions, scratch
+   for one pass, a stream, events and a pinned result block.
+   max_gamma in [1, EE_MAX_M-1]. */
+int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, unsigned flags,
+                      ee_session **out);
+int ee_session_free(ee_session *s);
+
+/* Prefill (synchronous): caches KV for all n prompt tokens, sets
+   pending = *first_token = argmax of the final head at the last prompt row,
+   kv_len = n.  With EE_HOLD_LAST (the paper's first round, where the drafts
+   follow the prompt directly): kv_len = n-1, pending = tokens[n-1], no head is
+   evaluated and *first_token is left alone.  Resets the session first.
+   tokens: n ids in [0, vocab). */
+int ee_prefill(ee_session *s, const int32_t *tokens, int n, unsigned flags, int32_t *first_token);
+/* Same, with n_emb rows of bf16[d_model] (raw uint16, row-major) placed before
+   the n tokens: the image-patch-prefix-then-text structure of the paper's
+   vision-language experiment. */
+int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_emb, const int32_t *tokens,
+                      int n, unsigned flags, int32_t *first_token);
+
+/* Asynchronous: enqueues one pass over [pending, draft_tokens[0..gamma-1]] and
+   returns.  exit_layers: n_exits strictly increasing values in [1, L-1], each
+   with a stored exit gain.  *out (may be NULL) receives the session's result
+   block.  A pass still in flight on this session is waited for first. */
+int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
+              int n_exits, const ee_verify_result **out);
+/* One pass for several sessions of one model (multi-client serving): every
+   weight byte is streamed once for all of them; attention, accept and rollback
+   are per session.  drafts[i] has gamma ids; n_sessions * (gamma+1) must not
+   exceed the model's max_rows.  outs may be NULL. */
+int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts,
+                    int gamma, const int32_t *exit_layers, int n_exits,
+                    const ee_verify_result **outs);
+
+int ee_wait_exit(ee_session *s, int exit_idx);   /* blocks until exit exit_idx is published */
+int ee_query_exit(ee_session *s, int exit_idx);  /* EE_OK or EE_NOT_READY                   */
+int ee_wait_final(ee_session *s);                /* blocks until the pass has finished      */
+int ee_query_final(ee_session *s);
+
+/* Milliseconds of GPU time from the start of the last pass to exit exit_idx's
+   event (exit_idx in [0, n_exits)) or to the final event (exit_idx == n_exits).
+   The pass must have finished. */
+int ee_pass_time_ms(ee_session *s, int exit_idx, float *ms);
+
+/* KV rollback / external commit: new_len <= kv_len; pages wholly beyond
+   new_len return to the session's free list. */
+int ee_kv_truncate(ee_session *s, int new_len);
+int ee_set_pending(ee_session *s, int32_t token);
+int ee_kv_len(ee_session *s, int *out);
+int ee_pending(ee_session *s, int32_t *out);
+
+/* Debug (needs EE_KEEP_LOGITS): logits of head head_idx of the last verify pass
+   (0..n_exits-1 = exit heads in order, n_exits = final head) as float[gamma+1][vocab]. */
+int ee_debug_logits(ee_session *s, int head_idx, float *out);
+
+/* hipDeviceSynchronize on `device`: every pass enqueued so far has finished. */
+int ee_device_synchronize(int device);
+
+/* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
+   kernels assume and compares with the plain 16x32 . 32x16 product. */
+int ee_debug_mfma_layout(int device);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

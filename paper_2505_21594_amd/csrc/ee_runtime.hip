@@ -1,0 +1,1033 @@
+// Host runtime and C ABI of libeeverify (declarations and semantics: include/ee.h).
+#include <fcntl.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <sys/mman.h>
+#include <sys/stat.h>
+#include <unistd.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "ee_kernels.hpp"
+
+using namespace ee;
+
+// ------------------------------------------------------------------ errors
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(EE_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+extern "C" const char *ee_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------ objects
+
+struct ee_model {
+    ee_model_config cfg;
+    int device;
+    int nwg;
+    size_t lds_budget;           // dynamic LDS bytes each launch asks for
+    ModelDev host_md;            // host copy of the device descriptor
+    ModelDev *dev_md;
+    std::vector<LayerDev> layers;
+    LayerDev *dev_layers;
+    std::vector<void *> allocs;  // every device allocation of the model
+    const float *g_exit[EE_MAX_EXITS];
+};
+
+struct ee_session {
+    const ee_model *m;
+    unsigned flags;
+    int max_ctx, max_gamma;
+    hipStream_t stream;
+    hipEvent_t ev_start, ev_final, ev_exit[EE_MAX_EXITS];
+    // KV cache
+    int n_pages;
+    uint16_t *kpool, *vpool;
+    int *dev_page_table;
+    int *host_page_table;            // pinned mirror
+    std::vector<int> free_pages;     // LIFO free list of physical pages
+    int pages_used;                  // logical pages mapped
+    float2 *rope;
+    // device state and staging
+    int *dev_state;
+    int *dev_drafts;
+    int *host_drafts;                // pinned
+    int *dev_pf_tokens;
+    int *host_pf_tokens;             // pinned
+    uint16_t *dev_pf_emb;
+    ee_verify_result *result;        // pinned, mapped
+    ee_verify_result *dev_result;
+    SessDev *dev_sessdev;            // [EE_MAX_BATCH] per-pass session descriptors
+    SessDev *host_sessdev;           // pinned staging for them
+    Scratch sc;
+    std::vector<void *> allocs;
+    // host mirror of the session state
+    int kv_len;
+    int pending;
+    bool has_pending;
+    bool in_flight;                  // a verify pass was enqueued and not yet waited for
+    int flight_gamma, flight_exits;
+    ee_session *leader;              // session whose stream/events carry the pass in flight
+};
+
+// ------------------------------------------------------------------ planning
+
+static GemmPlan make_plan(int N, int K, int kbt, int NW)
+{
+    GemmPlan p;
+    memset(&p, 0, sizeof p);
+    p.N = N;
+    p.K = K;
+    p.NT = (N + 15) / 16;
+    p.KT = (K + 31) / 32;
+    p.KBT = std::min(kbt, p.KT);
+    p.nKB = (p.KT + p.KBT - 1) / p.KBT;
+    p.KBT_last = p.KT - (p.nKB - 1) * p.KBT;
+    p.T = (long long)p.NT * p.KT;
+    // most waves sharing one run
+    int maxp = 1;
+    const long long B = (long long)p.NT * p.KBT;
+    for (int kb = 0; kb < p.nKB; ++kb) {
+        int klen = kb == p.nKB - 1 ? p.KBT_last : p.KBT;
+        for (int nt = 0; nt < p.NT; ++nt) {
+            long long s = (long long)kb * B + (long long)nt * klen, e = s + klen - 1;
+            int w0 = (int)(((s + 1) * (long long)NW - 1) / p.T), w1 = (int)(((e + 1) * (long long)NW - 1) / p.T);
+            maxp = std::max(maxp, w1 - w0 + 1);
+        }
+    }
+    p.MAXP = maxp;
+    return p;
+}
+
+template <typename T>
+static int dev_alloc(std::vector<void *> &list, T **out, size_t count, bool zero = true)
+{
+    void *p = nullptr;
+    size_t bytes = std::max<size_t>(count * sizeof(T), 256);
+    HIP_TRY(hipMalloc(&p, bytes));
+    list.push_back(p);
+    if (zero) HIP_TRY(hipMemset(p, 0, bytes));
+    *out = reinterpret_cast<T *>(p);
+    return EE_OK;
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ------------------------------------------------------------------ model load
+
+namespace {
+struct FileMap {
+    void *p = MAP_FAILED;
+    size_t n = 0;
+    ~FileMap()
+    {
+        if (p != MAP_FAILED) munmap(p, n);
+    }
+};
+}  // namespace
+
+static int upload_tiled(ee_model *m, GemmPlan &pl, const uint16_t *const *srcs, int n_src, size_t elems_each,
+                        uint16_t *tmp, const uint4 **out)
+{
+    for (int i = 0; i < n_src; ++i)
+        HIP_TRY(hipMemcpy(tmp + (size_t)i * elems_each, srcs[i], elems_each * 2, hipMemcpyHostToDevice));
+    uint4 *dst = nullptr;
+    int rc = dev_alloc(m->allocs, &dst, (size_t)pl.T * 64, false);
+    if (rc != EE_OK) return rc;
+    hipLaunchKernelGGL(tile_weights_kernel, dim3(2048), dim3(256), 0, 0, tmp, dst, pl);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());
+    *out = dst;
+    return EE_OK;
+}
+
+static int upload_gain(ee_model *m, const uint16_t *src, int d, uint16_t *tmp, const float **out)
+{
+    float *dst = nullptr;
+    int rc = dev_alloc(m->allocs, &dst, (size_t)d, false);
+    if (rc != EE_OK) return rc;
+    HIP_TRY(hipMemcpy(tmp, src, (size_t)d * 2, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((d + 255) / 256), dim3(256), 0, 0, tmp, dst, d);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipDeviceSynchronize());
+    *out = dst;
+    return EE_OK;
+}
+
+extern "C" int ee_model_free(ee_model *m)
+{
+    if (!m) return EE_OK;
+    hipSetDevice(m->device);
+    for (void *p : m->allocs) hipFree(p);
+    delete m;
+    return EE_OK;
+}
+
+extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_model **out)
+{
+    if (!path || !out) return fail(EE_EINVAL, "ee_model_load: null argument");
+    if (max_rows < 1 || max_rows > EE_MAX_ROWS) return fail(EE_EINVAL, "ee_model_load: max_rows %d not in [1,%d]", max_rows, EE_MAX_ROWS);
+    *out = nullptr;
+    int fd = open(path, O_RDONLY);
+    if (fd < 0) return fail(EE_EIO, "ee_model_load: cannot open %s", path);
+    struct stat st;
+    if (fstat(fd, &st) != 0) {
+        close(fd);
+        return fail(EE_EIO, "ee_model_load: cannot stat %s", path);
+    }
+    FileMap fm;
+    fm.n = (size_t)st.st_size;
+    if (fm.n < 256) {
+        close(fd);
+        return fail(EE_EFORMAT, "ee_model_load: %s is shorter than a header", path);
+    }
+    fm.p = mmap(nullptr, fm.n, PROT_READ, MAP_SHARED, fd, 0);
+    close(fd);
+    if (fm.p == MAP_FAILED) return fail(EE_EIO, "ee_model_load: cannot map %s", path);
+    const uint8_t *b = static_cast<const uint8_t *>(fm.p);
+    if (memcmp(b, "EEVMODL1", 8) != 0) return fail(EE_EFORMAT, "ee_model_load: bad magic in %s", path);
+    uint32_t u[8];
+    memcpy(u, b + 8, sizeof u);
+    if (u[0] != 1) return fail(EE_EFORMAT, "ee_model_load: unsupported version %u", u[0]);
+    ee_model_config c;
+    memset(&c, 0, sizeof c);
+    c.n_layers = (int)u[1];
+    c.d_model = (int)u[2];
+    c.n_heads = (int)u[3];
+    c.head_dim = (int)u[4];
+    c.d_ffn = (int)u[5];
+    c.vocab = (int)u[6];
+    c.n_exits = (int)u[7];
+    memcpy(&c.rope_base, b + 40, 4);
+    memcpy(&c.rms_eps, b + 44, 4);
+    if (c.n_layers < 1 || c.n_layers > 4096 || c.d_model < 16 || c.n_heads < 1 || c.d_ffn < 1 || c.vocab < 1 ||
+        c.n_exits < 0 || c.n_exits > EE_MAX_EXITS || (long long)c.n_heads * c.head_dim != c.d_model)
+        return fail(EE_EFORMAT, "ee_model_load: inconsistent header");
+    if (c.head_dim != 64 && c.head_dim != 128)
+        return fail(EE_EFORMAT, "ee_model_load: head_dim %d unsupported (64 or 128)", c.head_dim);
+    if (c.d_model % 16 != 0 || c.d_ffn % 2 != 0)
+        return fail(EE_EFORMAT, "ee_model_load: d_model must be a multiple of 16, d_ffn even");
+    uint32_t ex[EE_MAX_EXITS];
+    memcpy(ex, b + 48, sizeof ex);
+    for (int i = 0; i < c.n_exits; ++i) {
+        c.exit_layers[i] = (int)ex[i];
+        if (c.exit_layers[i] < 1 || c.exit_layers[i] >= c.n_layers || (i > 0 && c.exit_layers[i] <= c.exit_layers[i - 1]))
+            return fail(EE_EFORMAT, "ee_model_load: bad exit layer list");
+    }
+    const size_t d = (size_t)c.d_model, F = (size_t)c.d_ffn, V = (size_t)c.vocab;
+    // tensor offsets: each tensor starts on a 256-byte boundary, fixed order
+    size_t off = 256;
+    auto take = [&](size_t elems) -> const uint16_t * {
+        off = align_up(off, 256);
+        const uint16_t *p = reinterpret_cast<const uint16_t *>(b + off);
+        off += elems * 2;
+        return p;
+    };
+    struct LayerSrc {
+        const uint16_t *g_attn, *wq, *wk, *wv, *wo, *g_ffn, *wg, *wu, *wd;
+    };
+    const uint16_t *emb = take(V * d);
+    std::vector<LayerSrc> ls((size_t)c.n_layers);
+    for (auto &l : ls) {
+        l.g_attn = take(d);
+        l.wq = take(d * d);
+        l.wk = take(d * d);
+        l.wv = take(d * d);
+        l.wo = take(d * d);
+        l.g_ffn = take(d);
+        l.wg = take(F * d);
+        l.wu = take(F * d);
+        l.wd = take(d * F);
+    }
+    const uint16_t *g_final = take(d);
+    const uint16_t *w_lm = take(V * d);
+    const uint16_t *g_exit_src[EE_MAX_EXITS];
+    for (int i = 0; i < c.n_exits; ++i) g_exit_src[i] = take(d);
+    if (off > fm.n) return fail(EE_EFORMAT, "ee_model_load: %s is truncated (%zu < %zu bytes)", path, fm.n, off);
+
+    int n_dev = 0;
+    HIP_TRY(hipGetDeviceCount(&n_dev));
+    if (device < 0 || device >= n_dev) return fail(EE_EINVAL, "ee_model_load: device %d of %d", device, n_dev);
+    HIP_TRY(hipSetDevice(device));
+    hipDeviceProp_t prop;
+    HIP_TRY(hipGetDeviceProperties(&prop, device));
+    if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return fail(EE_EDEVICE, "ee_model_load: device %d is %s, this library is built for gfx950 only", device, prop.gcnArchName);
+
+    ee_model *m = new (std::nothrow) ee_model();
+    if (!m) return fail(EE_EDEVICE, "out of host memory");
+    m->device = device;
+    m->nwg = prop.multiProcessorCount;
+    if (const char *e = getenv("EE_NUM_WORKGROUPS")) {
+        int v = atoi(e);
+        if (v >= 1 && v <= prop.multiProcessorCount) m->nwg = v;
+    }
+    c.max_rows = max_rows;
+    c.n_workgroups = m->nwg;
+    m->cfg = c;
+    const int NW = m->nwg * WAVES_PER_WG;
+    const int kbt = max_rows <= 16 ? 32 : 16;  // K-block size: rows * KBT*32 * 4 bytes of LDS
+
+    ModelDev &md = m->host_md;
+    memset(&md, 0, sizeof md);
+    md.L = c.n_layers;
+    md.d = c.d_model;
+    md.H = c.n_heads;
+    md.hd = c.head_dim;
+    md.F = c.d_ffn;
+    md.V = c.vocab;
+    md.eps = c.rms_eps;
+    md.att_scale = (float)(1.0 / sqrt((double)c.head_dim));
+    md.Kpad_d = (int)align_up(d, 32);
+    md.Kpad_F = (int)align_up(F, 32);
+    md.rows_max = max_rows;
+    md.qkv = make_plan(3 * c.d_model, c.d_model, kbt, NW);
+    md.o = make_plan(c.d_model, c.d_model, kbt, NW);
+    md.gu = make_plan(2 * c.d_ffn, c.d_model, kbt, NW);
+    md.dn = make_plan(c.d_model, c.d_ffn, kbt, NW);
+    md.head = make_plan(c.vocab, c.d_model, kbt, NW);
+    if (c.d_ffn % 16 != 0) {
+        ee_model_free(m);
+        return fail(EE_EFORMAT, "ee_model_load: d_ffn must be a multiple of 16");
+    }
+
+    // LDS: staging of x_hat for the widest span, attention merge buffer, residual squares
+    size_t lds = 0;
+    GemmPlan *plans[5] = {&md.qkv, &md.o, &md.gu, &md.dn, &md.head};
+    for (GemmPlan *p : plans)  // one K-block of x_hat as hi and lo bf16 terms
+        lds = std::max(lds, (size_t)2 * max_rows * (p->KBT * 32 + 8) * 2);
+    lds = std::max(lds, (size_t)WAVES_PER_WG * ATT_ROWS * (c.head_dim + 2) * 4);
+    lds = std::max(lds, (size_t)max_rows * ((c.d_model + m->nwg - 1) / m->nwg) * 4);
+    size_t lds_cap = prop.sharedMemPerBlock;
+    {
+        int optin = 0;
+        if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
+            lds_cap = std::max(lds_cap, (size_t)optin);
+    }
+    if (lds > lds_cap) {
+        ee_model_free(m);
+        return fail(EE_EDEVICE, "ee_model_load: pass needs %zu bytes of LDS, device allows %zu", lds, lds_cap);
+    }
+    // more than half of the CU's LDS keeps it to one workgroup per compute unit
+    lds = std::max(lds, std::min((size_t)84 * 1024, lds_cap));
+    m->lds_budget = lds;
+    hipError_t fe = hipFuncSetAttribute(reinterpret_cast<const void *>(ee_segment_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (fe != hipSuccess) {
+        ee_model_free(m);
+        return fail(EE_EDEVICE, "hipFuncSetAttribute(%zu bytes LDS): %s", lds, hipGetErrorString(fe));
+    }
+
+    int rc = EE_OK;
+    uint16_t *tmp = nullptr;
+    size_t tmp_elems = std::max({V * d, 3 * d * d, 2 * F * d});
+    void *tmp_raw = nullptr;
+    if (hipMalloc(&tmp_raw, tmp_elems * 2) != hipSuccess) {
+        ee_model_free(m);
+        return fail(EE_EDEVICE, "ee_model_load: cannot allocate the upload buffer");
+    }
+    tmp = static_cast<uint16_t *>(tmp_raw);
+
+    auto bail = [&](int code) {
+        hipFree(tmp_raw);
+        ee_model_free(m);
+        return code;
+    };
+
+    // embedding table stays row-major
+    uint16_t *dev_emb = nullptr;
+    if ((rc = dev_alloc(m->allocs, &dev_emb, V * d, false)) != EE_OK) return bail(rc);
+    if (hipMemcpy(dev_emb, emb, V * d * 2, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of the embedding table failed"));
+    md.emb = dev_emb;
+
+    m->layers.resize((size_t)c.n_layers);
+    for (int l = 0; l < c.n_layers; ++l) {
+        LayerDev &ld = m->layers[(size_t)l];
+        const LayerSrc &s = ls[(size_t)l];
+        const uint16_t *qkv[3] = {s.wq, s.wk, s.wv};
+        const uint16_t *gu[2] = {s.wg, s.wu};
+        const uint16_t *wo[1] = {s.wo}, *wd[1] = {s.wd};
+        if ((rc = upload_tiled(m, md.qkv, qkv, 3, d * d, tmp, &ld.wqkv)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.o, wo, 1, d * d, tmp, &ld.wo)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.gu, gu, 2, F * d, tmp, &ld.wgu)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.dn, wd, 1, d * F, tmp, &ld.wd)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(m, s.g_attn, c.d_model, tmp, &ld.g_attn)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(m, s.g_ffn, c.d_model, tmp, &ld.g_ffn)) != EE_OK) return bail(rc);
+    }
+    {
+        const uint16_t *lm[1] = {w_lm};
+        if ((rc = upload_tiled(m, md.head, lm, 1, V * d, tmp, &md.wlm)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(m, g_final, c.d_model, tmp, &md.g_final)) != EE_OK) return bail(rc);
+        for (int i = 0; i < c.n_exits; ++i)
+            if ((rc = upload_gain(m, g_exit_src[i], c.d_model, tmp, &m->g_exit[i])) != EE_OK) return bail(rc);
+    }
+    hipFree(tmp_raw);
+    tmp_raw = nullptr;
+
+    // partial-result buffers, one per GEMM shape: pieces never written stay zero
+    for (GemmPlan *p : plans) {
+        size_t n = (size_t)p->nKB * p->NT * p->MAXP * max_rows * 16;
+        if ((rc = dev_alloc(m->allocs, &p->part, n, true)) != EE_OK) return bail(rc);
+    }
+    if ((rc = dev_alloc(m->allocs, &m->dev_layers, m->layers.size(), false)) != EE_OK) return bail(rc);
+    if (hipMemcpy(m->dev_layers, m->layers.data(), m->layers.size() * sizeof(LayerDev), hipMemcpyHostToDevice) != hipSuccess)
+        return bail(fail(EE_EDEVICE, "upload of the layer table failed"));
+    md.layers = m->dev_layers;
+    if ((rc = dev_alloc(m->allocs, &m->dev_md, 1, false)) != EE_OK) return bail(rc);
+    if (hipMemcpy(m->dev_md, &md, sizeof md, hipMemcpyHostToDevice) != hipSuccess)
+        return bail(fail(EE_EDEVICE, "upload of the model descriptor failed"));
+    if (hipDeviceSynchronize() != hipSuccess) return bail(fail(EE_EDEVICE, "device error while loading the model"));
+    *out = m;
+    return EE_OK;
+}
+
+extern "C" int ee_model_load(const char *path, int device, ee_model **out)
+{
+    return ee_model_load_ex(path, device, 16, out);
+}
+
+extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
+{
+    if (!m || !out) return fail(EE_EINVAL, "ee_model_info: null argument");
+    *out = m->cfg;
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ sessions
+
+static int attention_splits(const ee_model *m, int n_sess, int M)
+{
+    int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
+    int units = n_sess * m->cfg.n_heads * chunks;
+    int s = m->nwg / std::max(units, 1);
+    return std::max(1, std::min(s, ATT_MAX_SPLITS));
+}
+
+extern "C" int ee_session_free(ee_session *s)
+{
+    if (!s) return EE_OK;
+    hipSetDevice(s->m->device);
+    if (s->stream) hipStreamSynchronize(s->stream);
+    for (void *p : s->allocs) hipFree(p);
+    if (s->host_page_table) hipHostFree(s->host_page_table);
+    if (s->host_drafts) hipHostFree(s->host_drafts);
+    if (s->host_pf_tokens) hipHostFree(s->host_pf_tokens);
+    if (s->result) hipHostFree(s->result);
+    if (s->host_sessdev) hipHostFree(s->host_sessdev);
+    if (s->ev_start) hipEventDestroy(s->ev_start);
+    if (s->ev_final) hipEventDestroy(s->ev_final);
+    for (hipEvent_t e : s->ev_exit)
+        if (e) hipEventDestroy(e);
+    if (s->stream) hipStreamDestroy(s->stream);
+    delete s;
+    return EE_OK;
+}
+
+extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, unsigned flags, ee_session **out)
+{
+    if (!m || !out) return fail(EE_EINVAL, "ee_session_create: null argument");
+    *out = nullptr;
+    if (max_gamma < 1 || max_gamma > EE_MAX_M - 1) return fail(EE_EINVAL, "ee_session_create: max_gamma %d not in [1,%d]", max_gamma, EE_MAX_M - 1);
+    if (max_gamma + 1 > m->cfg.max_rows) return fail(EE_EINVAL, "ee_session_create: max_gamma+1 exceeds the model's max_rows %d", m->cfg.max_rows);
+    if (max_ctx < max_gamma + 2 || max_ctx > (1 << 20)) return fail(EE_EINVAL, "ee_session_create: max_ctx %d out of range", max_ctx);
+    HIP_TRY(hipSetDevice(m->device));
+    ee_session *s = new (std::nothrow) ee_session();
+    if (!s) return fail(EE_EDEVICE, "out of host memory");
+    s->m = m;
+    s->flags = flags;
+    s->max_ctx = max_ctx;
+    s->max_gamma = max_gamma;
+    s->leader = s;
+    const ee_model_config &c = m->cfg;
+    const int rows_max = c.max_rows;
+    const size_t d = (size_t)c.d_model;
+    int rc = EE_OK;
+#define S_TRY(expr)                  \
+    do {                             \
+        rc = (expr);                 \
+        if (rc != EE_OK) {           \
+            ee_session_free(s);      \
+            return rc;               \
+        }                            \
+    } while (0)
+#define S_HIP(expr)                                                                          \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            ee_session_free(s);                                                              \
+            return fail(EE_EDEVICE, "%s failed: %s", #expr, hipGetErrorString(e_));          \
+        }                                                                                    \
+    } while (0)
+
+    S_HIP(hipStreamCreate(&s->stream));
+    S_HIP(hipEventCreate(&s->ev_start));
+    S_HIP(hipEventCreate(&s->ev_final));
+    for (int i = 0; i < EE_MAX_EXITS; ++i) S_HIP(hipEventCreate(&s->ev_exit[i]));
+
+    s->n_pages = (max_ctx + KV_PAGE - 1) / KV_PAGE;
+    size_t kv_elems = (size_t)c.n_layers * s->n_pages * c.n_heads * KV_PAGE * c.head_dim;
+    S_TRY(dev_alloc(s->allocs, &s->kpool, kv_elems));
+    S_TRY(dev_alloc(s->allocs, &s->vpool, kv_elems));
+    S_TRY(dev_alloc(s->allocs, &s->dev_page_table, (size_t)s->n_pages));
+    S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_page_table), (size_t)s->n_pages * sizeof(int), hipHostMallocDefault));
+    memset(s->host_page_table, 0, (size_t)s->n_pages * sizeof(int));
+    // LIFO free list: the first logical page gets the highest physical page, so
+    // the mapping is never the identity
+    for (int p = 0; p < s->n_pages; ++p) s->free_pages.push_back(p);
+    s->pages_used = 0;
+
+    // RoPE table in double on the host: angle = pos * base^(-2j/hd)
+    {
+        const int half = c.head_dim / 2;
+        std::vector<float2> tab((size_t)max_ctx * half);
+        for (int j = 0; j < half; ++j) {
+            double theta = pow((double)c.rope_base, -2.0 * (double)j / (double)c.head_dim);
+            for (int pos = 0; pos < max_ctx; ++pos) {
+                double ang = (double)pos * theta;
+                tab[(size_t)pos * half + j] = make_float2((float)cos(ang), (float)sin(ang));
+            }
+        }
+        S_TRY(dev_alloc(s->allocs, &s->rope, tab.size(), false));
+        S_HIP(hipMemcpy(s->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice));
+    }
+
+    S_TRY(dev_alloc(s->allocs, &s->dev_state, 4));
+    S_TRY(dev_alloc(s->allocs, &s->dev_drafts, EE_MAX_M));
+    S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_drafts), EE_MAX_M * sizeof(int), hipHostMallocDefault));
+    S_TRY(dev_alloc(s->allocs, &s->dev_pf_tokens, (size_t)rows_max));
+    S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_pf_tokens), (size_t)rows_max * sizeof(int), hipHostMallocDefault));
+    S_TRY(dev_alloc(s->allocs, &s->dev_pf_emb, (size_t)rows_max * d));
+    S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->result), sizeof(ee_verify_result), hipHostMallocMapped));
+    memset(s->result, 0, sizeof(ee_verify_result));
+    S_HIP(hipHostGetDevicePointer(reinterpret_cast<void **>(&s->dev_result), s->result, 0));
+    S_TRY(dev_alloc(s->allocs, &s->dev_sessdev, EE_MAX_BATCH));
+    S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_sessdev), EE_MAX_BATCH * sizeof(SessDev), hipHostMallocDefault));
+
+    Scratch &sc = s->sc;
+    const ModelDev &md = m->host_md;
+    S_TRY(dev_alloc(s->allocs, &sc.h, (size_t)rows_max * d));
+    S_TRY(dev_alloc(s->allocs, &sc.q, (size_t)rows_max * d));
+    S_TRY(dev_alloc(s->allocs, &sc.xn, (size_t)rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.xh, (size_t)rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.attn, (size_t)rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.u, (size_t)rows_max * md.Kpad_F));
+    S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
+    S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
+    {
+        // attention partials: items <= max(units*splits) <= max(nwg, units); bound generously
+        size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
+        size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * 2;
+        S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
+    }
+    if (flags & EE_KEEP_LOGITS)
+        S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
+    S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
+    S_TRY(dev_alloc(s->allocs, &sc.bar, 1));
+    S_TRY(dev_alloc(s->allocs, &sc.err, 1));
+    S_HIP(hipDeviceSynchronize());
+#undef S_TRY
+#undef S_HIP
+    *out = s;
+    return EE_OK;
+}
+
+// map logical pages so that positions [0, upto) are backed; upload new entries
+static int ensure_pages(ee_session *s, int upto, hipStream_t stream)
+{
+    int need = (upto + KV_PAGE - 1) / KV_PAGE;
+    if (need > s->n_pages) return fail(EE_ECAPACITY, "KV cache: %d positions exceed max_ctx %d", upto, s->max_ctx);
+    int first_new = s->pages_used;
+    while (s->pages_used < need) {
+        if (s->free_pages.empty()) return fail(EE_ECAPACITY, "KV cache: out of pages");
+        s->host_page_table[s->pages_used++] = s->free_pages.back();
+        s->free_pages.pop_back();
+    }
+    if (s->pages_used > first_new)
+        HIP_TRY(hipMemcpyAsync(s->dev_page_table + first_new, s->host_page_table + first_new,
+                               (size_t)(s->pages_used - first_new) * sizeof(int), hipMemcpyHostToDevice, stream));
+    return EE_OK;
+}
+
+static void release_pages(ee_session *s, int keep_positions)
+{
+    int keep = (keep_positions + KV_PAGE - 1) / KV_PAGE;
+    while (s->pages_used > keep) s->free_pages.push_back(s->host_page_table[--s->pages_used]);
+}
+
+static void fill_sessdev(SessDev &sd, const ee_session *s)
+{
+    sd.state = s->dev_state;
+    sd.page_table = s->dev_page_table;
+    sd.kpool = s->kpool;
+    sd.vpool = s->vpool;
+    sd.rope = s->rope;
+    sd.drafts = s->dev_drafts;
+    sd.result = s->dev_result;
+    sd.n_pages = s->n_pages;
+    sd.pad_ = 0;
+}
+
+// launches one segment: either one cooperative launch or one launch per phase
+static int launch_segment(const ee_session *lead, PassArgs &a)
+{
+    const ee_model *m = lead->m;
+    int n_phases = (a.do_embed ? 1 : 0) + 10 * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 3 : 0);
+    if (n_phases == 0) return EE_OK;
+    if (lead->flags & EE_PHASE_LAUNCHES) {
+        for (int ph = 0; ph < n_phases; ++ph) {
+            a.ph_lo = ph;
+            a.ph_hi = ph + 1;
+            hipLaunchKernelGGL(ee_segment_kernel, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
+            HIP_TRY(hipGetLastError());
+        }
+    } else {
+        a.ph_lo = 0;
+        a.ph_hi = n_phases;
+        void *params[] = {&a};
+        HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(ee_segment_kernel), dim3(m->nwg),
+                                           dim3(WG_THREADS), params, (unsigned)m->lds_budget, lead->stream));
+    }
+    return EE_OK;
+}
+
+static void base_args(const ee_session *lead, PassArgs &a)
+{
+    memset(&a, 0, sizeof a);
+    a.md = lead->m->dev_md;
+    a.sc = lead->sc;
+    a.nwg = lead->m->nwg;
+    a.keep_logits = (lead->flags & EE_KEEP_LOGITS) ? 1 : 0;
+    a.spin_limit = 1u << 22;
+    if (const char *e = getenv("EE_SPIN_LIMIT")) a.spin_limit = (unsigned)strtoul(e, nullptr, 10);
+}
+
+static int finish_flight(ee_session *s)
+{
+    if (!s->in_flight) return EE_OK;
+    ee_session *lead = s->leader;
+    HIP_TRY(hipEventSynchronize(lead->ev_final));
+    s->in_flight = false;
+    if (s->result->device_status != 0) return fail(EE_EDEVICE, "a device-side wait gave up during the pass; results are invalid");
+    if (!(s->flags & EE_NO_AUTOCOMMIT)) {
+        s->kv_len += s->result->accept_len + 1;
+        s->pending = s->result->next_token;
+    }
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ prefill
+
+static int set_device_state(ee_session *s, bool set_kv, bool set_pending)
+{
+    hipLaunchKernelGGL(set_state_kernel, dim3(1), dim3(64), 0, s->stream, s->dev_state, s->kv_len, s->pending,
+                       set_kv ? 1 : 0, set_pending ? 1 : 0);
+    HIP_TRY(hipGetLastError());
+    return EE_OK;
+}
+
+extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_emb, const int32_t *tokens, int n,
+                                 unsigned flags, int32_t *first_token)
+{
+    if (!s) return fail(EE_EINVAL, "ee_prefill: null session");
+    if (n_emb < 0 || n < 0 || (n_emb > 0 && !emb_bf16) || (n > 0 && !tokens)) return fail(EE_EINVAL, "ee_prefill: bad arguments");
+    const ee_model *m = s->m;
+    const ee_model_config &c = m->cfg;
+    for (int i = 0; i < n; ++i)
+        if (tokens[i] < 0 || tokens[i] >= c.vocab) return fail(EE_EINVAL, "ee_prefill: token %d at %d outside [0,%d)", tokens[i], i, c.vocab);
+    const bool hold = (flags & EE_HOLD_LAST) != 0;
+    if (hold && n < 1) return fail(EE_EINVAL, "ee_prefill: EE_HOLD_LAST needs at least one token");
+    const int total = n_emb + n - (hold ? 1 : 0);
+    if (!hold && total < 1) return fail(EE_EINVAL, "ee_prefill: empty prompt");
+    if (total + 1 > s->max_ctx) return fail(EE_ECAPACITY, "ee_prefill: %d rows do not fit max_ctx %d", total, s->max_ctx);
+    HIP_TRY(hipSetDevice(m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK && rc != EE_EDEVICE) return rc;
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    // reset
+    release_pages(s, 0);
+    s->kv_len = 0;
+    s->has_pending = false;
+    s->leader = s;
+    s->flight_gamma = 0;
+    s->flight_exits = 0;
+    s->result->device_status = 0;
+    if ((rc = ensure_pages(s, total + 1, s->stream)) != EE_OK) return rc;
+
+    fill_sessdev(s->host_sessdev[0], s);
+    HIP_TRY(hipMemcpyAsync(s->dev_sessdev, s->host_sessdev, sizeof(SessDev), hipMemcpyHostToDevice, s->stream));
+    const int chunk = c.max_rows;
+    const size_t d = (size_t)c.d_model;
+    for (int start = 0; start < total; start += chunk) {
+        const int rows = std::min(chunk, total - start);
+        HIP_TRY(hipStreamSynchronize(s->stream));  // staging buffers are reused
+        for (int i = 0; i < rows; ++i) {
+            int r = start + i;
+            s->host_pf_tokens[i] = r < n_emb ? -1 : tokens[r - n_emb];
+        }
+        HIP_TRY(hipMemcpyAsync(s->dev_pf_tokens, s->host_pf_tokens, (size_t)rows * sizeof(int), hipMemcpyHostToDevice, s->stream));
+        if (start < n_emb) {
+            int ne = std::min(rows, n_emb - start);
+            HIP_TRY(hipMemcpyAsync(s->dev_pf_emb, emb_bf16 + (size_t)start * d, (size_t)ne * d * 2, hipMemcpyHostToDevice, s->stream));
+        }
+        const bool last = (start + rows == total) && !hold;
+        PassArgs a;
+        base_args(s, a);
+        a.n_sess = 1;
+        a.M = rows;
+        a.rows = rows;
+        a.mode = 1;
+        a.pf_tokens = s->dev_pf_tokens;
+        a.pf_emb = s->dev_pf_emb;
+        a.pf_pos0 = start;
+        a.layer_begin = 0;
+        a.layer_end = c.n_layers;
+        a.do_embed = 1;
+        a.head_kind = last ? HEAD_PREFILL : HEAD_NONE;
+        a.head_idx = 0;
+        a.head_gain = m->host_md.g_final;
+        a.att_splits = attention_splits(m, 1, rows);
+        a.sess = s->dev_sessdev;
+        if ((rc = launch_segment(s, a)) != EE_OK) return rc;
+    }
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    s->kv_len = total;
+    if (hold) {
+        s->pending = tokens[n - 1];
+    } else {
+        if (s->result->device_status != 0) return fail(EE_EDEVICE, "a device-side wait gave up during prefill");
+        s->pending = s->result->next_token;
+        if (first_token) *first_token = s->pending;
+    }
+    s->has_pending = true;
+    if ((rc = set_device_state(s, true, true)) != EE_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    return EE_OK;
+}
+
+extern "C" int ee_prefill(ee_session *s, const int32_t *tokens, int n, unsigned flags, int32_t *first_token)
+{
+    return ee_prefill_embeds(s, nullptr, 0, tokens, n, flags, first_token);
+}
+
+// ------------------------------------------------------------------ verify
+
+static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exits, const float **gains)
+{
+    if (n_exits < 0 || n_exits > EE_MAX_EXITS || (n_exits > 0 && !exit_layers))
+        return fail(EE_EINVAL, "ee_verify: n_exits %d not in [0,%d]", n_exits, EE_MAX_EXITS);
+    for (int e = 0; e < n_exits; ++e) {
+        if (exit_layers[e] < 1 || exit_layers[e] > m->cfg.n_layers - 1)
+            return fail(EE_EINVAL, "ee_verify: exit layer %d not in [1,%d]", exit_layers[e], m->cfg.n_layers - 1);
+        if (e > 0 && exit_layers[e] <= exit_layers[e - 1]) return fail(EE_EINVAL, "ee_verify: exit layers must increase strictly");
+        gains[e] = nullptr;
+        for (int i = 0; i < m->cfg.n_exits; ++i)
+            if (m->cfg.exit_layers[i] == exit_layers[e]) gains[e] = m->g_exit[i];
+        if (!gains[e]) return fail(EE_EINVAL, "ee_verify: the model stores no exit gain for layer %d", exit_layers[e]);
+    }
+    return EE_OK;
+}
+
+extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                               const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
+{
+    if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
+        return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
+    for (int i = 0; i < n_sessions; ++i)
+        if (!sessions[i] || !drafts[i]) return fail(EE_EINVAL, "ee_verify: null session or drafts");
+    ee_session *lead = sessions[0];
+    const ee_model *m = lead->m;
+    const ee_model_config &c = m->cfg;
+    const int M = gamma + 1;
+    if (gamma < 1) return fail(EE_EINVAL, "ee_verify: gamma %d < 1", gamma);
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        if (s->m != m) return fail(EE_EINVAL, "ee_verify_batch: sessions of different models");
+        if (gamma > s->max_gamma) return fail(EE_EINVAL, "ee_verify: gamma %d exceeds the session's max_gamma %d", gamma, s->max_gamma);
+        for (int j = 0; j < i; ++j)
+            if (sessions[j] == s) return fail(EE_EINVAL, "ee_verify_batch: session listed twice");
+        for (int j = 0; j < gamma; ++j)
+            if (drafts[i][j] < 0 || drafts[i][j] >= c.vocab)
+                return fail(EE_EINVAL, "ee_verify: draft token %d outside [0,%d)", drafts[i][j], c.vocab);
+    }
+    if (n_sessions * M > c.max_rows) return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, c.max_rows);
+    const float *gains[EE_MAX_EXITS];
+    int rc = check_exits(m, exit_layers, n_exits, gains);
+    if (rc != EE_OK) return rc;
+    HIP_TRY(hipSetDevice(m->device));
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        if ((rc = finish_flight(s)) != EE_OK) return rc;
+        if (!s->has_pending) return fail(EE_ESTATE, "ee_verify: session has no pending token (call ee_prefill first)");
+        if (s->kv_len + M > s->max_ctx) return fail(EE_ECAPACITY, "ee_verify: kv_len %d + %d rows exceed max_ctx %d", s->kv_len, M, s->max_ctx);
+    }
+    // everything below is enqueued on the leader's stream; other sessions' own
+    // streams are idle here (their last pass has been waited for)
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        if (s != lead) HIP_TRY(hipStreamSynchronize(s->stream));
+        if ((rc = ensure_pages(s, s->kv_len + M, lead->stream)) != EE_OK) return rc;
+        memcpy(s->host_drafts, drafts[i], (size_t)gamma * sizeof(int));
+        HIP_TRY(hipMemcpyAsync(s->dev_drafts, s->host_drafts, (size_t)gamma * sizeof(int), hipMemcpyHostToDevice, lead->stream));
+        s->result->gamma = gamma;
+        s->result->n_exits = n_exits;
+        s->result->device_status = 0;
+    }
+    PassArgs a;
+    base_args(lead, a);
+    a.n_sess = n_sessions;
+    a.M = M;
+    a.rows = n_sessions * M;
+    a.mode = 0;
+    a.att_splits = attention_splits(m, n_sessions, M);
+    a.commit = 1;
+    for (int i = 0; i < n_sessions; ++i) {
+        fill_sessdev(lead->host_sessdev[i], sessions[i]);
+        if (sessions[i]->flags & EE_NO_AUTOCOMMIT) a.commit = 0;
+    }
+    for (int i = 0; i < n_sessions; ++i)
+        if (((sessions[i]->flags & EE_NO_AUTOCOMMIT) != 0) != (a.commit == 0))
+            return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
+    HIP_TRY(hipMemcpyAsync(lead->dev_sessdev, lead->host_sessdev, (size_t)n_sessions * sizeof(SessDev),
+                           hipMemcpyHostToDevice, lead->stream));
+    a.sess = lead->dev_sessdev;
+
+    HIP_TRY(hipEventRecord(lead->ev_start, lead->stream));
+    int layer = 0;
+    for (int e = 0; e <= n_exits; ++e) {
+        const bool fin = (e == n_exits);
+        a.layer_begin = layer;
+        a.layer_end = fin ? c.n_layers : exit_layers[e];
+        a.do_embed = (e == 0) ? 1 : 0;
+        a.head_kind = fin ? HEAD_FINAL : HEAD_EXIT;
+        a.head_idx = e;
+        a.head_gain = fin ? m->host_md.g_final : gains[e];
+        if ((rc = launch_segment(lead, a)) != EE_OK) return rc;
+        HIP_TRY(hipEventRecord(fin ? lead->ev_final : lead->ev_exit[e], lead->stream));
+        layer = a.layer_end;
+    }
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        s->in_flight = true;
+        s->leader = lead;
+        s->flight_gamma = gamma;
+        s->flight_exits = n_exits;
+        if (outs) outs[i] = s->result;
+    }
+    return EE_OK;
+}
+
+extern "C" int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers, int n_exits,
+                         const ee_verify_result **out)
+{
+    if (!s) return fail(EE_EINVAL, "ee_verify: null session");
+    ee_session *ss[1] = {s};
+    const int32_t *dd[1] = {draft_tokens};
+    const ee_verify_result *oo[1] = {nullptr};
+    int rc = ee_verify_batch(ss, 1, dd, gamma, exit_layers, n_exits, oo);
+    if (rc == EE_OK && out) *out = oo[0];
+    return rc;
+}
+
+// ------------------------------------------------------------------ waiting
+
+static int exit_event(ee_session *s, int exit_idx, hipEvent_t *ev)
+{
+    if (!s) return fail(EE_EINVAL, "null session");
+    if (s->flight_exits < 0 || exit_idx < 0 || exit_idx >= s->flight_exits)
+        return fail(EE_EINVAL, "exit index %d not in [0,%d)", exit_idx, s->flight_exits);
+    *ev = s->leader->ev_exit[exit_idx];
+    return EE_OK;
+}
+
+extern "C" int ee_wait_exit(ee_session *s, int exit_idx)
+{
+    hipEvent_t ev;
+    int rc = exit_event(s, exit_idx, &ev);
+    if (rc != EE_OK) return rc;
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_wait_exit: no verify pass was enqueued");
+    HIP_TRY(hipEventSynchronize(ev));
+    return EE_OK;
+}
+
+extern "C" int ee_query_exit(ee_session *s, int exit_idx)
+{
+    hipEvent_t ev;
+    int rc = exit_event(s, exit_idx, &ev);
+    if (rc != EE_OK) return rc;
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_query_exit: no verify pass was enqueued");
+    hipError_t e = hipEventQuery(ev);
+    if (e == hipSuccess) return EE_OK;
+    if (e == hipErrorNotReady) return EE_NOT_READY;
+    return fail(EE_EDEVICE, "hipEventQuery: %s", hipGetErrorString(e));
+}
+
+extern "C" int ee_wait_final(ee_session *s)
+{
+    if (!s) return fail(EE_EINVAL, "null session");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_wait_final: no verify pass was enqueued");
+    return finish_flight(s);
+}
+
+extern "C" int ee_query_final(ee_session *s)
+{
+    if (!s) return fail(EE_EINVAL, "null session");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_query_final: no verify pass was enqueued");
+    if (!s->in_flight) return EE_OK;
+    hipError_t e = hipEventQuery(s->leader->ev_final);
+    if (e == hipSuccess) return EE_OK;
+    if (e == hipErrorNotReady) return EE_NOT_READY;
+    return fail(EE_EDEVICE, "hipEventQuery: %s", hipGetErrorString(e));
+}
+
+extern "C" int ee_pass_time_ms(ee_session *s, int exit_idx, float *ms)
+{
+    if (!s || !ms) return fail(EE_EINVAL, "null argument");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_pass_time_ms: no verify pass was enqueued");
+    if (s->in_flight) return fail(EE_ESTATE, "ee_pass_time_ms: the pass has not been waited for");
+    if (exit_idx < 0 || exit_idx > s->flight_exits) return fail(EE_EINVAL, "exit index %d not in [0,%d]", exit_idx, s->flight_exits);
+    ee_session *lead = s->leader;
+    hipEvent_t ev = exit_idx == s->flight_exits ? lead->ev_final : lead->ev_exit[exit_idx];
+    HIP_TRY(hipEventElapsedTime(ms, lead->ev_start, ev));
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ state
+
+extern "C" int ee_kv_truncate(ee_session *s, int new_len)
+{
+    if (!s) return fail(EE_EINVAL, "null session");
+    HIP_TRY(hipSetDevice(s->m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    if (new_len < 0 || new_len > s->kv_len) return fail(EE_EINVAL, "ee_kv_truncate: %d not in [0, kv_len=%d]", new_len, s->kv_len);
+    s->kv_len = new_len;
+    release_pages(s, new_len);
+    if ((rc = set_device_state(s, true, false)) != EE_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    return EE_OK;
+}
+
+extern "C" int ee_set_pending(ee_session *s, int32_t token)
+{
+    if (!s) return fail(EE_EINVAL, "null session");
+    if (token < 0 || token >= s->m->cfg.vocab) return fail(EE_EINVAL, "ee_set_pending: token %d outside [0,%d)", token, s->m->cfg.vocab);
+    HIP_TRY(hipSetDevice(s->m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    s->pending = token;
+    s->has_pending = true;
+    if ((rc = set_device_state(s, false, true)) != EE_OK) return rc;
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    return EE_OK;
+}
+
+extern "C" int ee_kv_len(ee_session *s, int *out)
+{
+    if (!s || !out) return fail(EE_EINVAL, "null argument");
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    *out = s->kv_len;
+    return EE_OK;
+}
+
+extern "C" int ee_pending(ee_session *s, int32_t *out)
+{
+    if (!s || !out) return fail(EE_EINVAL, "null argument");
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    if (!s->has_pending) return fail(EE_ESTATE, "ee_pending: no pending token");
+    *out = s->pending;
+    return EE_OK;
+}
+
+extern "C" int ee_debug_logits(ee_session *s, int head_idx, float *out)
+{
+    if (!s || !out) return fail(EE_EINVAL, "null argument");
+    if (!(s->flags & EE_KEEP_LOGITS)) return fail(EE_ESTATE, "ee_debug_logits: session was created without EE_KEEP_LOGITS");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_debug_logits: no verify pass was enqueued");
+    if (s->leader != s) return fail(EE_ESTATE, "ee_debug_logits: only for single-session passes");
+    if (head_idx < 0 || head_idx > s->flight_exits) return fail(EE_EINVAL, "head index %d not in [0,%d]", head_idx, s->flight_exits);
+    HIP_TRY(hipSetDevice(s->m->device));
+    HIP_TRY(hipEventSynchronize(s->ev_final));
+    const size_t V = (size_t)s->m->cfg.vocab, rows_max = (size_t)s->m->cfg.max_rows;
+    const int M = s->flight_gamma + 1;
+    HIP_TRY(hipMemcpy(out, s->sc.logits + (size_t)head_idx * rows_max * V, (size_t)M * V * sizeof(float), hipMemcpyDeviceToHost));
+    return EE_OK;
+}
+
+extern "C" int ee_device_synchronize(int device)
+{
+    HIP_TRY(hipSetDevice(device));
+    HIP_TRY(hipDeviceSynchronize());
+    return EE_OK;
+}
+
+// ------------------------------------------------------------------ self-check of the MFMA lane layout
+
+// Fills A[16][32] and B[32][16] with small integers, runs one MFMA through the
+// lane layout the kernels assume and compares with the plain product.
+// Returns EE_OK when every element agrees.
+extern "C" int ee_debug_mfma_layout(int device)
+{
+    HIP_TRY(hipSetDevice(device));
+    uint16_t ha[64 * 8], hb[64 * 8];
+    float A[16][32], B[32][16];
+    for (int i = 0; i < 16; ++i)
+        for (int k = 0; k < 32; ++k) A[i][k] = (float)((i * 7 + k * 3) % 13 - 6);
+    for (int k = 0; k < 32; ++k)
+        for (int j = 0; j < 16; ++j) B[k][j] = (float)((k * 5 + j * 11) % 9 - 4);
+    auto bf = [](float f) {
+        uint32_t u;
+        memcpy(&u, &f, 4);
+        return (uint16_t)(u >> 16);  // small integers are exact in bf16
+    };
+    for (int l = 0; l < 64; ++l)
+        for (int e = 0; e < 8; ++e) {
+            ha[l * 8 + e] = bf(A[l & 15][(l >> 4) * 8 + e]);
+            hb[l * 8 + e] = bf(B[(l >> 4) * 8 + e][l & 15]);
+        }
+    uint4 *da = nullptr, *db = nullptr;
+    float *dout = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&da), sizeof ha));
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&db), sizeof hb));
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&dout), 256 * sizeof(float)));
+    HIP_TRY(hipMemcpy(da, ha, sizeof ha, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(db, hb, sizeof hb, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(mfma_layout_probe_kernel, dim3(1), dim3(64), 0, 0, da, db, dout);
+    HIP_TRY(hipGetLastError());
+    float out[256];
+    HIP_TRY(hipMemcpy(out, dout, sizeof out, hipMemcpyDeviceToHost));
+    hipFree(da);
+    hipFree(db);
+    hipFree(dout);
+    int bad = 0;
+    for (int l = 0; l < 64; ++l)
+        for (int r = 0; r < 4; ++r) {
+            int i = (l >> 4) * 4 + r, j = l & 15;
+            float ref = 0.f;
+            for (int k = 0; k < 32; ++k) ref += A[i][k] * B[k][j];
+            if (out[l * 4 + r] != ref) ++bad;
+        }
+    if (bad) return fail(EE_EDEVICE, "MFMA lane layout differs from the assumed one in %d of 256 elements", bad);
+    return EE_OK;
+}

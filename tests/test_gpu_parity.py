@@ -1,0 +1,318 @@
+"""GPU parity: libeeverify (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Everything here needs a real MI355X."""
+import numpy as np
+import pytest
+
+import eegen
+import paper_2505_21594_amd as ee
+from oracle import oracle as eo
+from tests.parity import check_pass, gpu_logits
+
+pytestmark = pytest.mark.gpu
+
+TINY_EXITS = [2]
+# several tiles along N and K, ragged K (F = 1072 -> 33.5 k-tiles), two K-blocks, hd = 128
+MID = eegen.ModelConfig(n_layers=3, d_model=1280, n_heads=10, head_dim=128, d_ffn=1072, vocab=3000,
+                        exit_layers=(1, 2))
+
+
+@pytest.fixture(scope="module")
+def tiny_path(model_dir):
+    p = f"{model_dir}/gpu_tiny.bin"
+    eegen.write_model(p, eegen.TINY, 2024, gains="uniform")
+    return p
+
+
+@pytest.fixture(scope="module")
+def tiny_pair(tiny_path):
+    g = ee.Model(tiny_path)
+    o = eo.Model(tiny_path)
+    yield g, o
+    g.free()
+
+
+@pytest.fixture(scope="module")
+def mid_pair(model_dir):
+    p = f"{model_dir}/gpu_mid.bin"
+    eegen.write_model(p, MID, 77, gains="uniform", std=0.03)
+    g = ee.Model(p)
+    o = eo.Model(p)
+    yield g, o
+    g.free()
+
+
+def test_mfma_lane_layout():
+    ee.ee_debug_mfma_layout(0)
+
+
+def _one_round(g, o, prompt, drafts, exits, flags=0, what=""):
+    gs = g.session(len(prompt) + 64, max_gamma=15, flags=ee.KEEP_LOGITS | flags)
+    os_ = o.session(len(prompt) + 64)
+    try:
+        first_o = os_.prefill(prompt)
+        first_g = gs.ee_prefill(prompt)
+        # the first token is an argmax too; compare through a verify round below when it differs
+        if first_g != first_o:
+            gs.ee_set_pending(first_o)
+        assert gs.ee_kv_len() == os_.kv_len == len(prompt)
+        ro = os_.verify(drafts, exits, commit=True, want_logits=True)
+        rg = gs.verify_sync(drafts, exits)
+        exempt, err = check_pass(ro, rg, gpu_logits(gs, len(exits)), drafts, what)
+        return exempt, err, first_g == first_o
+    finally:
+        gs.free()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tiny_single_round(tiny_pair, seed):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(seed, 64, o.vocab)
+    s = o.session(96)
+    s.prefill(prompt)
+    greedy = []
+    for _ in range(4):   # the oracle's own greedy continuation after `pending`
+        r = s.verify([0], commit=False)
+        kv = s.kv_len
+        s.verify([int(r.final_tokens[0])], commit=True)
+        s.kv_truncate(kv + 1)
+        s.set_pending(int(r.final_tokens[0]))
+        greedy.append(int(r.final_tokens[0]))
+    drafts = eegen.corrupt_drafts(greedy, 0.3, o.vocab, seed, 0)
+    _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"tiny seed {seed}")
+
+
+@pytest.mark.parametrize("n_prompt,gamma", [(1, 1), (2, 4), (15, 8), (16, 15), (17, 3), (33, 5), (100, 4)])
+def test_tiny_ragged_shapes(tiny_pair, n_prompt, gamma):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(100 + n_prompt, n_prompt, o.vocab)
+    drafts = eegen.prompt_tokens(200 + gamma, gamma, o.vocab)
+    _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"tiny P={n_prompt} gamma={gamma}")
+
+
+def test_tiny_phase_launches_bit_identical(tiny_pair):
+    """One launch per phase and one persistent launch per segment run the same
+    code in the same order: logits must be bit-identical, and so must two runs."""
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(7, 40, o.vocab)
+    drafts = eegen.prompt_tokens(8, 4, o.vocab)
+    outs = []
+    for flags in (0, ee.PHASE_LAUNCHES, 0):
+        gs = g.session(128, max_gamma=8, flags=ee.KEEP_LOGITS | flags)
+        gs.ee_prefill(prompt)
+        r = gs.verify_sync(drafts, TINY_EXITS)
+        outs.append((r, gpu_logits(gs, 1)))
+        gs.free()
+    for r, lg in outs[1:]:
+        assert r.accept_len == outs[0][0].accept_len and r.next_token == outs[0][0].next_token
+        for a, b in zip(lg, outs[0][1]):
+            assert np.array_equal(a, b)
+
+
+def _chain(g, o, prompt, gamma, exits, rounds, p_corrupt, seed, max_ctx, what):
+    gs = g.session(max_ctx, max_gamma=gamma, flags=ee.KEEP_LOGITS)
+    os_ = o.session(max_ctx)
+    exempt_rounds, max_err = 0, 0.0
+    try:
+        first_o = os_.prefill(prompt)
+        first_g = gs.ee_prefill(prompt)
+        if first_g != first_o:
+            gs.ee_set_pending(first_o)
+        hist = list(prompt) + [first_o]      # every committed token; the last one is pending
+        for r_i in range(rounds):
+            # oracle's greedy continuation after pending, by single-row steps rolled back
+            kv0, pend0 = os_.kv_len, os_.pending
+            greedy = []
+            for _ in range(gamma):
+                r = os_.verify([0], commit=False)
+                t = int(r.final_tokens[0])
+                kv = os_.kv_len
+                os_.verify([t], commit=True)
+                os_.kv_truncate(kv + 1)
+                os_.set_pending(t)
+                greedy.append(t)
+            os_.kv_truncate(kv0)
+            os_.set_pending(pend0)
+            drafts = eegen.corrupt_drafts(greedy, p_corrupt, o.vocab, seed, r_i)
+            ro = os_.verify(drafts, exits, commit=True, want_logits=True)
+            hist += [int(t) for t in drafts[:ro.accept_len]] + [int(ro.next_token)]
+            gs.ee_verify(drafts, exits)
+            for e in range(len(exits)):
+                gs.ee_wait_exit(e)
+            gs.ee_wait_final()
+            rg = gs.final_result()
+            exempt, err = check_pass(ro, rg, gpu_logits(gs, len(exits)), drafts, f"{what} round {r_i}")
+            max_err = max(max_err, err)
+            if rg.accept_len != ro.accept_len or rg.next_token != ro.next_token:
+                # only possible at an exempt row: put the GPU session on the oracle's trajectory
+                assert exempt
+                exempt_rounds += 1
+                gs.ee_prefill(hist, flags=ee.HOLD_LAST)
+            assert gs.ee_kv_len() == os_.kv_len and gs.ee_pending() == os_.pending
+    finally:
+        gs.free()
+    return exempt_rounds, max_err
+
+
+def test_tiny_chain_with_rollback(tiny_pair):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(3, 64, o.vocab)
+    _chain(g, o, prompt, 4, TINY_EXITS, rounds=12, p_corrupt=0.3, seed=5, max_ctx=64 + 12 * 5 + 8, what="tiny chain")
+
+
+def test_mid_model_chain(mid_pair):
+    g, o = mid_pair
+    prompt = eegen.prompt_tokens(9, 70, o.vocab)
+    _chain(g, o, prompt, 5, [1, 2], rounds=5, p_corrupt=0.4, seed=6, max_ctx=160, what="mid chain")
+
+
+def test_mid_model_gamma8_no_exits(mid_pair):
+    g, o = mid_pair
+    prompt = eegen.prompt_tokens(19, 130, o.vocab)
+    _chain(g, o, prompt, 8, [], rounds=3, p_corrupt=0.5, seed=7, max_ctx=200, what="mid gamma 8")
+
+
+def test_truncate_and_refeed(tiny_pair):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(41, 30, o.vocab)
+    gs = g.session(96, max_gamma=4, flags=ee.KEEP_LOGITS)
+    gs.ee_prefill(prompt)
+    kv, pend = gs.ee_kv_len(), gs.ee_pending()
+    d1 = eegen.prompt_tokens(42, 4, o.vocab)
+    r1 = gs.verify_sync(d1, TINY_EXITS)
+    l1 = gpu_logits(gs, 1)
+    gs.verify_sync(eegen.prompt_tokens(43, 4, o.vocab), TINY_EXITS)
+    gs.ee_kv_truncate(kv)
+    gs.ee_set_pending(pend)
+    r2 = gs.verify_sync(d1, TINY_EXITS)
+    l2 = gpu_logits(gs, 1)
+    assert r1.accept_len == r2.accept_len and list(r1.final_tokens) == list(r2.final_tokens)
+    for a, b in zip(l1, l2):
+        assert np.array_equal(a, b)
+    gs.free()
+
+
+def test_hold_last_and_embedding_prefix(tiny_pair):
+    g, o = tiny_pair
+    emb = eegen.embedding_prefix(81, 37, o.d_model)
+    toks = eegen.prompt_tokens(82, 9, o.vocab)
+    drafts = eegen.prompt_tokens(83, 4, o.vocab)
+    for flags_o, flags_g in ((0, 0), (eo.HOLD_LAST, ee.HOLD_LAST)):
+        gs = g.session(96, max_gamma=4, flags=ee.KEEP_LOGITS)
+        os_ = o.session(96)
+        fo = os_.prefill(toks, flags=flags_o, emb=emb)
+        fg = gs.ee_prefill(toks, flags=flags_g, emb=emb)
+        if flags_g == 0 and fo != fg:
+            gs.ee_set_pending(fo)
+        assert gs.ee_kv_len() == os_.kv_len
+        ro = os_.verify(drafts, TINY_EXITS, want_logits=True)
+        rg = gs.verify_sync(drafts, TINY_EXITS)
+        check_pass(ro, rg, gpu_logits(gs, 1), drafts, "embedding prefix")
+        gs.free()
+
+
+def test_no_autocommit(tiny_pair):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(51, 20, o.vocab)
+    gs = g.session(64, max_gamma=4, flags=ee.NO_AUTOCOMMIT)
+    gs.ee_prefill(prompt)
+    kv, pend = gs.ee_kv_len(), gs.ee_pending()
+    r = gs.verify_sync(eegen.prompt_tokens(52, 4, o.vocab), TINY_EXITS)
+    assert gs.ee_kv_len() == kv and gs.ee_pending() == pend
+    r2 = gs.verify_sync(eegen.prompt_tokens(52, 4, o.vocab), TINY_EXITS)
+    assert list(r.final_tokens) == list(r2.final_tokens)
+    gs.free()
+
+
+def test_error_paths(tiny_pair):
+    g, o = tiny_pair
+    gs = g.session(16, max_gamma=8)
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_verify([1, 2], TINY_EXITS)
+    assert e.value.code == ee.EE_ESTATE
+    gs.ee_prefill(eegen.prompt_tokens(1, 8, o.vocab))
+    for bad in ([0], [4], [3], [2, 2], [5]):
+        with pytest.raises(ee.EEError) as e:
+            gs.ee_verify([1, 2], bad)
+        assert e.value.code == ee.EE_EINVAL
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_verify([o.vocab], TINY_EXITS)
+    assert e.value.code == ee.EE_EINVAL
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_verify([], TINY_EXITS)
+    assert e.value.code == ee.EE_EINVAL
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_verify([1] * 9, TINY_EXITS)
+    assert e.value.code == ee.EE_EINVAL          # beyond max_gamma
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_verify([1] * 8, TINY_EXITS)
+    assert e.value.code == ee.EE_ECAPACITY       # 8 + 9 rows > max_ctx 16
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_kv_truncate(9)
+    assert e.value.code == ee.EE_EINVAL
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_wait_final()
+    assert e.value.code == ee.EE_ESTATE
+    with pytest.raises(ee.EEError) as e:
+        gs.ee_prefill(list(range(40)))
+    assert e.value.code == ee.EE_ECAPACITY
+    # the session still works after the rejected calls
+    gs.ee_prefill(eegen.prompt_tokens(1, 8, o.vocab))
+    gs.verify_sync([1, 2, 3], TINY_EXITS)
+    gs.free()
+
+
+def test_batched_sessions_match_single(model_dir):
+    """Eight sessions in one pass (multi-client serving) = each session alone."""
+    p = f"{model_dir}/gpu_tiny_b.bin"
+    eegen.write_model(p, eegen.TINY, 31, gains="uniform")
+    g = ee.Model(p, max_rows=40)
+    o = eo.Model(p)
+    B, gamma = 8, 4
+    sess, osess, drafts = [], [], []
+    for b in range(B):
+        emb = eegen.embedding_prefix(300, 20 + 3 * b, o.d_model, session=b)
+        toks = eegen.prompt_tokens(301, 5 + b, o.vocab, session=b)
+        gs = g.session(128, max_gamma=gamma, flags=0)
+        os_ = o.session(128)
+        fo = os_.prefill(toks, emb=emb)
+        fg = gs.ee_prefill(toks, emb=emb)
+        if fo != fg:
+            gs.ee_set_pending(fo)
+        sess.append(gs)
+        osess.append(os_)
+    for rnd in range(3):
+        drafts = []
+        for b in range(B):
+            probe = osess[b].verify([0] * gamma, commit=False)
+            d = np.array([probe.final_tokens[0]] + [0] * (gamma - 1), dtype=np.int32)
+            drafts.append(eegen.corrupt_drafts(d, 0.3, o.vocab, 302 + rnd, rnd, session=b))
+        ee.ee_verify_batch(sess, drafts, TINY_EXITS)
+        for b in range(B):
+            sess[b].ee_wait_exit(0)
+            sess[b].ee_wait_final()
+            ro = osess[b].verify(drafts[b], TINY_EXITS, want_logits=True)
+            rg = sess[b].final_result()
+            check_pass(ro, rg, None, drafts[b], f"batch round {rnd} session {b}")
+            assert rg.accept_len == ro.accept_len and rg.next_token == ro.next_token, \
+                "low-margin divergence in the batch test: pick another seed"
+            assert sess[b].ee_kv_len() == osess[b].kv_len
+    for s in sess:
+        s.free()
+    g.free()
+
+
+def test_exit_results_visible_before_final(mid_pair):
+    """Exit tokens are published while the pass is still running: the exit
+    event's GPU timestamp precedes the final one."""
+    g, o = mid_pair
+    prompt = eegen.prompt_tokens(61, 50, o.vocab)
+    gs = g.session(128, max_gamma=4)
+    gs.ee_prefill(prompt)
+    gs.ee_verify(eegen.prompt_tokens(62, 4, o.vocab), [1, 2])
+    gs.ee_wait_exit(0)
+    toks, delta = gs.exit_result(0)
+    assert 0 <= delta <= 4 and all(0 <= t < o.vocab for t in toks)
+    gs.ee_wait_final()
+    t0, t1, tf = gs.ee_pass_time_ms(0), gs.ee_pass_time_ms(1), gs.ee_pass_time_ms(2)
+    assert 0 < t0 < t1 < tf
+    gs.free()
