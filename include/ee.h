@@ -169,6 +169,10 @@ int ee_debug_logits(ee_session *s, int head_idx, float *out);
 /* hipDeviceSynchronize on `device`: every pass enqueued so far has finished. */
 int ee_device_synchronize(int device);
 
+/* Measurement aid: `launches` launches of the pass kernel that execute `barriers`
+   grid-wide barriers each and nothing else; mean microseconds per launch. */
+int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch);
+
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
    kernels assume and compares with the plain 16x32 . 32x16 product. */
 int ee_debug_mfma_layout(int device);

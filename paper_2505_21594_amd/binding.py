@@ -33,7 +33,7 @@ EXPORTS = [
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
-    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize",
+    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost",
 ]
 
 
@@ -102,6 +102,7 @@ def load_library():
     lib.ee_debug_logits.argtypes = [vp, ci, vp]
     lib.ee_debug_mfma_layout.argtypes = [ci]
     lib.ee_device_synchronize.argtypes = [ci]
+    lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
     for name in EXPORTS:
         if name != "ee_last_error":
             getattr(lib, name).restype = ci
@@ -238,6 +239,11 @@ class Session:
         out = np.empty((self._gamma + 1, self.model.vocab), dtype=np.float32)
         _check(self._l.ee_debug_logits(self._h, head_idx, out.ctypes.data))
         return out
+
+    def ee_debug_launch_cost(self, launches: int, barriers: int) -> float:
+        us = ctypes.c_float()
+        _check(self._l.ee_debug_launch_cost(self._h, launches, barriers, ctypes.byref(us)))
+        return float(us.value)
 
     # plain reads of the pinned result block (no computation)
     def exit_result(self, exit_idx: int):

@@ -975,6 +975,39 @@ extern "C" int ee_debug_logits(ee_session *s, int head_idx, float *out)
     return EE_OK;
 }
 
+// Measurement aid: launches the segment kernel `launches` times with `barriers`
+// grid barriers each and no other work; returns the mean time per launch.
+extern "C" int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch)
+{
+    if (!s || !us_per_launch || launches < 1 || barriers < 0) return fail(EE_EINVAL, "bad argument");
+    const ee_model *m = s->m;
+    HIP_TRY(hipSetDevice(m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    PassArgs a;
+    base_args(s, a);
+    a.mode = 2;
+    a.layer_end = barriers;
+    a.sess = s->dev_sessdev;
+    void *params[] = {&a};
+    HIP_TRY(hipStreamSynchronize(s->stream));
+    HIP_TRY(hipEventRecord(s->ev_start, s->stream));
+    for (int i = 0; i < launches; ++i) {
+        if (barriers > 0)
+            HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(ee_segment_kernel), dim3(m->nwg),
+                                               dim3(WG_THREADS), params, (unsigned)m->lds_budget, s->stream));
+        else
+            hipLaunchKernelGGL(ee_segment_kernel, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, s->stream, a);
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipEventRecord(s->ev_final, s->stream));
+    HIP_TRY(hipEventSynchronize(s->ev_final));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, s->ev_start, s->ev_final));
+    *us_per_launch = ms * 1000.f / (float)launches;
+    return EE_OK;
+}
+
 extern "C" int ee_device_synchronize(int device)
 {
     HIP_TRY(hipSetDevice(device));
