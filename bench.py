@@ -123,7 +123,7 @@ def main():
     path = model_file(cfg, args.workload.split("_")[0], args.seed, pick_workdir())
 
     t = time.time()
-    model = ee.Model(path, device=0, max_rows=16)
+    model = ee.Model(path, device=0, max_rows=M)
     print(f"[bench] model on GPU in {time.time() - t:.1f}s, {model.n_workgroups} workgroups", file=sys.stderr, flush=True)
     rounds = W + K
     max_ctx = n_prompt + rounds * M + 2 * M + 16

@@ -8,46 +8,54 @@
 
 namespace ee {
 
-constexpr int WAVES_PER_WG = 8;          // 512 threads: two waves per SIMD
-constexpr int WG_THREADS = WAVES_PER_WG * 64;
+constexpr int WAVES = 16;                // waves per workgroup: four per SIMD keeps HBM busy
+constexpr int WG_THREADS = WAVES * 64;
+constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
 constexpr int KV_PAGE = 16;              // positions per KV page
-constexpr int ATT_ROWS = 8;              // query rows handled together in attention
+constexpr int ATT_ROWS = 4;              // query rows handled together in attention
 constexpr int ATT_MAX_SPLITS = 32;
 
-// Tiled layout of one weight matrix W[N][K] (row-major in the model file).
+// Weight layout of one GEMM y = x . W^T, W[N][K] row-major in the model file.
+//
 // A tile is the A operand of one v_mfma_f32_16x16x32_bf16: 16 rows of N by 32
 // columns of K, stored as 64 lanes x 16 bytes, lane l holding
-// W[nt*16 + (l & 15)][kt*32 + (l >> 4)*8 .. +7].  Tiles are ordered
-// [K-block][n-tile][k-tile inside the block]; a "run" is the KBT (or KBT_last)
-// consecutive tiles of one (K-block, n-tile).  Wave w of NW streams the
-// contiguous tile range [T*w/NW, T*(w+1)/NW) and emits one partial 16 x rows
-// result per run it touches.
+// W[nt*16 + (l & 15)][kt*32 + (l >> 4)*8 .. +7]  (1 KB per tile).
+//
+// The N axis is cut into units of `tpu` n-tiles (1, or 2 for a gate/up pair);
+// workgroup g owns the units [U*g/nwg, U*(g+1)/nwg) for the whole of K, so every
+// output element is complete inside one workgroup.  The tiles of a workgroup
+// are stored contiguously in the order it streams them:
+//   for group (GRP n-tiles) : for K-block kb : for n-tile in group : for k-tile in block
+// where K-block kb covers the k-tiles [KT*kb/nKB, KT*(kb+1)/nKB).  Inside one
+// (K-block, n-tile) run of klen tiles, wave w takes [klen*w/16, klen*(w+1)/16).
 struct GemmPlan {
-    int N, K;            // logical shape
-    int NT, KT;          // tiles along N and K (zero padded)
-    int KBT;             // k-tiles per full K-block
-    int nKB;             // number of K-blocks
-    int KBT_last;        // k-tiles in the last K-block
-    int MAXP;            // most waves that share one run
-    long long T;         // NT * KT
-    float *part;         // partial results [nKB*NT runs][MAXP][rows_max][16]
+    int N, K;        // logical shape (N counts rows after concatenation / interleaving)
+    int NT, KT;      // tiles along N and K (K zero-padded to 32)
+    int tpu;         // n-tiles per unit
+    int U;           // units = NT / tpu
+    int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
+    int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
+    int xs_stride;   // bf16 elements per staged row of x_hat
+    int pad_;
 };
 
-struct LayerDev {
-    const uint4 *wqkv, *wo, *wgu, *wd;   // tiled weights
-    const float *g_attn, *g_ffn;         // norm gains
-};
+enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };
+enum GemmKind { G_QKV = 0, G_O = 1, G_GU = 2, G_DN = 3, G_HEAD = 4 };
+enum StageType { ST_EMBED = 0, ST_GEMM = 1, ST_ATT = 2, ST_MERGE = 3, ST_ACCEPT = 4, ST_NONE = 5 };
 
 struct ModelDev {
     int L, d, H, hd, F, V;
     float eps, att_scale;
     int Kpad_d, Kpad_F;                  // K rounded up to 32
     int rows_max;
-    GemmPlan qkv, o, gu, dn, head;
-    const uint16_t *emb;                 // [V][d] bf16, row-major
-    const uint4 *wlm;                    // tiled LM head
+    int lds_slots_off, lds_zbuf_off, lds_misc_off;  // byte offsets inside the dynamic LDS block
+    GemmPlan plan[5];                    // indexed by GemmKind: QKV, O, GU, DN, HEAD
+    // tiled weights: one allocation per GEMM kind, layer l at w[kind] + l * wstride[kind] (uint4 units)
+    const uint4 *w[5];
+    long long wstride[5];
+    const float *g_attn, *g_ffn;         // [L][d]
     const float *g_final;
-    const LayerDev *layers;
+    const uint16_t *emb;                 // [V][d] bf16, row-major
 };
 
 struct SessDev {
@@ -61,35 +69,26 @@ struct SessDev {
     int pad_;
 };
 
-struct GridBarrier {
-    unsigned count;
-    unsigned gen;
-};
-
 struct Scratch {
     float *h;            // [rows_max][d]        residual stream
-    float *q;            // [rows_max][d]        queries after RoPE
-    float *xn;           // [rows_max][Kpad_d]   gain-scaled hidden state, next GEMM input
-    float *xh;           // [rows_max][Kpad_d]   same with the head's gain
+    float *q;            // [rows_max][d]        queries after RoPE (pair-interleaved inside each head)
     float *attn;         // [rows_max][Kpad_d]   attention output
     float *u;            // [rows_max][Kpad_F]   silu(gate)*up
-    float *ss_a;         // [nwg][rows_max]      partial sums of h^2 after the FFN block / embedding
-    float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
-    float *att_part;     // attention partials
+    float *att_part;     // attention partials (only when the position range is split)
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
-    GridBarrier *bar;
+    unsigned *bar_flags; // [nwg]                grid barrier: last epoch each workgroup arrived at
     int *err;            // set to 1 when a bounded wait gave up
 };
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
 struct PassArgs {
-    const ModelDev *md;
+    const ModelDev *md;                  // device copy of the model descriptor
     Scratch sc;
     int nwg;
     int n_sess, M, rows;                 // rows = n_sess * M
-    int mode;                            // 0 verify, 1 prefill chunk
+    int mode;                            // 0 verify, 1 prefill chunk, 2 barrier measurement
     const int *pf_tokens;                // prefill: [rows] token ids, < 0 => embedding row
     const uint16_t *pf_emb;              // prefill: [rows][d] bf16
     int pf_pos0;                         // prefill: position of row 0
@@ -99,8 +98,9 @@ struct PassArgs {
     const float *head_gain;
     int commit, keep_logits;
     int att_splits;
-    int ph_lo, ph_hi;                    // window of this launch inside the segment's phase list
+    int ph_lo, ph_hi;                    // stages [ph_lo, ph_hi) of the segment's stage list run in this launch
     unsigned spin_limit;
+    unsigned epoch_base;                 // barrier epoch before this launch
     const SessDev *sess;                 // device array [n_sess]
 };
 

@@ -1,30 +1,27 @@
 // gfx950 kernels of the verification pass.
 //
 // One persistent kernel runs a whole segment of the pass (embedding, a range of
-// layers, optionally an LM head with its accept step) as a list of phases with
-// a grid-wide barrier between consecutive phases.  "P" phases stream weights or
-// the KV cache (HBM-bound), "R" phases reduce partial results and apply the
-// element-wise epilogues (latency-bound, tiny).
+// layers, optionally an LM head with its accept step) as a list of stages with
+// a grid-wide barrier between consecutive stages.  Per layer (Eq. 3 of the
+// paper, f = Llama-2 block) there are five stages:
+//   QKV   x_hat . [Wq;Wk;Wv]^T, * rstd, RoPE, q -> scratch, k/v -> paged bf16 cache
+//   ATT   causal attention of the new rows over the cache         -> attn
+//   O     h += attn . Wo^T
+//   GU    u = silu(rstd * x_hat.Wg^T) * (rstd * x_hat.Wu^T)
+//   DN    h += u . Wd^T
+// (plus a merge stage after ATT when the position range is split over
+// workgroups).  Head (z^(l) = LMHead(h^(l)); accept rule of Eq. 2 / Eq. 5):
+//   HEAD    x_hat . W_lm^T, * rstd, argmax candidate per workgroup
+//   ACCEPT  global argmax (lowest id wins ties), accept length, publication to
+//           pinned host memory, KV commit.
 //
-// Per layer (Eq. 3 of the paper, f = Llama-2 block):
-//   P_QKV  x_hat . [Wq;Wk;Wv]^T                       -> partials
-//   R_QKV  reduce, * rstd, RoPE, q -> scratch, k/v -> paged bf16 cache
-//   P_ATT  causal attention of the new rows over the cache, split over positions
-//   R_ATT  merge the splits                            -> attn
-//   P_O    attn . Wo^T                                 -> partials
-//   R_O    h += ., sum of squares, x_hat = g_ffn * h   -> xn
-//   P_GU   x_hat . [Wg;Wu]^T                           -> partials
-//   R_GU   silu(rstd*gate) * (rstd*up)                 -> u
-//   P_DN   u . Wd^T                                    -> partials
-//   R_DN   h += ., sum of squares, x_hat for the next layer and/or the head
-// Head (z^(l) = LMHead(h^(l)); accept rule of Eq. 2 / Eq. 5):
-//   P_HEAD x_hat . W_lm^T -> partials; R_HEAD reduce, * rstd, per-workgroup
-//   argmax; R_ACCEPT global argmax (lowest id wins ties), accept length,
-//   publication to pinned host memory, KV commit.
-//
-// RMSNorm is split: the GEMM input is g * h; the row factor
-// rstd = 1/sqrt(mean(h^2)+eps) is applied to the fp32 GEMM result, which is
-// the same product because rstd is constant along K.
+// Every GEMM stage streams the weights once (HBM-bound).  A workgroup owns whole
+// n-tiles for the full K, so its outputs are complete after a cross-wave sum in
+// LDS and the element-wise epilogue runs in the same stage.  RMSNorm is split:
+// the GEMM input is g * h, the row factor rstd = 1/sqrt(mean(h^2)+eps) (computed
+// by every workgroup while it stages h) multiplies the fp32 result.
+// Each wave fetches the first weight tiles of its next GEMM stage before it
+// enters the barrier, so HBM stays busy while the grid synchronises.
 #pragma once
 
 #include "ee_device.hpp"
@@ -34,6 +31,8 @@ namespace ee {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+
+constexpr int D = PF_DEPTH;
 
 // 16-byte streaming load (weights are read once per pass: no reuse in cache)
 __device__ __forceinline__ uint4 load_stream16(const uint4 *p)
@@ -45,11 +44,11 @@ __device__ __forceinline__ uint4 load_stream16(const uint4 *p)
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 // round to nearest even; inputs are finite
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
 {
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return u >> 16;
 }
 
 __device__ __forceinline__ void unpack8(const uint4 &v, float *f)
@@ -66,28 +65,33 @@ __device__ __forceinline__ void unpack8(const uint4 &v, float *f)
 
 // ------------------------------------------------------------------ grid barrier
 
-// Sense-reversing barrier over all workgroups of a cooperative launch.  The
-// wait is bounded: after spin_limit polls the workgroup raises *err and goes
-// on, and every later barrier falls through, so the grid always drains.
-__device__ __forceinline__ void grid_barrier(GridBarrier *b, unsigned nwg, int *err, unsigned spin_limit)
+// Every workgroup publishes the epoch it has reached in its own flag and waits
+// until all flags have reached it.  The wait is bounded: after spin_limit polls
+// the workgroup raises *err and goes on, and later barriers fall through at once,
+// so the grid always drains.
+__device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsigned epoch, int *err,
+                                             unsigned spin_limit)
 {
     __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned gen = __hip_atomic_load(&b->gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x < 64) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-        unsigned prev = __hip_atomic_fetch_add(&b->count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (prev == nwg - 1) {
-            __hip_atomic_store(&b->count, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&b->gen, gen + 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-        } else {
-            unsigned spins = 0;
-            while (__hip_atomic_load(&b->gen, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gen) {
-                if (__hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
-                if (++spins > spin_limit) {
-                    __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(2);
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&flags[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        while (true) {
+            bool ok = true;
+            for (unsigned i = threadIdx.x; i < nwg; i += 64) {
+                unsigned f = __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = ok && ((int)(f - epoch) >= 0);
+            }
+            if (__all(ok)) break;
+            ++spins;
+            if ((spins & 63u) == 0 &&
+                __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+                break;
+            if (spins > spin_limit) {
+                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
             }
         }
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
@@ -111,300 +115,484 @@ __device__ __forceinline__ int row_token(const PassArgs &a, int r)
     return i == 0 ? a.sess[s].state[1] : a.sess[s].drafts[i - 1];
 }
 
-// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order
-__device__ __forceinline__ void load_rstd(const float *ss, int nwg, int rows_max, int rows, int d, float eps,
-                                          float *rstd_lds)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int m = wave; m < rows; m += WAVES_PER_WG) {
-        float s = 0.f;
-        for (int g = lane; g < nwg; g += 64) s += ss[(size_t)g * rows_max + m];
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-        if (lane == 0) rstd_lds[m] = 1.0f / sqrtf(s / (float)d + eps);
-    }
-    __syncthreads();
-}
+// ------------------------------------------------------------------ LDS map
 
-// ------------------------------------------------------------------ tile index arithmetic
-
-struct TilePos {
-    int kb, nt, kti, klen;
+struct Misc {  // views into the misc region of the LDS block
+    float *rstd;       // [rows_max]
+    float *ssq;        // [rows_max][WAVES]
+    int *pos;          // [rows_max]
+    long long *kvoff;  // [rows_max]  element offset of (layer, page, slot, head 0) in the KV pools
+    float2 *rope;      // [rows_max][hd/2]
+    float *bestv;      // [rows_max]
+    int *besti;        // [rows_max]
 };
 
-__device__ __forceinline__ TilePos tile_decode(const GemmPlan &pl, long long t)
+__device__ __forceinline__ Misc misc_views(const ModelDev &md, char *lds)
 {
-    TilePos p;
-    const long long B = (long long)pl.NT * pl.KBT;
-    const long long full = (long long)(pl.nKB - 1) * B;
-    if (t < full) {
-        p.kb = (int)(t / B);
-        int rem = (int)(t - (long long)p.kb * B);
-        p.nt = rem / pl.KBT;
-        p.kti = rem - p.nt * pl.KBT;
-        p.klen = pl.KBT;
-    } else {
-        p.kb = pl.nKB - 1;
-        int rem = (int)(t - full);
-        p.nt = rem / pl.KBT_last;
-        p.kti = rem - p.nt * pl.KBT_last;
-        p.klen = pl.KBT_last;
-    }
-    return p;
+    Misc m;
+    char *p = lds + md.lds_misc_off;
+    const int R = md.rows_max;
+    m.kvoff = reinterpret_cast<long long *>(p);
+    p += (size_t)R * 8;
+    m.rope = reinterpret_cast<float2 *>(p);
+    p += (size_t)R * (md.hd / 2) * 8;
+    m.rstd = reinterpret_cast<float *>(p);
+    p += (size_t)R * 4;
+    m.ssq = reinterpret_cast<float *>(p);
+    p += (size_t)R * WAVES * 4;
+    m.pos = reinterpret_cast<int *>(p);
+    p += (size_t)R * 4;
+    m.bestv = reinterpret_cast<float *>(p);
+    p += (size_t)R * 4;
+    m.besti = reinterpret_cast<int *>(p);
+    return m;
 }
 
-// wave that streams tile t: the w with floor(T*w/NW) <= t < floor(T*(w+1)/NW)
-__device__ __forceinline__ int tile_owner(long long T, int NW, long long t)
+// ------------------------------------------------------------------ weight-stream geometry
+
+struct Seg {  // one (group, K-block) of a workgroup's tile sequence, seen from one wave
+    int gn;           // n-tiles in the group
+    int klen, kst;    // k-tiles of the block, first k-tile
+    int s0, slen;     // this wave's slice of every run: [s0, s0 + slen)
+    int n;            // tiles of this wave in the segment = gn * slen
+    long long base;   // tile index of the segment's first tile
+};
+
+__device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int &nt0, int &n_local)
 {
-    return (int)(((t + 1) * (long long)NW - 1) / T);
+    int u0 = (int)((long long)pl.U * g / nwg), u1 = (int)((long long)pl.U * (g + 1) / nwg);
+    nt0 = u0 * pl.tpu;
+    n_local = (u1 - u0) * pl.tpu;
 }
 
-// ------------------------------------------------------------------ P: weight-streaming GEMM
-
-// partial[run][piece][m][16] = W_tile(16 x 32) . x_hat^T(32 x rows) summed over the tiles of
-// the run that fall into this wave's range.  x: fp32 [rows][ldx], already scaled by the norm
-// gain.  The MFMA takes bf16 operands; x is fed as two bf16 terms, hi = bf16(x) and
-// lo = bf16(x - hi), so that the activations keep about 16 mantissa bits (the weights are
-// exact bf16 values).  The matrix cores are idle most of the time in this HBM-bound loop,
-// so the second MFMA per tile is free.
-template <int MT>
-__device__ void gemm_phase(const GemmPlan &pl, const uint4 *__restrict__ W, const float *__restrict__ x,
-                           int ldx, int rows, int rows_max, int nwg, char *lds)
+__device__ __forceinline__ Seg seg_setup(const GemmPlan &pl, int nt0, int n_local, int wave, int gi, int kb)
 {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int NW = nwg * WAVES_PER_WG;
-    const long long T = pl.T;
-    const int w0 = blockIdx.x * WAVES_PER_WG;
-    const long long g0 = T * w0 / NW, g1 = T * (w0 + WAVES_PER_WG) / NW;
-    if (g0 >= g1) return;  // uniform over the workgroup
-
-    const int kb_lo = tile_decode(pl, g0).kb, kb_hi = tile_decode(pl, g1 - 1).kb;
-    const int xs_stride = pl.KBT * 32 + 8;                  // bf16 elements per staged row
-    uint16_t *xs_hi = reinterpret_cast<uint16_t *>(lds);    // [rows][xs_stride]
-    uint16_t *xs_lo = xs_hi + (size_t)rows * xs_stride;
-    const long long t0 = T * (w0 + wave) / NW, t1 = T * (w0 + wave + 1) / NW;
-    const long long B = (long long)pl.NT * pl.KBT;
-
-    int brow[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * xs_stride;
-    const int bk = (lane >> 4) * 8;
-    const size_t pstride = (size_t)rows_max * 16;
-    constexpr int D = 8;  // tiles in flight per wave (8 KB)
-
-    for (int kb = kb_lo; kb <= kb_hi; ++kb) {
-        if (kb > kb_lo) __syncthreads();
-        // stage K-block kb of x_hat as hi/lo bf16
-        {
-            const int c8_per_row = pl.KBT * 4;  // 8-element chunks per row
-            const int total = rows * c8_per_row;
-            for (int i = tid; i < total; i += WG_THREADS) {
-                int row = i / c8_per_row, c = i - row * c8_per_row;
-                int k = kb * pl.KBT * 32 + c * 8;
-                uint4 hi = make_uint4(0, 0, 0, 0), lo = make_uint4(0, 0, 0, 0);
-                if (k < ldx) {
-                    const float4 *src = reinterpret_cast<const float4 *>(x + (size_t)row * ldx + k);
-                    float4 a = src[0], b = src[1];
-                    float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-                    uint32_t h[8], l[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        h[e] = f32_to_bf16(f[e]);
-                        l[e] = f32_to_bf16(f[e] - bf16_to_f32((uint16_t)h[e]));
-                    }
-                    hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-                    lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-                }
-                *reinterpret_cast<uint4 *>(xs_hi + (size_t)row * xs_stride + c * 8) = hi;
-                *reinterpret_cast<uint4 *>(xs_lo + (size_t)row * xs_stride + c * 8) = lo;
-            }
-        }
-        __syncthreads();
-
-        // this wave's tiles inside K-block kb
-        const int klen = (kb == pl.nKB - 1) ? pl.KBT_last : pl.KBT;
-        const long long blk_start = (long long)kb * B, blk_end = blk_start + (long long)pl.NT * klen;
-        const long long ta = t0 > blk_start ? t0 : blk_start, tb = t1 < blk_end ? t1 : blk_end;
-        if (ta >= tb) continue;
-        const int n = (int)(tb - ta);
-        int rem = (int)(ta - blk_start);
-        int nt = rem / klen, kti = rem - nt * klen;
-        // the first run may have been begun by earlier waves
-        int piece = (w0 + wave) - tile_owner(T, NW, blk_start + (long long)nt * klen);
-
-        f32x4_t acc[MT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-
-        const uint4 *wp = W + (size_t)ta * 64 + lane;
-        uint4 buf[D];
-#pragma unroll
-        for (int j = 0; j < D; ++j)
-            if (j < n) buf[j] = load_stream16(wp + (size_t)j * 64);
-
-        for (int i = 0; i < n; i += D) {
-#pragma unroll
-            for (int j = 0; j < D; ++j) {
-                if (i + j < n) {
-                    uint4 av = buf[j];
-                    if (i + j + D < n) buf[j] = load_stream16(wp + (size_t)(i + j + D) * 64);
-                    bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
-                    const int xo = kti * 32 + bk;
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        uint4 bh = *reinterpret_cast<const uint4 *>(xs_hi + brow[mt] + xo);
-                        uint4 bl = *reinterpret_cast<const uint4 *>(xs_lo + brow[mt] + xo);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
-                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
-                    }
-                    ++kti;
-                    if (kti == klen || i + j + 1 == n) {
-                        // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
-                        float *dst = pl.part + ((size_t)(kb * pl.NT + nt) * pl.MAXP + piece) * pstride;
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) {
-                            int m = mt * 16 + (lane & 15);
-                            if (m < rows)
-                                *reinterpret_cast<float4 *>(dst + (size_t)m * 16 + (lane >> 4) * 4) =
-                                    make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
-                            acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-                        }
-                        piece = 0;
-                        if (kti == klen) {
-                            kti = 0;
-                            ++nt;
-                        }
-                    }
-                }
-            }
-        }
-    }
-}
-
-__device__ __forceinline__ void gemm_dispatch(const GemmPlan &pl, const uint4 *W, const float *x, int ldx,
-                                              int rows, int rows_max, int nwg, char *lds)
-{
-    if (rows <= 16)
-        gemm_phase<1>(pl, W, x, ldx, rows, rows_max, nwg, lds);
-    else if (rows <= 32)
-        gemm_phase<2>(pl, W, x, ldx, rows, rows_max, nwg, lds);
-    else
-        gemm_phase<3>(pl, W, x, ldx, rows, rows_max, nwg, lds);
-}
-
-// sum of all partials of output (m, n), fixed order (K-block, then piece)
-__device__ __forceinline__ float reduce_out(const GemmPlan &pl, int rows_max, int m, int n)
-{
-    const size_t pstride = (size_t)rows_max * 16;
-    const float *p = pl.part + ((size_t)(n >> 4) * pl.MAXP) * pstride + (size_t)m * 16 + (n & 15);
-    const size_t kb_stride = (size_t)pl.NT * pl.MAXP * pstride;
-    float s = 0.f;
-    for (int kb = 0; kb < pl.nKB; ++kb) {
-        for (int pc = 0; pc < pl.MAXP; ++pc) s += p[(size_t)pc * pstride];
-        p += kb_stride;
-    }
+    Seg s;
+    s.gn = min(pl.GRP, n_local - gi * pl.GRP);
+    s.kst = pl.KT * kb / pl.nKB;
+    s.klen = pl.KT * (kb + 1) / pl.nKB - s.kst;
+    s.s0 = s.klen * wave / WAVES;
+    s.slen = s.klen * (wave + 1) / WAVES - s.s0;
+    s.n = s.gn * s.slen;
+    s.base = (long long)nt0 * pl.KT + (long long)gi * pl.GRP * pl.KT + (long long)s.gn * s.kst;
     return s;
 }
 
-// ------------------------------------------------------------------ R: residual stream
-
-// Columns [g*cw, (g+1)*cw) of every row belong to workgroup g.
-//   SRC 0: h = embedding of the row's token (or the supplied embedding row)
-//   SRC 1: h += reduced GEMM output of plan pl
-// Then: partial sum of squares per row -> ss[g][m]; x_hat = gain * h (bf16) for
-// up to two consumers (next layer's GEMM, LM head).
-template <int SRC>
-__device__ void resid_phase(const PassArgs &a, const GemmPlan *pl, const float *gain1, float *x1,
-                            const float *gain2, float *x2, float *ss, char *lds)
+// first min(D, s.n) tiles of the wave's sequence in segment s
+__device__ __forceinline__ void seg_prefetch(const uint4 *__restrict__ W, const Seg &s, uint4 (&pre)[D])
 {
-    const ModelDev &md = *a.md;
-    const int d = md.d, rows = a.rows, tid = threadIdx.x;
-    const int cw = (d + a.nwg - 1) / a.nwg;
-    const int n0 = blockIdx.x * cw;
-    const int ncol = max(0, min(cw, d - n0));
-    float *sq = reinterpret_cast<float *>(lds);  // [rows][cw]
-    const int items = rows * ncol;
-    for (int it = tid; it < items; it += WG_THREADS) {
-        int m = it / ncol, c = it - m * ncol, n = n0 + c;
-        float v;
-        if (SRC == 0) {
-            int tok = row_token(a, m);
-            v = tok >= 0 ? bf16_to_f32(md.emb[(size_t)tok * d + n]) : bf16_to_f32(a.pf_emb[(size_t)m * d + n]);
-        } else {
-            v = a.sc.h[(size_t)m * d + n] + reduce_out(*pl, md.rows_max, m, n);
-        }
-        a.sc.h[(size_t)m * d + n] = v;
-        sq[m * cw + c] = v * v;
-        if (x1) x1[(size_t)m * md.Kpad_d + n] = gain1[n] * v;
-        if (x2) x2[(size_t)m * md.Kpad_d + n] = gain2[n] * v;
-    }
-    __syncthreads();
-    if (tid < rows) {
-        float s = 0.f;
-        for (int c = 0; c < ncol; ++c) s += sq[tid * cw + c];
-        ss[(size_t)blockIdx.x * md.rows_max + tid] = s;
-    }
-}
-
-// ------------------------------------------------------------------ R_QKV: reduce, RoPE, cache write
-
-__device__ void rqkv_phase(const PassArgs &a, int layer, char *lds)
-{
-    const ModelDev &md = *a.md;
-    const int d = md.d, hd = md.hd, half = hd >> 1, H = md.H, rows = a.rows;
-    float *rstd = reinterpret_cast<float *>(lds);
-    load_rstd(a.sc.ss_a, a.nwg, md.rows_max, rows, d, md.eps, rstd);
-    const int per_row = 3 * (d >> 1);
-    const int items = rows * per_row;
-    const int gsz = a.nwg * WG_THREADS;
-    for (int it = blockIdx.x * WG_THREADS + threadIdx.x; it < items; it += gsz) {
-        int m = it / per_row, c = it - m * per_row;
-        int sect = c / (d >> 1);       // 0 q, 1 k, 2 v
-        int cc = c - sect * (d >> 1);
-        int s = a.mode == 1 ? 0 : m / a.M;
-        int pos = row_pos(a, m);
-        const SessDev &sd = a.sess[s];
-        float rs = rstd[m];
-        if (sect < 2) {
-            int head = cc / half, j = cc - head * half;
-            int n0 = head * hd + j, n1 = n0 + half;
-            float x0 = rs * reduce_out(md.qkv, md.rows_max, m, sect * d + n0);
-            float x1 = rs * reduce_out(md.qkv, md.rows_max, m, sect * d + n1);
-            float2 cs = sd.rope[(size_t)pos * half + j];
-            float y0 = x0 * cs.x - x1 * cs.y;
-            float y1 = x1 * cs.x + x0 * cs.y;
-            if (sect == 0) {
-                a.sc.q[(size_t)m * d + n0] = y0;
-                a.sc.q[(size_t)m * d + n1] = y1;
-            } else {
-                int page = sd.page_table[pos / KV_PAGE];
-                size_t base = ((((size_t)layer * sd.n_pages + page) * H + head) * KV_PAGE + (pos % KV_PAGE)) * hd;
-                sd.kpool[base + j] = f32_to_bf16(y0);
-                sd.kpool[base + j + half] = f32_to_bf16(y1);
+    const int lane = threadIdx.x & 63;
+    int ntg = 0, kk = 0;
+#pragma unroll
+    for (int j = 0; j < D; ++j) {
+        if (j < s.n) {
+            pre[j] = load_stream16(W + (size_t)(s.base + (long long)ntg * s.klen + s.s0 + kk) * 64 + lane);
+            if (++kk == s.slen) {
+                kk = 0;
+                ++ntg;
             }
-        } else {
-            int n0 = cc * 2;
-            int head = n0 / hd, e = n0 - head * hd;
-            float v0 = rs * reduce_out(md.qkv, md.rows_max, m, 2 * d + n0);
-            float v1 = rs * reduce_out(md.qkv, md.rows_max, m, 2 * d + n0 + 1);
-            int page = sd.page_table[pos / KV_PAGE];
-            size_t base = ((((size_t)layer * sd.n_pages + page) * H + head) * KV_PAGE + (pos % KV_PAGE)) * hd;
-            uint32_t pk = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
-            *reinterpret_cast<uint32_t *>(sd.vpool + base + e) = pk;
         }
     }
 }
 
-// ------------------------------------------------------------------ P_ATT: split attention
+struct NextGemm {  // the GEMM stage that follows in the same launch
+    const GemmPlan *pl;  // in device memory; nullptr: nothing to fetch
+    const uint4 *W;
+};
+
+__device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint4 (&pre)[D])
+{
+    if (!nx.pl) return false;
+    int nt0, n_local;
+    wg_units(*nx.pl, nwg, blockIdx.x, nt0, n_local);
+    if (n_local == 0) return true;
+    Seg s = seg_setup(*nx.pl, nt0, n_local, threadIdx.x >> 6, 0, 0);
+    seg_prefetch(nx.W, s, pre);
+    return true;
+}
+
+// ------------------------------------------------------------------ GEMM stage
+
+
+struct GemmIn {
+    const float *x;     // [rows][ldx] fp32
+    int ldx;
+    const float *gain;  // [K] or nullptr
+    bool norm;          // accumulate sum of squares of x, publish rstd
+};
+
+// Stage K-block (kst, klen) of x_hat = gain * x as two bf16 terms, hi = bf16(x_hat) and
+// lo = bf16(x_hat - hi): the activations keep about 16 mantissa bits while the MFMA takes
+// bf16 operands (weights are exact bf16).  The matrix cores idle most of the time in this
+// HBM-bound loop, so the second MFMA per tile is free.
+__device__ __forceinline__ void stage_x(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int klen,
+                                        bool first_block, bool want_ss, const Misc &mi, char *lds)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    uint16_t *xs_hi = reinterpret_cast<uint16_t *>(lds);
+    uint16_t *xs_lo = xs_hi + (size_t)rows * pl.xs_stride;
+    const int wpr = rows >= WAVES ? 1 : WAVES / rows;  // waves per row
+    const int c8 = klen * 4;                           // 8-element chunks per row in this block
+    for (int it = wave; it < rows * wpr; it += WAVES) {
+        const int row = it / wpr, part = it - row * wpr;
+        const int c_lo = c8 * part / wpr, c_hi = c8 * (part + 1) / wpr;
+        float ss = 0.f;
+        for (int c = c_lo + lane; c < c_hi; c += 64) {
+            const int k = kst * 32 + c * 8;
+            uint4 hi = make_uint4(0, 0, 0, 0), lo = make_uint4(0, 0, 0, 0);
+            if (k < pl.K) {
+                const float4 *src = reinterpret_cast<const float4 *>(in.x + (size_t)row * in.ldx + k);
+                float4 a = src[0], b = src[1];
+                float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+                if (want_ss) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
+                }
+                if (in.gain) {
+                    const float4 *gp = reinterpret_cast<const float4 *>(in.gain + k);
+                    float4 ga = gp[0], gb = gp[1];
+                    f[0] *= ga.x; f[1] *= ga.y; f[2] *= ga.z; f[3] *= ga.w;
+                    f[4] *= gb.x; f[5] *= gb.y; f[6] *= gb.z; f[7] *= gb.w;
+                }
+                uint32_t h[8], l[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    h[e] = f32_to_bf16(f[e]);
+                    l[e] = f32_to_bf16(f[e] - __uint_as_float(h[e] << 16));
+                }
+                hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+                lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+            }
+            *reinterpret_cast<uint4 *>(xs_hi + (size_t)row * pl.xs_stride + c * 8) = hi;
+            *reinterpret_cast<uint4 *>(xs_lo + (size_t)row * pl.xs_stride + c * 8) = lo;
+        }
+        if (want_ss) {
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            if (lane == 0) {
+                float *slot = mi.ssq + row * WAVES + part;
+                *slot = first_block ? ss : *slot + ss;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
+{
+    return v > bv || (v == bv && i < bi);
+}
+
+// Epilogue of one group: sum the waves' partial tiles, apply the stage's element-wise tail.
+__device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const GemmPlan &pl, int nt_first,
+                                              int gn, int rows, const Misc &mi, char *lds)
+{
+    const ModelDev &md = *a.md;
+    const float *slots = reinterpret_cast<const float *>(lds + md.lds_slots_off);
+    const int tid = threadIdx.x;
+    const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
+    if (kind == G_GU) {
+        const int items = (gn >> 1) * rows * 4;
+        for (int idx = tid; idx < items; idx += WG_THREADS) {
+            int p = idx / (rows * 4), rem = idx - p * rows * 4;
+            int m = rem >> 2, qd = rem & 3;
+            const float *sg = slots + ((size_t)(2 * p) * rows + m) * 16 + qd * 4;
+            const float *su = sg + (size_t)rows * 16;
+            float4 G = make_float4(0.f, 0.f, 0.f, 0.f), U = G;
+            for (int w = 0; w < WAVES; ++w) {
+                float4 x = *reinterpret_cast<const float4 *>(sg + w * wstride);
+                float4 y = *reinterpret_cast<const float4 *>(su + w * wstride);
+                G.x += x.x; G.y += x.y; G.z += x.z; G.w += x.w;
+                U.x += y.x; U.y += y.y; U.z += y.z; U.w += y.w;
+            }
+            const float rs = mi.rstd[m];
+            float g[4] = {G.x * rs, G.y * rs, G.z * rs, G.w * rs}, u[4] = {U.x * rs, U.y * rs, U.z * rs, U.w * rs};
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + __expf(-g[e])) * u[e];
+            const int f = ((nt_first >> 1) + p) * 16 + qd * 4;
+            *reinterpret_cast<float4 *>(a.sc.u + (size_t)m * md.Kpad_F + f) = make_float4(o[0], o[1], o[2], o[3]);
+        }
+        return;
+    }
+    float *zbuf = reinterpret_cast<float *>(lds + md.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group
+    const int items = gn * rows * 4;
+    for (int idx = tid; idx < items; idx += WG_THREADS) {
+        int ntg = idx / (rows * 4), rem = idx - ntg * rows * 4;
+        int m = rem >> 2, qd = rem & 3;
+        const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
+        float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int w = 0; w < WAVES; ++w) {
+            float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
+            S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
+        }
+        const int n = (nt_first + ntg) * 16 + qd * 4;  // four consecutive output columns
+        if (kind == G_O || kind == G_DN) {
+            if (n < md.d) {
+                float4 *hp = reinterpret_cast<float4 *>(a.sc.h + (size_t)m * md.d + n);
+                float4 hv = *hp;
+                *hp = make_float4(hv.x + S.x, hv.y + S.y, hv.z + S.z, hv.w + S.w);
+            }
+        } else if (kind == G_QKV) {
+            const int d = md.d, hd = md.hd;
+            const float rs = mi.rstd[m];
+            float v[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
+            const int sect = n / d, c = n - sect * d;
+            const int head = c / hd, e = c - head * hd;
+            if (sect < 2) {
+                // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2
+                float2 c0 = mi.rope[m * (hd >> 1) + (e >> 1)], c1 = mi.rope[m * (hd >> 1) + (e >> 1) + 1];
+                float y0 = v[0] * c0.x - v[1] * c0.y, y1 = v[1] * c0.x + v[0] * c0.y;
+                float y2 = v[2] * c1.x - v[3] * c1.y, y3 = v[3] * c1.x + v[2] * c1.y;
+                v[0] = y0; v[1] = y1; v[2] = y2; v[3] = y3;
+            }
+            if (sect == 0) {
+                *reinterpret_cast<float4 *>(a.sc.q + (size_t)m * d + c) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+                const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
+                uint16_t *pool = sect == 1 ? sd.kpool : sd.vpool;
+                uint2 pk;
+                pk.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
+                pk.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
+                *reinterpret_cast<uint2 *>(pool + mi.kvoff[m] + (size_t)head * KV_PAGE * hd + e) = pk;
+            }
+        } else {  // G_HEAD
+            const float rs = mi.rstd[m];
+            float z[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
+            float *zr = zbuf + (size_t)m * pl.GRP * 16 + ntg * 16 + qd * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (n + e >= md.V) z[e] = -INFINITY;
+                zr[e] = z[e];
+            }
+            if (a.keep_logits) {
+                float *keep = a.sc.logits + ((size_t)a.head_idx * md.rows_max + m) * md.V;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (n + e < md.V) keep[n + e] = z[e];
+            }
+        }
+    }
+    if (kind == G_HEAD) {
+        __syncthreads();
+        const int lane = tid & 63, wave = tid >> 6;
+        for (int m = wave; m < rows; m += WAVES) {
+            float bv = -INFINITY;
+            int bi = 0x7FFFFFFF;
+            for (int c = lane; c < gn * 16; c += 64) {
+                float z = zbuf[(size_t)m * pl.GRP * 16 + c];
+                int n = nt_first * 16 + c;
+                if (cand_better(z, n, bv, bi)) {
+                    bv = z;
+                    bi = n;
+                }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                float ov = __shfl_xor(bv, off, 64);
+                int oi = __shfl_xor(bi, off, 64);
+                if (cand_better(ov, oi, bv, bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+            }
+            if (lane == 0 && cand_better(bv, bi, mi.bestv[m], mi.besti[m])) {
+                mi.bestv[m] = bv;
+                mi.besti[m] = bi;
+            }
+        }
+    }
+}
+
+template <int MT>
+__device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const uint4 *__restrict__ W,
+                             const GemmIn &in, uint4 (&buf)[D], bool &have_pre, const NextGemm &next, char *lds)
+{
+    const ModelDev &md = *a.md;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int rows = a.rows;
+    const Misc mi = misc_views(md, lds);
+    int nt0, n_local;
+    wg_units(pl, a.nwg, blockIdx.x, nt0, n_local);
+
+    if (kind == G_HEAD) {
+        if (tid < rows) {
+            mi.bestv[tid] = -INFINITY;
+            mi.besti[tid] = 0x7FFFFFFF;
+        }
+    }
+    if (n_local == 0) {  // nothing to stream here (uniform over the workgroup)
+        have_pre = prefetch_stage(next, a.nwg, buf);
+        if (kind == G_HEAD && tid < rows)
+            a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(-INFINITY), 0x7FFFFFFF);
+        return;
+    }
+    if (kind == G_QKV) {
+        // per-row position, KV slot and RoPE factors for the epilogue
+        if (tid < rows) {
+            const int m = tid;
+            const int pos = row_pos(a, m);
+            const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
+            const int page = sd.page_table[pos / KV_PAGE];
+            mi.pos[m] = pos;
+            mi.kvoff[m] = ((((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE + (pos % KV_PAGE)) * md.hd;
+        }
+        const int half = md.hd >> 1;
+        for (int i = tid; i < rows * half; i += WG_THREADS) {
+            int m = i / half, j = i - m * half;
+            const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
+            mi.rope[i] = sd.rope[(size_t)row_pos(a, m) * half + j];
+        }
+    }
+
+    const uint16_t *xs_hi = reinterpret_cast<const uint16_t *>(lds);
+    const uint16_t *xs_lo = xs_hi + (size_t)rows * pl.xs_stride;
+    float *slots = reinterpret_cast<float *>(lds + md.lds_slots_off);
+    int brow[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * pl.xs_stride;
+    const int bk = (lane >> 4) * 8;
+    const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
+    bool seg_pre = have_pre;  // buf[] holds the first tiles of the coming segment
+
+    for (int gi = 0; gi < n_groups; ++gi) {
+        const int gn = min(pl.GRP, n_local - gi * pl.GRP);
+        for (int kb = 0; kb < pl.nKB; ++kb) {
+            const Seg s = seg_setup(pl, nt0, n_local, wave, gi, kb);
+            const bool restage = pl.nKB > 1 || gi == 0;
+            if (restage) {
+                if (gi > 0 || kb > 0) __syncthreads();  // x_hat of the previous block is dead
+                stage_x(pl, in, rows, s.kst, s.klen, kb == 0, in.norm && gi == 0, mi, lds);
+                __syncthreads();
+                if (in.norm && gi == 0 && kb == pl.nKB - 1 && tid < rows) {
+                    const int wpr = rows >= WAVES ? 1 : WAVES / rows;
+                    float t = 0.f;
+                    for (int p = 0; p < wpr; ++p) t += mi.ssq[tid * WAVES + p];
+                    mi.rstd[tid] = 1.0f / sqrtf(t / (float)pl.K + md.eps);
+                }
+            }
+
+            // ---- this wave's tiles of the segment
+            f32x4_t acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+            if (!seg_pre) seg_prefetch(W, s, buf);  // otherwise buf already holds the segment's first tiles
+            seg_pre = false;
+            if (s.slen == 0 && kb == 0) {  // no tiles in this block: contribute zeros
+                for (int ntg = 0; ntg < gn; ++ntg)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        int m = mt * 16 + (lane & 15);
+                        if (m < rows)
+                            *reinterpret_cast<float4 *>(slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4) =
+                                make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
+            }
+            int ntg = 0, kk = 0;        // compute cursor
+            int lntg = 0, lkk = 0;      // load cursor, D tiles ahead
+            {
+                int adv = min(D, s.n);  // tiles already fetched
+                if (s.slen > 0) {
+                    lntg = adv / s.slen;
+                    lkk = adv - lntg * s.slen;
+                }
+            }
+            const uint4 *wp = W + (size_t)(s.base + s.s0) * 64 + lane;
+            for (int i = 0; i < s.n; i += D) {
+#pragma unroll
+                for (int j = 0; j < D; ++j) {
+                    if (i + j < s.n) {
+                        uint4 av = buf[j];
+                        if (i + j + D < s.n) {
+                            buf[j] = load_stream16(wp + (size_t)((long long)lntg * s.klen + lkk) * 64);
+                            if (++lkk == s.slen) {
+                                lkk = 0;
+                                ++lntg;
+                            }
+                        }
+                        bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
+                        const int xo = (s.s0 + kk) * 32 + bk;
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) {
+                            uint4 bh = *reinterpret_cast<const uint4 *>(xs_hi + brow[mt] + xo);
+                            uint4 bl = *reinterpret_cast<const uint4 *>(xs_lo + brow[mt] + xo);
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
+                        }
+                        if (++kk == s.slen) {
+                            // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt) {
+                                int m = mt * 16 + (lane & 15);
+                                if (m < rows) {
+                                    float4 *dst = reinterpret_cast<float4 *>(
+                                        slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
+                                    float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
+                                    if (kb > 0) {
+                                        float4 o = *dst;
+                                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                                    }
+                                    *dst = v;
+                                }
+                                acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                            }
+                            kk = 0;
+                            ++ntg;
+                        }
+                    }
+                }
+            }
+            // ---- fetch ahead: next segment of this stage, or the first tiles of the next GEMM stage
+            const bool last_seg = (gi == n_groups - 1) && (kb == pl.nKB - 1);
+            if (!last_seg) {
+                const int ngi = kb + 1 < pl.nKB ? gi : gi + 1, nkb = kb + 1 < pl.nKB ? kb + 1 : 0;
+                const Seg ns = seg_setup(pl, nt0, n_local, wave, ngi, nkb);
+                seg_prefetch(W, ns, buf);
+                seg_pre = true;
+            } else {
+                have_pre = prefetch_stage(next, a.nwg, buf);
+            }
+        }
+        __syncthreads();
+        gemm_epilogue(a, kind, layer, pl, nt0 + gi * pl.GRP, gn, rows, mi, lds);
+        if (gi + 1 < n_groups) __syncthreads();
+    }
+    if (kind == G_HEAD) {
+        __syncthreads();
+        if (tid < rows)
+            a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(mi.bestv[tid]), mi.besti[tid]);
+    }
+}
+
+// ------------------------------------------------------------------ embedding
+
+__device__ void embed_stage(const PassArgs &a)
+{
+    const ModelDev &md = *a.md;
+    const int d = md.d, q4 = d >> 2;
+    const int gsz = a.nwg * WG_THREADS;
+    for (int it = blockIdx.x * WG_THREADS + threadIdx.x; it < a.rows * q4; it += gsz) {
+        int m = it / q4, c = (it - m * q4) * 4;
+        int tok = row_token(a, m);
+        const uint16_t *src = tok >= 0 ? md.emb + (size_t)tok * d + c : a.pf_emb + (size_t)m * d + c;
+        uint2 r = *reinterpret_cast<const uint2 *>(src);
+        *reinterpret_cast<float4 *>(a.sc.h + (size_t)m * d + c) =
+            make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+                        __uint_as_float(r.y & 0xFFFF0000u));
+    }
+}
+
+// ------------------------------------------------------------------ attention
 
 constexpr float ATT_NEG = -1.0e30f;  // finite stand-in for "no position seen yet"
 
-// Work item = (session, head, chunk of up to ATT_ROWS query rows, split of the
-// position range).  Each wave takes a contiguous part of the split; a group of
-// HD/8 lanes handles one cached position per step (16-byte loads of K and V).
-// Output per item: un-normalised accumulator, running max and sum per row.
+// Work item = (session, head, chunk of up to ATT_ROWS query rows, split of the position
+// range).  The 16 waves of the workgroup share the split's positions; a group of HD/8 lanes
+// handles one cached position per step (16-byte loads of K and V).  q and the cached k use
+// the same pair-interleaved order inside a head, so their dot product is unchanged.
+// With one split the normalised output is written directly; otherwise un-normalised
+// partials (accumulator, running max, running sum) go to scratch for the merge stage.
 template <int HD>
-__device__ void att_phase(const PassArgs &a, int layer, char *lds)
+__device__ void att_stage(const PassArgs &a, int layer, char *lds)
 {
     constexpr int LPP = HD / 8;    // lanes per position
     constexpr int PPI = 64 / LPP;  // positions per wave step
@@ -424,11 +612,11 @@ __device__ void att_phase(const PassArgs &a, int layer, char *lds)
         int hh = rem / n_chunks, ch = rem - hh * n_chunks;
         int r0 = ch * ATT_ROWS, nr = min(ATT_ROWS, M - r0);
         const SessDev &sd = a.sess[s];
-        int P = row_pos(a, s * M);              // position of the session's first row
-        int n_pos = P + r0 + nr;                // positions visible to the chunk's last row
-        int lo = (int)((long long)n_pos * sp / n_splits), hi = (int)((long long)n_pos * (sp + 1) / n_splits);
-        int wlo = lo + (int)((long long)(hi - lo) * wave / WAVES_PER_WG);
-        int whi = lo + (int)((long long)(hi - lo) * (wave + 1) / WAVES_PER_WG);
+        const int P = row_pos(a, s * M);          // position of the session's first row
+        const int n_pos = P + r0 + nr;            // positions visible to the chunk's last row
+        const int lo = (int)((long long)n_pos * sp / n_splits), hi = (int)((long long)n_pos * (sp + 1) / n_splits);
+        const int wlo = lo + (int)((long long)(hi - lo) * wave / WAVES);
+        const int whi = lo + (int)((long long)(hi - lo) * (wave + 1) / WAVES);
 
         float q[ATT_ROWS][8], acc[ATT_ROWS][8], mx[ATT_ROWS], l[ATT_ROWS];
 #pragma unroll
@@ -444,11 +632,11 @@ __device__ void att_phase(const PassArgs &a, int layer, char *lds)
         }
 
         for (int pb = wlo; pb < whi; pb += PPI) {
-            int p = pb + grp;
-            bool live = p < whi;
-            int pc = live ? p : wlo;
-            int page = sd.page_table[pc / KV_PAGE];
-            size_t off = ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * HD + e8 * 8;
+            const int p = pb + grp;
+            const bool live = p < whi;
+            const int pc = live ? p : wlo;
+            const int page = sd.page_table[pc / KV_PAGE];
+            const size_t off = ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * HD + e8 * 8;
             uint4 kk = *reinterpret_cast<const uint4 *>(sd.kpool + off);
             uint4 vv = *reinterpret_cast<const uint4 *>(sd.vpool + off);
             float kf[8], vf[8];
@@ -500,30 +688,45 @@ __device__ void att_phase(const PassArgs &a, int layer, char *lds)
         }
         __syncthreads();
         // merge the waves, fixed order
-        float *out = a.sc.att_part + (size_t)item * ATT_ROWS * REC;
-        for (int t = tid; t < nr * REC; t += WG_THREADS) {
-            int i = t / REC, e = t - i * REC;
-            float gm = ATT_NEG;
-            for (int w = 0; w < WAVES_PER_WG; ++w) gm = fmaxf(gm, wbuf[((size_t)w * ATT_ROWS + i) * REC + HD]);
-            float r;
-            if (e == HD) {
-                r = gm;
-            } else {
-                r = 0.f;
-                int src = (e == HD + 1) ? HD + 1 : e;
-                for (int w = 0; w < WAVES_PER_WG; ++w) {
+        if (n_splits == 1) {
+            for (int t = tid; t < nr * HD; t += WG_THREADS) {
+                int i = t / HD, e = t - i * HD;
+                float gm = ATT_NEG;
+                for (int w = 0; w < WAVES; ++w) gm = fmaxf(gm, wbuf[((size_t)w * ATT_ROWS + i) * REC + HD]);
+                float num = 0.f, den = 0.f;
+                for (int w = 0; w < WAVES; ++w) {
                     const float *wr = wbuf + ((size_t)w * ATT_ROWS + i) * REC;
-                    r += wr[src] * __expf(wr[HD] - gm);
+                    float f = __expf(wr[HD] - gm);
+                    num += wr[e] * f;
+                    den += wr[HD + 1] * f;
                 }
+                a.sc.attn[(size_t)(s * M + r0 + i) * md.Kpad_d + hh * HD + e] = num / den;
             }
-            out[(size_t)i * REC + e] = r;
+        } else {
+            float *out = a.sc.att_part + (size_t)item * ATT_ROWS * REC;
+            for (int t = tid; t < nr * REC; t += WG_THREADS) {
+                int i = t / REC, e = t - i * REC;
+                float gm = ATT_NEG;
+                for (int w = 0; w < WAVES; ++w) gm = fmaxf(gm, wbuf[((size_t)w * ATT_ROWS + i) * REC + HD]);
+                float r;
+                if (e == HD) {
+                    r = gm;
+                } else {
+                    r = 0.f;
+                    for (int w = 0; w < WAVES; ++w) {
+                        const float *wr = wbuf + ((size_t)w * ATT_ROWS + i) * REC;
+                        r += wr[e] * __expf(wr[HD] - gm);
+                    }
+                }
+                out[(size_t)i * REC + e] = r;
+            }
         }
         __syncthreads();
     }
 }
 
-// merge the splits, normalise, write the attention output
-__device__ void ratt_phase(const PassArgs &a)
+// merge the splits, normalise, write the attention output (only when n_splits > 1)
+__device__ void att_merge_stage(const PassArgs &a)
 {
     const ModelDev &md = *a.md;
     const int d = md.d, HD = md.hd, H = md.H, M = a.M, rows = a.rows;
@@ -550,75 +753,17 @@ __device__ void ratt_phase(const PassArgs &a)
     }
 }
 
-// ------------------------------------------------------------------ R_GU
-
-__device__ void rgu_phase(const PassArgs &a, char *lds)
-{
-    const ModelDev &md = *a.md;
-    const int F = md.F, rows = a.rows;
-    float *rstd = reinterpret_cast<float *>(lds);
-    load_rstd(a.sc.ss_f, a.nwg, md.rows_max, rows, md.d, md.eps, rstd);
-    const int gsz = a.nwg * WG_THREADS;
-    for (int it = blockIdx.x * WG_THREADS + threadIdx.x; it < rows * F; it += gsz) {
-        int m = it / F, f = it - m * F;
-        float g = rstd[m] * reduce_out(md.gu, md.rows_max, m, f);
-        float u = rstd[m] * reduce_out(md.gu, md.rows_max, m, F + f);
-        float sg = g / (1.0f + __expf(-g));
-        a.sc.u[(size_t)m * md.Kpad_F + f] = sg * u;
-    }
-}
-
-// ------------------------------------------------------------------ heads
-
-__device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
-{
-    return v > bv || (v == bv && i < bi);
-}
-
-// logits of this workgroup's vocabulary slice, argmax candidate per row
-__device__ void rhead_phase(const PassArgs &a, char *lds)
-{
-    const ModelDev &md = *a.md;
-    const int V = md.V, rows = a.rows;
-    float *rstd = reinterpret_cast<float *>(lds);
-    load_rstd(a.sc.ss_a, a.nwg, md.rows_max, rows, md.d, md.eps, rstd);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int vw = (V + a.nwg - 1) / a.nwg;
-    const int lo = blockIdx.x * vw, hi = min(V, lo + vw);
-    float *keep = a.keep_logits ? a.sc.logits + (size_t)a.head_idx * md.rows_max * V : nullptr;
-    for (int m = wave; m < rows; m += WAVES_PER_WG) {
-        float bv = -INFINITY;
-        int bi = 0x7FFFFFFF;
-        for (int n = lo + lane; n < hi; n += 64) {
-            float z = rstd[m] * reduce_out(md.head, md.rows_max, m, n);
-            if (keep) keep[(size_t)m * V + n] = z;
-            if (cand_better(z, n, bv, bi)) {
-                bv = z;
-                bi = n;
-            }
-        }
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            float ov = __shfl_xor(bv, off, 64);
-            int oi = __shfl_xor(bi, off, 64);
-            if (cand_better(ov, oi, bv, bi)) {
-                bv = ov;
-                bi = oi;
-            }
-        }
-        if (lane == 0) a.sc.cand[(size_t)blockIdx.x * md.rows_max + m] = make_int2(__float_as_int(bv), bi);
-    }
-}
+// ------------------------------------------------------------------ accept
 
 // Workgroup 0: global argmax per row, accept rule per session, publication.
-__device__ void accept_phase(const PassArgs &a, char *lds)
+__device__ void accept_stage(const PassArgs &a, char *lds)
 {
     if (blockIdx.x != 0) return;
     const ModelDev &md = *a.md;
     const int rows = a.rows, M = a.M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int *tok = reinterpret_cast<int *>(lds);
-    for (int m = wave; m < rows; m += WAVES_PER_WG) {
+    for (int m = wave; m < rows; m += WAVES) {
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
         for (int g = lane; g < a.nwg; g += 64) {
@@ -654,8 +799,13 @@ __device__ void accept_phase(const PassArgs &a, char *lds)
             sd.state[1] = last;
         } else {
             const int gamma = M - 1;
+            int dr[EE_MAX_M];
+#pragma unroll
+            for (int i = 0; i < EE_MAX_M - 1; ++i) dr[i] = i < gamma ? sd.drafts[i] : -1;
             int delta = 0;
-            while (delta < gamma && sd.drafts[delta] == t[delta]) ++delta;
+#pragma unroll
+            for (int i = 0; i < EE_MAX_M - 1; ++i)
+                if (delta == i && i < gamma && dr[i] == t[i]) delta = i + 1;
             if (a.head_kind == HEAD_EXIT) {
                 for (int i = 0; i < M; ++i) res->exit_tokens[a.head_idx][i] = t[i];
                 res->exit_accept_len[a.head_idx] = delta;
@@ -674,87 +824,171 @@ __device__ void accept_phase(const PassArgs &a, char *lds)
     }
 }
 
-// ------------------------------------------------------------------ the segment kernel
+// ------------------------------------------------------------------ kernels of the pass
+//
+// Stage list of a segment: [EMBED] { QKV ATT [MERGE] O GU DN } x layers [HEAD ACCEPT].
+// Consecutive GEMM stages run inside one launch of the chain kernel with a grid barrier
+// between them; attention, embedding, merge and accept are launches of their own.
 
-__global__ void __launch_bounds__(WG_THREADS) ee_segment_kernel(PassArgs a)
+struct StageDesc {
+    int type, kind, layer;
+};
+
+__device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
+{
+    StageDesc sd = {ST_NONE, 0, 0};
+    const bool split = a.att_splits > 1;
+    const int per_layer = 5 + (split ? 1 : 0);
+    int idx = ph - (a.do_embed ? 1 : 0);
+    if (idx < 0) {
+        sd.type = ST_EMBED;
+        return sd;
+    }
+    const int nl = a.layer_end - a.layer_begin;
+    if (idx < per_layer * nl) {
+        int li = idx / per_layer, r = idx - li * per_layer;
+        sd.layer = a.layer_begin + li;
+        if (r == 0) {
+            sd.type = ST_GEMM;
+            sd.kind = G_QKV;
+        } else if (r == 1) {
+            sd.type = ST_ATT;
+        } else if (split && r == 2) {
+            sd.type = ST_MERGE;
+        } else {
+            sd.type = ST_GEMM;
+            sd.kind = G_O + (r - (split ? 3 : 2));
+        }
+        return sd;
+    }
+    idx -= per_layer * nl;
+    if (a.head_kind != HEAD_NONE) {
+        if (idx == 0) {
+            sd.type = ST_GEMM;
+            sd.kind = G_HEAD;
+        } else if (idx == 1) {
+            sd.type = ST_ACCEPT;
+        }
+    }
+    return sd;
+}
+
+__device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind, int layer)
+{
+    const ModelDev &md = *a.md;
+    switch (kind) {
+    case G_QKV: return GemmIn{a.sc.h, md.d, md.g_attn + (size_t)layer * md.d, true};
+    case G_O: return GemmIn{a.sc.attn, md.Kpad_d, nullptr, false};
+    case G_GU: return GemmIn{a.sc.h, md.d, md.g_ffn + (size_t)layer * md.d, true};
+    case G_DN: return GemmIn{a.sc.u, md.Kpad_F, nullptr, false};
+    default: return GemmIn{a.sc.h, md.d, a.head_gain, true};
+    }
+}
+
+// GEMM stages [ph_lo, ph_hi) of the stage list (all of them must be GEMM stages).
+// MT = 16-row tiles of the pass (rows <= 16 * MT).
+template <int MT>
+__global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
 {
     extern __shared__ __align__(16) char lds[];
+    const ModelDev &md = *a.md;
+    unsigned nbar = 0;
     if (a.mode == 2) {  // measurement aid: layer_end grid barriers and nothing else
-        for (int i = 0; i < a.layer_end; ++i) grid_barrier(a.sc.bar, a.nwg, a.sc.err, a.spin_limit);
+        for (int i = 0; i < a.layer_end; ++i)
+            grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
         return;
     }
-    const ModelDev &md = *a.md;
-    int ph = 0;
-    bool first = true;
+    uint4 buf[D];           // weight tiles in flight; carried from one stage into the next
+    bool have_pre = false;  // buf holds the first tiles of the coming stage
+    for (int ph = a.ph_lo; ph < a.ph_hi; ++ph) {
+        if (ph > a.ph_lo) grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
+        const StageDesc st = stage_decode(a, ph);
+        NextGemm nx = {nullptr, nullptr};
+        if (ph + 1 < a.ph_hi) {
+            const StageDesc sn = stage_decode(a, ph + 1);
+            nx.pl = &md.plan[sn.kind];
+            nx.W = md.w[sn.kind] + (size_t)sn.layer * md.wstride[sn.kind];
+        }
+        const GemmIn in = gemm_input(a, st.kind, st.layer);
+        gemm_stage_t<MT>(a, st.kind, st.layer, md.plan[st.kind], md.w[st.kind] + (size_t)st.layer * md.wstride[st.kind],
+                         in, buf, have_pre, nx, lds);
+    }
+}
 
-#define EE_PHASE(body)                                                          \
-    do {                                                                        \
-        if (ph >= a.ph_lo && ph < a.ph_hi) {                                    \
-            if (!first) grid_barrier(a.sc.bar, a.nwg, a.sc.err, a.spin_limit);  \
-            first = false;                                                      \
-            body;                                                               \
-        }                                                                       \
-        ++ph;                                                                   \
-    } while (0)
+template <int HD>
+__global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a)
+{
+    extern __shared__ __align__(16) char lds[];
+    att_stage<HD>(a, stage_decode(a, a.ph_lo).layer, lds);
+}
 
-    if (a.do_embed) {
-        const bool head_next = (a.layer_begin == a.layer_end) && a.head_kind != HEAD_NONE;
-        EE_PHASE(resid_phase<0>(a, nullptr, a.layer_begin < md.L ? md.layers[a.layer_begin].g_attn : nullptr,
-                                a.layer_begin < md.L ? a.sc.xn : nullptr, head_next ? a.head_gain : nullptr,
-                                head_next ? a.sc.xh : nullptr, a.sc.ss_a, lds));
-    }
-    for (int l = a.layer_begin; l < a.layer_end; ++l) {
-        const LayerDev &lw = md.layers[l];
-        EE_PHASE(gemm_dispatch(md.qkv, lw.wqkv, a.sc.xn, md.Kpad_d, a.rows, md.rows_max, a.nwg, lds));
-        EE_PHASE(rqkv_phase(a, l, lds));
-        if (md.hd == 128)
-            EE_PHASE(att_phase<128>(a, l, lds));
-        else
-            EE_PHASE(att_phase<64>(a, l, lds));
-        EE_PHASE(ratt_phase(a));
-        EE_PHASE(gemm_dispatch(md.o, lw.wo, a.sc.attn, md.Kpad_d, a.rows, md.rows_max, a.nwg, lds));
-        EE_PHASE(resid_phase<1>(a, &md.o, lw.g_ffn, a.sc.xn, nullptr, nullptr, a.sc.ss_f, lds));
-        EE_PHASE(gemm_dispatch(md.gu, lw.wgu, a.sc.xn, md.Kpad_d, a.rows, md.rows_max, a.nwg, lds));
-        EE_PHASE(rgu_phase(a, lds));
-        EE_PHASE(gemm_dispatch(md.dn, lw.wd, a.sc.u, md.Kpad_F, a.rows, md.rows_max, a.nwg, lds));
-        const bool more = l + 1 < md.L;
-        const bool head_next = (l + 1 == a.layer_end) && a.head_kind != HEAD_NONE;
-        EE_PHASE(resid_phase<1>(a, &md.dn, more ? md.layers[l + 1].g_attn : nullptr, more ? a.sc.xn : nullptr,
-                                head_next ? a.head_gain : nullptr, head_next ? a.sc.xh : nullptr, a.sc.ss_a, lds));
-    }
-    if (a.head_kind != HEAD_NONE) {
-        EE_PHASE(gemm_dispatch(md.head, md.wlm, a.sc.xh, md.Kpad_d, a.rows, md.rows_max, a.nwg, lds));
-        EE_PHASE(rhead_phase(a, lds));
-        EE_PHASE(accept_phase(a, lds));
-    }
-#undef EE_PHASE
+// embedding, attention merge, accept: stage ph_lo
+__global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a)
+{
+    extern __shared__ __align__(16) char lds[];
+    const StageDesc st = stage_decode(a, a.ph_lo);
+    if (st.type == ST_EMBED)
+        embed_stage(a);
+    else if (st.type == ST_MERGE)
+        att_merge_stage(a);
+    else if (st.type == ST_ACCEPT)
+        accept_stage(a, lds);
 }
 
 // ------------------------------------------------------------------ load-time kernels
 
-// row-major bf16 src[N][K] -> tiled layout (see GemmPlan); zero padding outside N x K
-__global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, GemmPlan pl)
+// source row of output column n for the row orders the stages expect
+__device__ __forceinline__ int perm_row(int perm, int n, int d, int hd, int F)
 {
-    const long long total = pl.T * 64;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        long long t = i >> 6;
-        int lane = (int)(i & 63);
-        TilePos p = tile_decode(pl, t);
-        int n = p.nt * 16 + (lane & 15);
-        int k0 = (p.kb * pl.KBT + p.kti) * 32 + (lane >> 4) * 8;
-        uint16_t v[8];
+    if (perm == PERM_QKV) {
+        int sect = n / d, c = n - sect * d;
+        if (sect >= 2) return n;
+        int head = c / hd, e = c - head * hd;
+        int src_e = (e & 1) ? (e >> 1) + (hd >> 1) : (e >> 1);  // RoPE pair (j, j+hd/2) -> columns (2j, 2j+1)
+        return sect * d + head * hd + src_e;
+    }
+    if (perm == PERM_GU) {
+        int tile = n >> 4, r = n & 15;
+        int p = tile >> 1, which = tile & 1;                     // gate tile p, up tile p, gate tile p+1, ...
+        return which * F + p * 16 + r;
+    }
+    return n;
+}
+
+// row-major bf16 src[N][K] -> the tiled layout of GemmPlan; block g writes workgroup g's tiles
+__global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, GemmPlan pl, int nwg,
+                                    int perm, int d, int hd, int F)
+{
+    const int g = blockIdx.x;
+    int nt0, n_local;
+    wg_units(pl, nwg, g, nt0, n_local);
+    if (n_local == 0) return;
+    const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6, nsub = blockDim.x >> 6;
+    const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
+    for (int gi = 0; gi < n_groups; ++gi) {
+        const int gn = min(pl.GRP, n_local - gi * pl.GRP);
+        for (int kb = 0; kb < pl.nKB; ++kb) {
+            const int kst = pl.KT * kb / pl.nKB, klen = pl.KT * (kb + 1) / pl.nKB - kst;
+            const long long base = (long long)nt0 * pl.KT + (long long)gi * pl.GRP * pl.KT + (long long)gn * kst;
+            for (int t = sub; t < gn * klen; t += nsub) {
+                int ntg = t / klen, kti = t - ntg * klen;
+                int n = (nt0 + gi * pl.GRP + ntg) * 16 + (lane & 15);
+                int k0 = (kst + kti) * 32 + (lane >> 4) * 8;
+                uint16_t v[8];
+                int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            int k = k0 + e;
-            v[e] = (n < pl.N && k < pl.K) ? src[(size_t)n * pl.K + k] : (uint16_t)0;
+                for (int e = 0; e < 8; ++e) {
+                    int k = k0 + e;
+                    v[e] = (row >= 0 && k < pl.K) ? src[(size_t)row * pl.K + k] : (uint16_t)0;
+                }
+                uint4 o;
+                o.x = v[0] | ((uint32_t)v[1] << 16);
+                o.y = v[2] | ((uint32_t)v[3] << 16);
+                o.z = v[4] | ((uint32_t)v[5] << 16);
+                o.w = v[6] | ((uint32_t)v[7] << 16);
+                dst[(size_t)(base + t) * 64 + lane] = o;
+            }
         }
-        uint4 o;
-        o.x = v[0] | ((uint32_t)v[1] << 16);
-        o.y = v[2] | ((uint32_t)v[3] << 16);
-        o.z = v[4] | ((uint32_t)v[5] << 16);
-        o.w = v[6] | ((uint32_t)v[7] << 16);
-        dst[i] = o;
     }
 }
 

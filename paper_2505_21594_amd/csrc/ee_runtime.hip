@@ -48,8 +48,6 @@ struct ee_model {
     size_t lds_budget;           // dynamic LDS bytes each launch asks for
     ModelDev host_md;            // host copy of the device descriptor
     ModelDev *dev_md;
-    std::vector<LayerDev> layers;
-    LayerDev *dev_layers;
     std::vector<void *> allocs;  // every device allocation of the model
     const float *g_exit[EE_MAX_EXITS];
 };
@@ -80,6 +78,7 @@ struct ee_session {
     SessDev *dev_sessdev;            // [EE_MAX_BATCH] per-pass session descriptors
     SessDev *host_sessdev;           // pinned staging for them
     Scratch sc;
+    unsigned epoch;                  // grid-barrier epoch reached by the launches enqueued so far
     std::vector<void *> allocs;
     // host mirror of the session state
     int kv_len;
@@ -92,31 +91,61 @@ struct ee_session {
 
 // ------------------------------------------------------------------ planning
 
-static GemmPlan make_plan(int N, int K, int kbt, int NW)
+typedef void (*pass_kernel_t)(PassArgs);
+
+static pass_kernel_t chain_kernel(int rows)
+{
+    return rows <= 16 ? ee_gemm_chain_kernel<1> : (rows <= 32 ? ee_gemm_chain_kernel<2> : ee_gemm_chain_kernel<3>);
+}
+
+static pass_kernel_t att_kernel(int hd) { return hd == 128 ? ee_att_kernel<128> : ee_att_kernel<64>; }
+
+// n-tiles the busiest workgroup owns
+static int plan_max_local(int U, int tpu, int nwg)
+{
+    int mx = 0;
+    for (int g = 0; g < nwg; ++g) {
+        int u0 = (int)((long long)U * g / nwg), u1 = (int)((long long)U * (g + 1) / nwg);
+        mx = std::max(mx, (u1 - u0) * tpu);
+    }
+    return mx;
+}
+
+static GemmPlan make_plan(int N, int K, int tpu, int nwg, int rows_max, size_t slot_budget)
 {
     GemmPlan p;
     memset(&p, 0, sizeof p);
     p.N = N;
     p.K = K;
     p.NT = (N + 15) / 16;
+    p.NT = (p.NT + tpu - 1) / tpu * tpu;
     p.KT = (K + 31) / 32;
-    p.KBT = std::min(kbt, p.KT);
-    p.nKB = (p.KT + p.KBT - 1) / p.KBT;
-    p.KBT_last = p.KT - (p.nKB - 1) * p.KBT;
-    p.T = (long long)p.NT * p.KT;
-    // most waves sharing one run
-    int maxp = 1;
-    const long long B = (long long)p.NT * p.KBT;
-    for (int kb = 0; kb < p.nKB; ++kb) {
-        int klen = kb == p.nKB - 1 ? p.KBT_last : p.KBT;
-        for (int nt = 0; nt < p.NT; ++nt) {
-            long long s = (long long)kb * B + (long long)nt * klen, e = s + klen - 1;
-            int w0 = (int)(((s + 1) * (long long)NW - 1) / p.T), w1 = (int)(((e + 1) * (long long)NW - 1) / p.T);
-            maxp = std::max(maxp, w1 - w0 + 1);
+    p.tpu = tpu;
+    p.U = p.NT / tpu;
+    // group: as many n-tiles as the cross-wave reduction buffer holds
+    const size_t per_tile = (size_t)WAVES * rows_max * 16 * sizeof(float);
+    int grp = (int)(slot_budget / per_tile) / tpu * tpu;
+    grp = std::max(grp, tpu);
+    p.GRP = std::min(grp, std::max(plan_max_local(p.U, tpu, nwg), tpu));
+    p.nKB = 1;
+    return p;
+}
+
+static size_t plan_slot_bytes(const GemmPlan &p, int rows_max) { return (size_t)WAVES * p.GRP * rows_max * 16 * sizeof(float); }
+
+// K-blocks so that one block of x_hat (hi and lo bf16 terms, all rows) fits `budget` bytes
+static bool plan_set_blocks(GemmPlan &p, int rows_max, size_t budget)
+{
+    for (int nkb = 1; nkb <= p.KT; ++nkb) {
+        int klen = (p.KT + nkb - 1) / nkb;
+        size_t stride = (size_t)klen * 32 + 8;
+        if ((size_t)2 * rows_max * stride * 2 <= budget) {
+            p.nKB = nkb;
+            p.xs_stride = (int)stride;
+            return true;
         }
     }
-    p.MAXP = maxp;
-    return p;
+    return false;
 }
 
 template <typename T>
@@ -146,31 +175,25 @@ struct FileMap {
 };
 }  // namespace
 
-static int upload_tiled(ee_model *m, GemmPlan &pl, const uint16_t *const *srcs, int n_src, size_t elems_each,
-                        uint16_t *tmp, const uint4 **out)
+// concatenates the sources row-wise in a device buffer and writes layer slice `dst` in tile order
+static int upload_tiled(const ee_model *m, const GemmPlan &pl, int perm, const uint16_t *const *srcs, int n_src,
+                        size_t elems_each, uint16_t *tmp, uint4 *dst)
 {
     for (int i = 0; i < n_src; ++i)
         HIP_TRY(hipMemcpy(tmp + (size_t)i * elems_each, srcs[i], elems_each * 2, hipMemcpyHostToDevice));
-    uint4 *dst = nullptr;
-    int rc = dev_alloc(m->allocs, &dst, (size_t)pl.T * 64, false);
-    if (rc != EE_OK) return rc;
-    hipLaunchKernelGGL(tile_weights_kernel, dim3(2048), dim3(256), 0, 0, tmp, dst, pl);
+    hipLaunchKernelGGL(tile_weights_kernel, dim3(m->nwg), dim3(512), 0, 0, tmp, dst, pl, m->nwg, perm,
+                       m->cfg.d_model, m->cfg.head_dim, m->cfg.d_ffn);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipDeviceSynchronize());
-    *out = dst;
     return EE_OK;
 }
 
-static int upload_gain(ee_model *m, const uint16_t *src, int d, uint16_t *tmp, const float **out)
+static int upload_gain(const uint16_t *src, int d, uint16_t *tmp, float *dst)
 {
-    float *dst = nullptr;
-    int rc = dev_alloc(m->allocs, &dst, (size_t)d, false);
-    if (rc != EE_OK) return rc;
     HIP_TRY(hipMemcpy(tmp, src, (size_t)d * 2, hipMemcpyHostToDevice));
     hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((d + 255) / 256), dim3(256), 0, 0, tmp, dst, d);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipDeviceSynchronize());
-    *out = dst;
     return EE_OK;
 }
 
@@ -285,9 +308,6 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     c.max_rows = max_rows;
     c.n_workgroups = m->nwg;
     m->cfg = c;
-    const int NW = m->nwg * WAVES_PER_WG;
-    const int kbt = max_rows <= 16 ? 32 : 16;  // K-block size: rows * KBT*32 * 4 bytes of LDS
-
     ModelDev &md = m->host_md;
     memset(&md, 0, sizeof md);
     md.L = c.n_layers;
@@ -301,41 +321,62 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.Kpad_d = (int)align_up(d, 32);
     md.Kpad_F = (int)align_up(F, 32);
     md.rows_max = max_rows;
-    md.qkv = make_plan(3 * c.d_model, c.d_model, kbt, NW);
-    md.o = make_plan(c.d_model, c.d_model, kbt, NW);
-    md.gu = make_plan(2 * c.d_ffn, c.d_model, kbt, NW);
-    md.dn = make_plan(c.d_model, c.d_ffn, kbt, NW);
-    md.head = make_plan(c.vocab, c.d_model, kbt, NW);
     if (c.d_ffn % 16 != 0) {
         ee_model_free(m);
         return fail(EE_EFORMAT, "ee_model_load: d_ffn must be a multiple of 16");
     }
 
-    // LDS: staging of x_hat for the widest span, attention merge buffer, residual squares
-    size_t lds = 0;
-    GemmPlan *plans[5] = {&md.qkv, &md.o, &md.gu, &md.dn, &md.head};
-    for (GemmPlan *p : plans)  // one K-block of x_hat as hi and lo bf16 terms
-        lds = std::max(lds, (size_t)2 * max_rows * (p->KBT * 32 + 8) * 2);
-    lds = std::max(lds, (size_t)WAVES_PER_WG * ATT_ROWS * (c.head_dim + 2) * 4);
-    lds = std::max(lds, (size_t)max_rows * ((c.d_model + m->nwg - 1) / m->nwg) * 4);
+    // ---- LDS map: [x_hat hi | x_hat lo] [cross-wave slots] [head logits of a group] [misc]
     size_t lds_cap = prop.sharedMemPerBlock;
     {
         int optin = 0;
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
             lds_cap = std::max(lds_cap, (size_t)optin);
     }
-    if (lds > lds_cap) {
+    const size_t slot_budget = std::max<size_t>(48 * 1024, (size_t)2 * WAVES * max_rows * 16 * sizeof(float));
+    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
+    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
+    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg, max_rows, slot_budget);
+    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1, m->nwg, max_rows, slot_budget);
+    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1, m->nwg, max_rows, slot_budget);
+    GemmPlan *plans[5] = {&md.plan[0], &md.plan[1], &md.plan[2], &md.plan[3], &md.plan[4]};
+    size_t slots = 0;
+    for (GemmPlan *p : plans) slots = std::max(slots, plan_slot_bytes(*p, max_rows));
+    const size_t zbuf = align_up((size_t)max_rows * md.plan[G_HEAD].GRP * 16 * sizeof(float), 256);
+    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + WAVES * 4 + 4 + 4 + 4), 256);
+    const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float);
+    if (slots + zbuf + misc + 4096 > lds_cap) {
         ee_model_free(m);
-        return fail(EE_EDEVICE, "ee_model_load: pass needs %zu bytes of LDS, device allows %zu", lds, lds_cap);
+        return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
     }
+    const size_t x_budget = (lds_cap - slots - zbuf - misc) / 256 * 256;
+    size_t x_bytes = 0;
+    for (GemmPlan *p : plans) {
+        if (!plan_set_blocks(*p, max_rows, x_budget)) {
+            ee_model_free(m);
+            return fail(EE_EDEVICE, "ee_model_load: cannot fit one K-block of %d rows into %zu bytes of LDS", max_rows, x_budget);
+        }
+        x_bytes = std::max(x_bytes, (size_t)2 * max_rows * p->xs_stride * 2);
+    }
+    x_bytes = align_up(std::max(x_bytes, att), 256);
+    md.lds_slots_off = (int)x_bytes;
+    md.lds_zbuf_off = (int)(x_bytes + slots);
+    md.lds_misc_off = (int)(x_bytes + slots + zbuf);
+    size_t lds = x_bytes + slots + zbuf + misc;
     // more than half of the CU's LDS keeps it to one workgroup per compute unit
     lds = std::max(lds, std::min((size_t)84 * 1024, lds_cap));
     m->lds_budget = lds;
-    hipError_t fe = hipFuncSetAttribute(reinterpret_cast<const void *>(ee_segment_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    if (fe != hipSuccess) {
-        ee_model_free(m);
-        return fail(EE_EDEVICE, "hipFuncSetAttribute(%zu bytes LDS): %s", lds, hipGetErrorString(fe));
+    {
+        pass_kernel_t ks[6] = {chain_kernel(16), chain_kernel(32), chain_kernel(48), att_kernel(64), att_kernel(128),
+                               ee_misc_kernel};
+        for (pass_kernel_t k : ks) {
+            hipError_t fe = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (fe != hipSuccess) {
+                ee_model_free(m);
+                return fail(EE_EDEVICE, "hipFuncSetAttribute(%zu bytes LDS): %s", lds, hipGetErrorString(fe));
+            }
+        }
     }
 
     int rc = EE_OK;
@@ -360,39 +401,54 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if (hipMemcpy(dev_emb, emb, V * d * 2, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of the embedding table failed"));
     md.emb = dev_emb;
 
-    m->layers.resize((size_t)c.n_layers);
+    // tiled weights: one allocation per GEMM kind, layers at a fixed stride
+    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].NT * md.plan[k].KT * 64;
+    md.wstride[G_HEAD] = 0;
+    const long long s_qkv = md.wstride[G_QKV], s_o = md.wstride[G_O], s_gu = md.wstride[G_GU], s_dn = md.wstride[G_DN];
+    uint4 *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdn = nullptr, *wlm = nullptr;
+    float *g_attn = nullptr, *g_ffn = nullptr, *g_final_d = nullptr;
+    const size_t Lz = (size_t)c.n_layers;
+    if ((rc = dev_alloc(m->allocs, &wqkv, Lz * s_qkv, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].NT * md.plan[G_HEAD].KT * 64, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
     for (int l = 0; l < c.n_layers; ++l) {
-        LayerDev &ld = m->layers[(size_t)l];
         const LayerSrc &s = ls[(size_t)l];
         const uint16_t *qkv[3] = {s.wq, s.wk, s.wv};
         const uint16_t *gu[2] = {s.wg, s.wu};
-        const uint16_t *wo[1] = {s.wo}, *wd[1] = {s.wd};
-        if ((rc = upload_tiled(m, md.qkv, qkv, 3, d * d, tmp, &ld.wqkv)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.o, wo, 1, d * d, tmp, &ld.wo)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.gu, gu, 2, F * d, tmp, &ld.wgu)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.dn, wd, 1, d * F, tmp, &ld.wd)) != EE_OK) return bail(rc);
-        if ((rc = upload_gain(m, s.g_attn, c.d_model, tmp, &ld.g_attn)) != EE_OK) return bail(rc);
-        if ((rc = upload_gain(m, s.g_ffn, c.d_model, tmp, &ld.g_ffn)) != EE_OK) return bail(rc);
+        const uint16_t *so[1] = {s.wo}, *sd[1] = {s.wd};
+        if ((rc = upload_tiled(m, md.plan[G_QKV], PERM_QKV, qkv, 3, d * d, tmp, wqkv + (size_t)l * s_qkv)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.plan[G_O], PERM_NONE, so, 1, d * d, tmp, wo + (size_t)l * s_o)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.plan[G_GU], PERM_GU, gu, 2, F * d, tmp, wgu + (size_t)l * s_gu)) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.plan[G_DN], PERM_NONE, sd, 1, d * F, tmp, wdn + (size_t)l * s_dn)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(s.g_attn, c.d_model, tmp, g_attn + (size_t)l * d)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(s.g_ffn, c.d_model, tmp, g_ffn + (size_t)l * d)) != EE_OK) return bail(rc);
     }
     {
         const uint16_t *lm[1] = {w_lm};
-        if ((rc = upload_tiled(m, md.head, lm, 1, V * d, tmp, &md.wlm)) != EE_OK) return bail(rc);
-        if ((rc = upload_gain(m, g_final, c.d_model, tmp, &md.g_final)) != EE_OK) return bail(rc);
-        for (int i = 0; i < c.n_exits; ++i)
-            if ((rc = upload_gain(m, g_exit_src[i], c.d_model, tmp, &m->g_exit[i])) != EE_OK) return bail(rc);
+        if ((rc = upload_tiled(m, md.plan[G_HEAD], PERM_NONE, lm, 1, V * d, tmp, wlm)) != EE_OK) return bail(rc);
+        if ((rc = upload_gain(g_final, c.d_model, tmp, g_final_d)) != EE_OK) return bail(rc);
+        for (int i = 0; i < c.n_exits; ++i) {
+            float *ge = nullptr;
+            if ((rc = dev_alloc(m->allocs, &ge, d, false)) != EE_OK) return bail(rc);
+            if ((rc = upload_gain(g_exit_src[i], c.d_model, tmp, ge)) != EE_OK) return bail(rc);
+            m->g_exit[i] = ge;
+        }
     }
+    md.w[G_QKV] = wqkv;
+    md.w[G_O] = wo;
+    md.w[G_GU] = wgu;
+    md.w[G_DN] = wdn;
+    md.w[G_HEAD] = wlm;
+    md.g_attn = g_attn;
+    md.g_ffn = g_ffn;
+    md.g_final = g_final_d;
     hipFree(tmp_raw);
     tmp_raw = nullptr;
-
-    // partial-result buffers, one per GEMM shape: pieces never written stay zero
-    for (GemmPlan *p : plans) {
-        size_t n = (size_t)p->nKB * p->NT * p->MAXP * max_rows * 16;
-        if ((rc = dev_alloc(m->allocs, &p->part, n, true)) != EE_OK) return bail(rc);
-    }
-    if ((rc = dev_alloc(m->allocs, &m->dev_layers, m->layers.size(), false)) != EE_OK) return bail(rc);
-    if (hipMemcpy(m->dev_layers, m->layers.data(), m->layers.size() * sizeof(LayerDev), hipMemcpyHostToDevice) != hipSuccess)
-        return bail(fail(EE_EDEVICE, "upload of the layer table failed"));
-    md.layers = m->dev_layers;
     if ((rc = dev_alloc(m->allocs, &m->dev_md, 1, false)) != EE_OK) return bail(rc);
     if (hipMemcpy(m->dev_md, &md, sizeof md, hipMemcpyHostToDevice) != hipSuccess)
         return bail(fail(EE_EDEVICE, "upload of the model descriptor failed"));
@@ -415,11 +471,15 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 
 // ------------------------------------------------------------------ sessions
 
-static int attention_splits(const ee_model *m, int n_sess, int M)
+// Splits of the position range per attention unit: one while a single workgroup can
+// walk the cache of a head in a few microseconds, more for long contexts (then a
+// merge stage follows the attention stage).
+static int attention_splits(const ee_model *m, int n_sess, int M, int n_pos_max)
 {
+    if (n_pos_max <= 1536) return 1;
     int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     int units = n_sess * m->cfg.n_heads * chunks;
-    int s = m->nwg / std::max(units, 1);
+    int s = std::min((n_pos_max + 1023) / 1024, m->nwg / std::max(units, 1));
     return std::max(1, std::min(s, ATT_MAX_SPLITS));
 }
 
@@ -527,14 +587,9 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     const ModelDev &md = m->host_md;
     S_TRY(dev_alloc(s->allocs, &sc.h, (size_t)rows_max * d));
     S_TRY(dev_alloc(s->allocs, &sc.q, (size_t)rows_max * d));
-    S_TRY(dev_alloc(s->allocs, &sc.xn, (size_t)rows_max * md.Kpad_d));
-    S_TRY(dev_alloc(s->allocs, &sc.xh, (size_t)rows_max * md.Kpad_d));
     S_TRY(dev_alloc(s->allocs, &sc.attn, (size_t)rows_max * md.Kpad_d));
     S_TRY(dev_alloc(s->allocs, &sc.u, (size_t)rows_max * md.Kpad_F));
-    S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
-    S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
-        // attention partials: items <= max(units*splits) <= max(nwg, units); bound generously
         size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
         size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * 2;
         S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
@@ -542,8 +597,9 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     if (flags & EE_KEEP_LOGITS)
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
-    S_TRY(dev_alloc(s->allocs, &sc.bar, 1));
+    S_TRY(dev_alloc(s->allocs, &sc.bar_flags, (size_t)m->nwg));
     S_TRY(dev_alloc(s->allocs, &sc.err, 1));
+    s->epoch = 0;
     S_HIP(hipDeviceSynchronize());
 #undef S_TRY
 #undef S_HIP
@@ -587,25 +643,51 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
     sd.pad_ = 0;
 }
 
-// launches one segment: either one cooperative launch or one launch per phase
-static int launch_segment(const ee_session *lead, PassArgs &a)
+// host mirror of the kernels' stage list: [EMBED] { QKV ATT [MERGE] O GU DN } x layers [HEAD ACCEPT]
+static int stage_type(const PassArgs &a, int ph)
+{
+    const bool split = a.att_splits > 1;
+    const int per_layer = 5 + (split ? 1 : 0);
+    int idx = ph - (a.do_embed ? 1 : 0);
+    if (idx < 0) return ST_EMBED;
+    const int nl = a.layer_end - a.layer_begin;
+    if (idx < per_layer * nl) {
+        int r = idx % per_layer;
+        if (r == 0) return ST_GEMM;
+        if (r == 1) return ST_ATT;
+        if (split && r == 2) return ST_MERGE;
+        return ST_GEMM;
+    }
+    idx -= per_layer * nl;
+    if (a.head_kind != HEAD_NONE) return idx == 0 ? ST_GEMM : ST_ACCEPT;
+    return ST_NONE;
+}
+
+// Enqueues the stages of one segment.  Runs of consecutive GEMM stages go into one launch
+// of the chain kernel (grid barriers inside); with EE_PHASE_LAUNCHES every stage is a launch
+// of its own.  The chain kernel's barrier needs every workgroup resident: the grid is one
+// workgroup per compute unit and the LDS request keeps it to one per unit; the wait is
+// bounded, so a violated assumption ends in an error status, not in a hang.
+static int launch_segment(ee_session *lead, PassArgs &a)
 {
     const ee_model *m = lead->m;
-    int n_phases = (a.do_embed ? 1 : 0) + 10 * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 3 : 0);
-    if (n_phases == 0) return EE_OK;
-    if (lead->flags & EE_PHASE_LAUNCHES) {
-        for (int ph = 0; ph < n_phases; ++ph) {
-            a.ph_lo = ph;
-            a.ph_hi = ph + 1;
-            hipLaunchKernelGGL(ee_segment_kernel, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
-            HIP_TRY(hipGetLastError());
-        }
-    } else {
-        a.ph_lo = 0;
-        a.ph_hi = n_phases;
-        void *params[] = {&a};
-        HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(ee_segment_kernel), dim3(m->nwg),
-                                           dim3(WG_THREADS), params, (unsigned)m->lds_budget, lead->stream));
+    const int per_layer = 5 + (a.att_splits > 1 ? 1 : 0);
+    const int n_phases = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 2 : 0);
+    const bool single = (lead->flags & EE_PHASE_LAUNCHES) != 0;
+    int ph = 0;
+    while (ph < n_phases) {
+        const int type = stage_type(a, ph);
+        int end = ph + 1;
+        if (type == ST_GEMM && !single)
+            while (end < n_phases && stage_type(a, end) == ST_GEMM) ++end;
+        a.ph_lo = ph;
+        a.ph_hi = end;
+        a.epoch_base = lead->epoch;
+        pass_kernel_t k = type == ST_GEMM ? chain_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
+        hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
+        HIP_TRY(hipGetLastError());
+        lead->epoch += (unsigned)(end - ph - 1);
+        ph = end;
     }
     return EE_OK;
 }
@@ -617,7 +699,7 @@ static void base_args(const ee_session *lead, PassArgs &a)
     a.sc = lead->sc;
     a.nwg = lead->m->nwg;
     a.keep_logits = (lead->flags & EE_KEEP_LOGITS) ? 1 : 0;
-    a.spin_limit = 1u << 22;
+    a.spin_limit = 1u << 20;
     if (const char *e = getenv("EE_SPIN_LIMIT")) a.spin_limit = (unsigned)strtoul(e, nullptr, 10);
 }
 
@@ -705,7 +787,7 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
         a.head_kind = last ? HEAD_PREFILL : HEAD_NONE;
         a.head_idx = 0;
         a.head_gain = m->host_md.g_final;
-        a.att_splits = attention_splits(m, 1, rows);
+        a.att_splits = attention_splits(m, 1, rows, start + rows);
         a.sess = s->dev_sessdev;
         if ((rc = launch_segment(s, a)) != EE_OK) return rc;
     }
@@ -798,7 +880,11 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     a.M = M;
     a.rows = n_sessions * M;
     a.mode = 0;
-    a.att_splits = attention_splits(m, n_sessions, M);
+    {
+        int n_pos_max = 0;
+        for (int i = 0; i < n_sessions; ++i) n_pos_max = std::max(n_pos_max, sessions[i]->kv_len + M);
+        a.att_splits = attention_splits(m, n_sessions, M, n_pos_max);
+    }
     a.commit = 1;
     for (int i = 0; i < n_sessions; ++i) {
         fill_sessdev(lead->host_sessdev[i], sessions[i]);
@@ -988,16 +1074,14 @@ extern "C" int ee_debug_launch_cost(ee_session *s, int launches, int barriers, f
     base_args(s, a);
     a.mode = 2;
     a.layer_end = barriers;
+    a.rows = 1;
     a.sess = s->dev_sessdev;
-    void *params[] = {&a};
     HIP_TRY(hipStreamSynchronize(s->stream));
     HIP_TRY(hipEventRecord(s->ev_start, s->stream));
     for (int i = 0; i < launches; ++i) {
-        if (barriers > 0)
-            HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<const void *>(ee_segment_kernel), dim3(m->nwg),
-                                               dim3(WG_THREADS), params, (unsigned)m->lds_budget, s->stream));
-        else
-            hipLaunchKernelGGL(ee_segment_kernel, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, s->stream, a);
+        a.epoch_base = s->epoch;
+        hipLaunchKernelGGL(chain_kernel(1), dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, s->stream, a);
+        s->epoch += (unsigned)barriers;
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipEventRecord(s->ev_final, s->stream));
