@@ -8,7 +8,7 @@
 
 namespace ee {
 
-constexpr int WAVES = 16;                // waves per workgroup: four per SIMD keeps HBM busy
+constexpr int WAVES = 12;                // waves per workgroup: three per SIMD, 168 VGPRs each
 constexpr int WG_THREADS = WAVES * 64;
 constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
 constexpr int KV_PAGE = 16;              // positions per KV page
@@ -23,11 +23,14 @@ constexpr int ATT_MAX_SPLITS = 32;
 //
 // The N axis is cut into units of `tpu` n-tiles (1, or 2 for a gate/up pair);
 // workgroup g owns the units [U*g/nwg, U*(g+1)/nwg) for the whole of K, so every
-// output element is complete inside one workgroup.  The tiles of a workgroup
-// are stored contiguously in the order it streams them:
+// output element is complete inside one workgroup.  A workgroup walks its tiles
 //   for group (GRP n-tiles) : for K-block kb : for n-tile in group : for k-tile in block
-// where K-block kb covers the k-tiles [KT*kb/nKB, KT*(kb+1)/nKB).  Inside one
-// (K-block, n-tile) run of klen tiles, wave w takes [klen*w/16, klen*(w+1)/16).
+// where K-block kb covers the k-tiles [KT*kb/nKB, KT*(kb+1)/nKB); inside one
+// (K-block, n-tile) run of klen tiles, wave w takes [klen*w/WAVES, klen*(w+1)/WAVES).
+// In memory the tiles are interleaved over the whole chip: the i-th tile of the
+// sequence of wave w of workgroup g sits at tile slot (i*nwg + g)*WAVES + w, so at any
+// moment all waves together read one contiguous window (measured: up to 15 % more
+// HBM bandwidth than one contiguous range per wave).  `steps` is the longest sequence.
 struct GemmPlan {
     int N, K;        // logical shape (N counts rows after concatenation / interleaving)
     int NT, KT;      // tiles along N and K (K zero-padded to 32)
@@ -36,7 +39,7 @@ struct GemmPlan {
     int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
     int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
     int xs_stride;   // bf16 elements per staged row of x_hat
-    int pad_;
+    int steps;       // tile slots per wave (longest wave sequence)
 };
 
 enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };
@@ -66,14 +69,22 @@ struct SessDev {
     const int *drafts;                   // device copy of this pass's drafts
     ee_verify_result *result;            // device address of the pinned result block
     int n_pages;
+    int kv_len;                          // positions cached before this pass (host mirror of state[0])
+    int pending;                         // token of row 0 (host mirror of state[1])
     int pad_;
 };
 
 struct Scratch {
     float *h;            // [rows_max][d]        residual stream
     float *q;            // [rows_max][d]        queries after RoPE (pair-interleaved inside each head)
-    float *attn;         // [rows_max][Kpad_d]   attention output
-    float *u;            // [rows_max][Kpad_F]   silu(gate)*up
+    // GEMM inputs as two bf16 terms each (x = hi + lo up to ~16 mantissa bits), written by the
+    // stage that produces them: hi at [0], lo at [1]
+    uint16_t *xn[2];     // [rows_max][Kpad_d]   gain * h for the next QKV or gate/up GEMM
+    uint16_t *xh[2];     // [rows_max][Kpad_d]   head_gain * h for the LM head
+    uint16_t *attn[2];   // [rows_max][Kpad_d]   attention output
+    uint16_t *u[2];      // [rows_max][Kpad_F]   silu(gate)*up
+    float *ss_a;         // [nwg][rows_max]      partial sums of h^2 after the FFN block / embedding
+    float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
     float *att_part;     // attention partials (only when the position range is split)
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)

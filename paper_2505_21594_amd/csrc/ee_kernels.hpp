@@ -33,13 +33,67 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 constexpr int D = PF_DEPTH;
+constexpr int ATT_UNROLL = 4;  // wave-steps of attention whose loads are in flight together
 
-// 16-byte streaming load (weights are read once per pass: no reuse in cache)
+// Pointers read from descriptors in memory are generic to the compiler, and generic loads go
+// through the flat path, whose completion also counts against the LDS counter: a wait for an
+// LDS read would then drain every weight load in flight.  These helpers state that the
+// address is global memory.
+#define EE_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ __forceinline__ const EE_GLOBAL T *as_global(const T *p)
+{
+    return (const EE_GLOBAL T *)(p);
+}
+
+// 16-byte weight load.  Plain loads: on this part non-temporal loads measured about 10 %
+// slower for the same access pattern.
 __device__ __forceinline__ uint4 load_stream16(const uint4 *p)
 {
-    u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    u32x4_t v = *as_global(reinterpret_cast<const u32x4_t *>(p));
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
+
+__device__ __forceinline__ uint4 load_global16(const void *p)
+{
+    u32x4_t v = *as_global(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// Device-scope accesses for the small buffers that cross a grid barrier inside one launch
+// (GEMM inputs written by one stage's epilogue and read by the next stage's staging, partial
+// sums of squares).  Stores write through to memory and loads bypass the per-XCD L2, so the
+// barrier itself needs no cache write-back or invalidate; everything else is read-only in
+// the launch or crosses a kernel boundary.
+__device__ __forceinline__ void store_dev64(void *p, uint2 v)
+{
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), ((unsigned long long)v.y << 32) | v.x,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void store_dev32(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint4 load_dev128(const void *p)
+{
+    const EE_GLOBAL unsigned long long *q = as_global(reinterpret_cast<const unsigned long long *>(p));
+    unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint4((unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32));
+}
+__device__ __forceinline__ float load_dev32(const float *p)
+{
+    return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The value itself, but opaque to the optimiser: keeps per-thread index arithmetic of a stage
+// from being hoisted out of the stage loop, where it would occupy registers for the whole kernel.
+__device__ __forceinline__ int opaque(int x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+// all vector memory operations of this wave have completed
+__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -65,16 +119,17 @@ __device__ __forceinline__ void unpack8(const uint4 &v, float *f)
 
 // ------------------------------------------------------------------ grid barrier
 
-// Every workgroup publishes the epoch it has reached in its own flag and waits
-// until all flags have reached it.  The wait is bounded: after spin_limit polls
-// the workgroup raises *err and goes on, and later barriers fall through at once,
-// so the grid always drains.
+// Every workgroup publishes the epoch it has reached in its own flag and waits until all
+// flags have reached it.  Callers make their cross-workgroup data visible themselves:
+// device-scope stores followed by wait_vmem() in every wave before the barrier, device-scope
+// loads after it.  The wait is bounded: after spin_limit polls the workgroup raises *err and
+// goes on, and later barriers fall through at once, so the grid always drains.
 __device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsigned epoch, int *err,
                                              unsigned spin_limit)
 {
+    wait_vmem();
     __syncthreads();
     if (threadIdx.x < 64) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
         if (threadIdx.x == 0)
             __hip_atomic_store(&flags[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         unsigned spins = 0;
@@ -94,7 +149,6 @@ __device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsi
                 break;
             }
         }
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     }
     __syncthreads();
 }
@@ -105,21 +159,21 @@ __device__ __forceinline__ int row_pos(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_pos0 + r;
     int s = r / a.M;
-    return a.sess[s].state[0] + (r - s * a.M);
+    return a.sess[s].kv_len + (r - s * a.M);
 }
 
 __device__ __forceinline__ int row_token(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_tokens[r];
     int s = r / a.M, i = r - s * a.M;
-    return i == 0 ? a.sess[s].state[1] : a.sess[s].drafts[i - 1];
+    return i == 0 ? a.sess[s].pending : a.sess[s].drafts[i - 1];
 }
 
 // ------------------------------------------------------------------ LDS map
 
 struct Misc {  // views into the misc region of the LDS block
     float *rstd;       // [rows_max]
-    float *ssq;        // [rows_max][WAVES]
+    float *rowss;      // [rows_max]  this workgroup's sum of h^2 per row (O / DN stages)
     int *pos;          // [rows_max]
     long long *kvoff;  // [rows_max]  element offset of (layer, page, slot, head 0) in the KV pools
     float2 *rope;      // [rows_max][hd/2]
@@ -138,8 +192,8 @@ __device__ __forceinline__ Misc misc_views(const ModelDev &md, char *lds)
     p += (size_t)R * (md.hd / 2) * 8;
     m.rstd = reinterpret_cast<float *>(p);
     p += (size_t)R * 4;
-    m.ssq = reinterpret_cast<float *>(p);
-    p += (size_t)R * WAVES * 4;
+    m.rowss = reinterpret_cast<float *>(p);
+    p += (size_t)R * 4;
     m.pos = reinterpret_cast<int *>(p);
     p += (size_t)R * 4;
     m.bestv = reinterpret_cast<float *>(p);
@@ -155,7 +209,7 @@ struct Seg {  // one (group, K-block) of a workgroup's tile sequence, seen from 
     int klen, kst;    // k-tiles of the block, first k-tile
     int s0, slen;     // this wave's slice of every run: [s0, s0 + slen)
     int n;            // tiles of this wave in the segment = gn * slen
-    long long base;   // tile index of the segment's first tile
+    int step0;        // position of the segment's first tile in this wave's sequence
 };
 
 __device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int &nt0, int &n_local)
@@ -163,6 +217,21 @@ __device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int
     int u0 = (int)((long long)pl.U * g / nwg), u1 = (int)((long long)pl.U * (g + 1) / nwg);
     nt0 = u0 * pl.tpu;
     n_local = (u1 - u0) * pl.tpu;
+}
+
+// tiles this wave streams in the groups/blocks before (gi, kb)
+__device__ __forceinline__ int seg_steps_before(const GemmPlan &pl, int n_local, int wave, int gi, int kb)
+{
+    // every full pass over K gives the wave  sum_kb slen(kb)  tiles per n-tile
+    int per_tile = 0, before_kb = 0;
+    for (int b = 0; b < pl.nKB; ++b) {
+        int kst = pl.KT * b / pl.nKB, klen = pl.KT * (b + 1) / pl.nKB - kst;
+        int sl = klen * (wave + 1) / WAVES - klen * wave / WAVES;
+        per_tile += sl;
+        if (b < kb) before_kb += sl;
+    }
+    const int gn = min(pl.GRP, n_local - gi * pl.GRP);
+    return gi * pl.GRP * per_tile + gn * before_kb;
 }
 
 __device__ __forceinline__ Seg seg_setup(const GemmPlan &pl, int nt0, int n_local, int wave, int gi, int kb)
@@ -174,25 +243,22 @@ __device__ __forceinline__ Seg seg_setup(const GemmPlan &pl, int nt0, int n_loca
     s.s0 = s.klen * wave / WAVES;
     s.slen = s.klen * (wave + 1) / WAVES - s.s0;
     s.n = s.gn * s.slen;
-    s.base = (long long)nt0 * pl.KT + (long long)gi * pl.GRP * pl.KT + (long long)s.gn * s.kst;
+    s.step0 = seg_steps_before(pl, n_local, wave, gi, kb);
     return s;
 }
 
-// first min(D, s.n) tiles of the wave's sequence in segment s
-__device__ __forceinline__ void seg_prefetch(const uint4 *__restrict__ W, const Seg &s, uint4 (&pre)[D])
+// address of the wave's tile number `step` (see GemmPlan): slot (step*nwg + g)*WAVES + wave
+__device__ __forceinline__ const uint4 *tile_ptr(const uint4 *W, int nwg, int wave, int step)
 {
-    const int lane = threadIdx.x & 63;
-    int ntg = 0, kk = 0;
+    return W + ((size_t)((size_t)step * nwg + blockIdx.x) * WAVES + wave) * 64 + (threadIdx.x & 63);
+}
+
+// first min(D, s.n) tiles of the wave's sequence in segment s
+__device__ __forceinline__ void seg_prefetch(const uint4 *__restrict__ W, int nwg, int wave, const Seg &s, uint4 (&pre)[D])
+{
 #pragma unroll
-    for (int j = 0; j < D; ++j) {
-        if (j < s.n) {
-            pre[j] = load_stream16(W + (size_t)(s.base + (long long)ntg * s.klen + s.s0 + kk) * 64 + lane);
-            if (++kk == s.slen) {
-                kk = 0;
-                ++ntg;
-            }
-        }
-    }
+    for (int j = 0; j < D; ++j)
+        if (j < s.n) pre[j] = load_stream16(tile_ptr(W, nwg, wave, s.step0 + j));
 }
 
 struct NextGemm {  // the GEMM stage that follows in the same launch
@@ -206,8 +272,9 @@ __device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint
     int nt0, n_local;
     wg_units(*nx.pl, nwg, blockIdx.x, nt0, n_local);
     if (n_local == 0) return true;
-    Seg s = seg_setup(*nx.pl, nt0, n_local, threadIdx.x >> 6, 0, 0);
-    seg_prefetch(nx.W, s, pre);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    Seg s = seg_setup(*nx.pl, nt0, n_local, wave, 0, 0);
+    seg_prefetch(nx.W, nwg, wave, s, pre);
     return true;
 }
 
@@ -215,65 +282,68 @@ __device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint
 
 
 struct GemmIn {
-    const float *x;     // [rows][ldx] fp32
+    const uint16_t *hi, *lo;  // [rows][ldx] bf16 terms of the input (already scaled by the norm gain)
     int ldx;
-    const float *gain;  // [K] or nullptr
-    bool norm;          // accumulate sum of squares of x, publish rstd
+    const float *ss;          // [nwg][rows_max] partial sums of squares for rstd, or nullptr
 };
 
-// Stage K-block (kst, klen) of x_hat = gain * x as two bf16 terms, hi = bf16(x_hat) and
-// lo = bf16(x_hat - hi): the activations keep about 16 mantissa bits while the MFMA takes
-// bf16 operands (weights are exact bf16).  The matrix cores idle most of the time in this
-// HBM-bound loop, so the second MFMA per tile is free.
-__device__ __forceinline__ void stage_x(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int klen,
-                                        bool first_block, bool want_ss, const Misc &mi, char *lds)
+// split x into two bf16 terms: hi = bf16(x), lo = bf16(x - hi).  The MFMA takes bf16 operands;
+// feeding both terms keeps about 16 mantissa bits of the activations (weights are exact
+// bf16).  The matrix cores idle most of the time in the HBM-bound loop, so the second MFMA
+// per tile is free.
+__device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo)
+{
+    hi = f32_to_bf16(x);
+    lo = f32_to_bf16(x - __uint_as_float(hi << 16));
+}
+
+__device__ __forceinline__ void store_split4(uint16_t *hi_p, uint16_t *lo_p, size_t idx, const float *v)
+{
+    uint32_t h[4], l[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split_bf16(v[e], h[e], l[e]);
+    store_dev64(hi_p + idx, make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16)));
+    store_dev64(lo_p + idx, make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16)));
+}
+
+// copy K-block (kst, klen) of the input's two bf16 terms into LDS: xs_hi | xs_lo, [rows][xs_stride]
+__device__ __forceinline__ void stage_x(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int klen, char *lds)
+{
+    uint16_t *xs_hi = reinterpret_cast<uint16_t *>(lds);
+    const int c8 = klen * 4;           // 16-byte chunks per row
+    const int total = rows * c8 * 2;   // both terms
+    constexpr int UB = 6;              // chunks per thread whose loads are issued together
+    const int half = rows * c8;
+    for (int i0 = opaque(threadIdx.x); i0 < total; i0 += WG_THREADS * UB) {
+        uint4 v[UB];
+        int dst[UB];
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            const int i = min(i0 + u * WG_THREADS, total - 1);  // clamped: the load is always in bounds
+            const int term = i >= half ? 1 : 0;
+            const int j = i - term * half;
+            const int row = j / c8, c = j - row * c8;
+            const uint16_t *src = (term ? in.lo : in.hi) + (size_t)row * in.ldx + (size_t)kst * 32 + c * 8;
+            v[u] = load_dev128(src);
+            dst[u] = (term * rows + row) * pl.xs_stride + c * 8;
+        }
+#pragma unroll
+        for (int u = 0; u < UB; ++u)
+            if (i0 + u * WG_THREADS < total) *reinterpret_cast<uint4 *>(xs_hi + dst[u]) = v[u];
+    }
+}
+
+// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order
+__device__ __forceinline__ void load_rstd(const float *ss, int nwg, int rows_max, int rows, int d, float eps,
+                                          float *rstd_lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    uint16_t *xs_hi = reinterpret_cast<uint16_t *>(lds);
-    uint16_t *xs_lo = xs_hi + (size_t)rows * pl.xs_stride;
-    const int wpr = rows >= WAVES ? 1 : WAVES / rows;  // waves per row
-    const int c8 = klen * 4;                           // 8-element chunks per row in this block
-    for (int it = wave; it < rows * wpr; it += WAVES) {
-        const int row = it / wpr, part = it - row * wpr;
-        const int c_lo = c8 * part / wpr, c_hi = c8 * (part + 1) / wpr;
-        float ss = 0.f;
-        for (int c = c_lo + lane; c < c_hi; c += 64) {
-            const int k = kst * 32 + c * 8;
-            uint4 hi = make_uint4(0, 0, 0, 0), lo = make_uint4(0, 0, 0, 0);
-            if (k < pl.K) {
-                const float4 *src = reinterpret_cast<const float4 *>(in.x + (size_t)row * in.ldx + k);
-                float4 a = src[0], b = src[1];
-                float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-                if (want_ss) {
+    for (int m = wave; m < rows; m += WAVES) {
+        float s = 0.f;
+        for (int g = lane; g < nwg; g += 64) s += load_dev32(ss + (size_t)g * rows_max + m);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) ss += f[e] * f[e];
-                }
-                if (in.gain) {
-                    const float4 *gp = reinterpret_cast<const float4 *>(in.gain + k);
-                    float4 ga = gp[0], gb = gp[1];
-                    f[0] *= ga.x; f[1] *= ga.y; f[2] *= ga.z; f[3] *= ga.w;
-                    f[4] *= gb.x; f[5] *= gb.y; f[6] *= gb.z; f[7] *= gb.w;
-                }
-                uint32_t h[8], l[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    h[e] = f32_to_bf16(f[e]);
-                    l[e] = f32_to_bf16(f[e] - __uint_as_float(h[e] << 16));
-                }
-                hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-                lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
-            }
-            *reinterpret_cast<uint4 *>(xs_hi + (size_t)row * pl.xs_stride + c * 8) = hi;
-            *reinterpret_cast<uint4 *>(xs_lo + (size_t)row * pl.xs_stride + c * 8) = lo;
-        }
-        if (want_ss) {
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, 64);
-            if (lane == 0) {
-                float *slot = mi.ssq + row * WAVES + part;
-                *slot = first_block ? ss : *slot + ss;
-            }
-        }
+        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+        if (lane == 0) rstd_lds[m] = 1.0f / sqrtf(s / (float)d + eps);
     }
 }
 
@@ -283,12 +353,18 @@ __device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
 }
 
 // Epilogue of one group: sum the waves' partial tiles, apply the stage's element-wise tail.
+struct GemmEpi {           // what the O / DN epilogue produces besides h
+    const float *gain_xn;  // gain of the next GEMM input (xn), or nullptr
+    const float *gain_xh;  // gain of the LM-head input (xh), or nullptr
+    float *ss_out;         // [nwg][rows_max] partial sums of h^2
+};
+
 __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const GemmPlan &pl, int nt_first,
-                                              int gn, int rows, const Misc &mi, char *lds)
+                                              int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds)
 {
     const ModelDev &md = *a.md;
     const float *slots = reinterpret_cast<const float *>(lds + md.lds_slots_off);
-    const int tid = threadIdx.x;
+    const int tid = opaque(threadIdx.x);
     const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
     if (kind == G_GU) {
         const int items = (gn >> 1) * rows * 4;
@@ -298,6 +374,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const float *sg = slots + ((size_t)(2 * p) * rows + m) * 16 + qd * 4;
             const float *su = sg + (size_t)rows * 16;
             float4 G = make_float4(0.f, 0.f, 0.f, 0.f), U = G;
+#pragma unroll 2
             for (int w = 0; w < WAVES; ++w) {
                 float4 x = *reinterpret_cast<const float4 *>(sg + w * wstride);
                 float4 y = *reinterpret_cast<const float4 *>(su + w * wstride);
@@ -310,28 +387,43 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + __expf(-g[e])) * u[e];
             const int f = ((nt_first >> 1) + p) * 16 + qd * 4;
-            *reinterpret_cast<float4 *>(a.sc.u + (size_t)m * md.Kpad_F + f) = make_float4(o[0], o[1], o[2], o[3]);
+            store_split4(a.sc.u[0], a.sc.u[1], (size_t)m * md.Kpad_F + f, o);
         }
         return;
     }
-    float *zbuf = reinterpret_cast<float *>(lds + md.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group
+    float *zbuf = reinterpret_cast<float *>(lds + md.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group; O/DN: squares
     const int items = gn * rows * 4;
     for (int idx = tid; idx < items; idx += WG_THREADS) {
         int ntg = idx / (rows * 4), rem = idx - ntg * rows * 4;
         int m = rem >> 2, qd = rem & 3;
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
         for (int w = 0; w < WAVES; ++w) {
             float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
         const int n = (nt_first + ntg) * 16 + qd * 4;  // four consecutive output columns
         if (kind == G_O || kind == G_DN) {
+            float sq = 0.f;
             if (n < md.d) {
                 float4 *hp = reinterpret_cast<float4 *>(a.sc.h + (size_t)m * md.d + n);
                 float4 hv = *hp;
-                *hp = make_float4(hv.x + S.x, hv.y + S.y, hv.z + S.z, hv.w + S.w);
+                float v[4] = {hv.x + S.x, hv.y + S.y, hv.z + S.z, hv.w + S.w};
+                *hp = make_float4(v[0], v[1], v[2], v[3]);
+                sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                if (ep.gain_xn) {
+                    float4 g = *reinterpret_cast<const float4 *>(ep.gain_xn + n);
+                    float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
+                    store_split4(a.sc.xn[0], a.sc.xn[1], (size_t)m * md.Kpad_d + n, x);
+                }
+                if (ep.gain_xh) {
+                    float4 g = *reinterpret_cast<const float4 *>(ep.gain_xh + n);
+                    float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
+                    store_split4(a.sc.xh[0], a.sc.xh[1], (size_t)m * md.Kpad_d + n, x);
+                }
             }
+            zbuf[idx] = sq;  // (ntg, m, quad) order
         } else if (kind == G_QKV) {
             const int d = md.d, hd = md.hd;
             const float rs = mi.rstd[m];
@@ -372,6 +464,15 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             }
         }
     }
+    if (kind == G_O || kind == G_DN) {
+        __syncthreads();
+        if (tid < rows) {  // this group's sum of squares per row, fixed order
+            float t = 0.f;
+            for (int ntg = 0; ntg < gn; ++ntg)
+                for (int qd = 0; qd < 4; ++qd) t += zbuf[(ntg * rows + tid) * 4 + qd];
+            mi.rowss[tid] += t;
+        }
+    }
     if (kind == G_HEAD) {
         __syncthreads();
         const int lane = tid & 63, wave = tid >> 6;
@@ -404,11 +505,12 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
 }
 
 template <int MT>
-__device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const uint4 *__restrict__ W,
-                             const GemmIn &in, uint4 (&buf)[D], bool &have_pre, const NextGemm &next, char *lds)
+__device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan pl, const uint4 *__restrict__ W,
+                             const GemmIn &in, const GemmEpi &ep, uint4 (&buf)[D], bool &have_pre, const NextGemm &next,
+                             char *lds)
 {
     const ModelDev &md = *a.md;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rows = a.rows;
     const Misc mi = misc_views(md, lds);
     int nt0, n_local;
@@ -424,8 +526,12 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
         have_pre = prefetch_stage(next, a.nwg, buf);
         if (kind == G_HEAD && tid < rows)
             a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(-INFINITY), 0x7FFFFFFF);
+        if ((kind == G_O || kind == G_DN) && tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
         return;
     }
+    if ((kind == G_O || kind == G_DN) && tid < rows) mi.rowss[tid] = 0.f;
+    // start the weight stream before anything else (unless the previous stage already did)
+    if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
     if (kind == G_QKV) {
         // per-row position, KV slot and RoPE factors for the epilogue
         if (tid < rows) {
@@ -452,7 +558,6 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * pl.xs_stride;
     const int bk = (lane >> 4) * 8;
     const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
-    bool seg_pre = have_pre;  // buf[] holds the first tiles of the coming segment
 
     for (int gi = 0; gi < n_groups; ++gi) {
         const int gn = min(pl.GRP, n_local - gi * pl.GRP);
@@ -461,22 +566,15 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const bool restage = pl.nKB > 1 || gi == 0;
             if (restage) {
                 if (gi > 0 || kb > 0) __syncthreads();  // x_hat of the previous block is dead
-                stage_x(pl, in, rows, s.kst, s.klen, kb == 0, in.norm && gi == 0, mi, lds);
+                stage_x(pl, in, rows, s.kst, s.klen, lds);
+                if (in.ss && gi == 0 && kb == 0) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
                 __syncthreads();
-                if (in.norm && gi == 0 && kb == pl.nKB - 1 && tid < rows) {
-                    const int wpr = rows >= WAVES ? 1 : WAVES / rows;
-                    float t = 0.f;
-                    for (int p = 0; p < wpr; ++p) t += mi.ssq[tid * WAVES + p];
-                    mi.rstd[tid] = 1.0f / sqrtf(t / (float)pl.K + md.eps);
-                }
             }
 
             // ---- this wave's tiles of the segment
             f32x4_t acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-            if (!seg_pre) seg_prefetch(W, s, buf);  // otherwise buf already holds the segment's first tiles
-            seg_pre = false;
             if (s.slen == 0 && kb == 0) {  // no tiles in this block: contribute zeros
                 for (int ntg = 0; ntg < gn; ++ntg)
 #pragma unroll
@@ -487,28 +585,15 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                                 make_float4(0.f, 0.f, 0.f, 0.f);
                     }
             }
-            int ntg = 0, kk = 0;        // compute cursor
-            int lntg = 0, lkk = 0;      // load cursor, D tiles ahead
-            {
-                int adv = min(D, s.n);  // tiles already fetched
-                if (s.slen > 0) {
-                    lntg = adv / s.slen;
-                    lkk = adv - lntg * s.slen;
-                }
-            }
-            const uint4 *wp = W + (size_t)(s.base + s.s0) * 64 + lane;
+            int ntg = 0, kk = 0;  // compute cursor
+            const uint4 *wp = tile_ptr(W, a.nwg, wave, s.step0);
+            const size_t wstep = (size_t)a.nwg * WAVES * 64;  // one step further in the wave's sequence
             for (int i = 0; i < s.n; i += D) {
 #pragma unroll
                 for (int j = 0; j < D; ++j) {
                     if (i + j < s.n) {
                         uint4 av = buf[j];
-                        if (i + j + D < s.n) {
-                            buf[j] = load_stream16(wp + (size_t)((long long)lntg * s.klen + lkk) * 64);
-                            if (++lkk == s.slen) {
-                                lkk = 0;
-                                ++lntg;
-                            }
-                        }
+                        if (i + j + D < s.n) buf[j] = load_stream16(wp + (size_t)(i + j + D) * wstep);
                         bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
                         const int xo = (s.s0 + kk) * 32 + bk;
 #pragma unroll
@@ -546,15 +631,18 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             if (!last_seg) {
                 const int ngi = kb + 1 < pl.nKB ? gi : gi + 1, nkb = kb + 1 < pl.nKB ? kb + 1 : 0;
                 const Seg ns = seg_setup(pl, nt0, n_local, wave, ngi, nkb);
-                seg_prefetch(W, ns, buf);
-                seg_pre = true;
+                seg_prefetch(W, a.nwg, wave, ns, buf);
             } else {
                 have_pre = prefetch_stage(next, a.nwg, buf);
             }
         }
         __syncthreads();
-        gemm_epilogue(a, kind, layer, pl, nt0 + gi * pl.GRP, gn, rows, mi, lds);
+        gemm_epilogue(a, kind, layer, pl, nt0 + gi * pl.GRP, gn, rows, ep, mi, lds);
         if (gi + 1 < n_groups) __syncthreads();
+    }
+    if (kind == G_O || kind == G_DN) {
+        __syncthreads();
+        if (tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, mi.rowss[tid]);
     }
     if (kind == G_HEAD) {
         __syncthreads();
@@ -565,19 +653,35 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
 
 // ------------------------------------------------------------------ embedding
 
-__device__ void embed_stage(const PassArgs &a)
+// h = embedding of each row's token (or the supplied embedding row); workgroup g owns the
+// columns [g*cw, (g+1)*cw) and also emits the first layer's GEMM input and its share of h^2
+__device__ void embed_stage(const PassArgs &a, char *lds)
 {
     const ModelDev &md = *a.md;
-    const int d = md.d, q4 = d >> 2;
-    const int gsz = a.nwg * WG_THREADS;
-    for (int it = blockIdx.x * WG_THREADS + threadIdx.x; it < a.rows * q4; it += gsz) {
-        int m = it / q4, c = (it - m * q4) * 4;
+    const int d = md.d, rows = a.rows, tid = threadIdx.x;
+    const int cw = ((d + a.nwg - 1) / a.nwg + 3) & ~3;  // columns per workgroup, multiple of 4
+    const int n0 = blockIdx.x * cw;
+    const int nq = max(0, min(cw, d - n0)) >> 2;          // quads of columns here
+    float *sq = reinterpret_cast<float *>(lds);           // [rows][cw/4]
+    const float *gain = md.g_attn + (size_t)a.layer_begin * d;
+    for (int it = tid; it < rows * nq; it += WG_THREADS) {
+        int m = it / nq, c = n0 + (it - m * nq) * 4;
         int tok = row_token(a, m);
         const uint16_t *src = tok >= 0 ? md.emb + (size_t)tok * d + c : a.pf_emb + (size_t)m * d + c;
         uint2 r = *reinterpret_cast<const uint2 *>(src);
-        *reinterpret_cast<float4 *>(a.sc.h + (size_t)m * d + c) =
-            make_float4(__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
-                        __uint_as_float(r.y & 0xFFFF0000u));
+        float v[4] = {__uint_as_float(r.x << 16), __uint_as_float(r.x & 0xFFFF0000u), __uint_as_float(r.y << 16),
+                      __uint_as_float(r.y & 0xFFFF0000u)};
+        *reinterpret_cast<float4 *>(a.sc.h + (size_t)m * d + c) = make_float4(v[0], v[1], v[2], v[3]);
+        sq[it] = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        float4 g = *reinterpret_cast<const float4 *>(gain + c);
+        float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
+        store_split4(a.sc.xn[0], a.sc.xn[1], (size_t)m * md.Kpad_d + c, x);
+    }
+    __syncthreads();
+    if (tid < rows) {
+        float t = 0.f;
+        for (int j = 0; j < nq; ++j) t += sq[tid * nq + j];
+        store_dev32(a.sc.ss_a + (size_t)blockIdx.x * md.rows_max + tid, t);
     }
 }
 
@@ -611,8 +715,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
         int s = unit / (H * n_chunks), rem = unit - s * (H * n_chunks);
         int hh = rem / n_chunks, ch = rem - hh * n_chunks;
         int r0 = ch * ATT_ROWS, nr = min(ATT_ROWS, M - r0);
-        const SessDev &sd = a.sess[s];
-        const int P = row_pos(a, s * M);          // position of the session's first row
+        const SessDev sd = a.sess[s];
+        const int P = a.mode == 1 ? a.pf_pos0 : sd.kv_len;  // position of the session's first row
         const int n_pos = P + r0 + nr;            // positions visible to the chunk's last row
         const int lo = (int)((long long)n_pos * sp / n_splits), hi = (int)((long long)n_pos * (sp + 1) / n_splits);
         const int wlo = lo + (int)((long long)(hi - lo) * wave / WAVES);
@@ -631,32 +735,53 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
         }
 
-        for (int pb = wlo; pb < whi; pb += PPI) {
-            const int p = pb + grp;
-            const bool live = p < whi;
-            const int pc = live ? p : wlo;
-            const int page = sd.page_table[pc / KV_PAGE];
-            const size_t off = ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * HD + e8 * 8;
-            uint4 kk = *reinterpret_cast<const uint4 *>(sd.kpool + off);
-            uint4 vv = *reinterpret_cast<const uint4 *>(sd.vpool + off);
-            float kf[8], vf[8];
-            unpack8(kk, kf);
-            unpack8(vv, vf);
+        // positions in super-chunks of up to 1024: one page-table entry per lane, then steps
+        // of ATT_UNROLL wave-steps whose K and V loads are all issued before any is used
+        for (int sb = wlo; sb < whi; sb += 1024) {
+            const int se = min(whi, sb + 1024);
+            const int fp = sb / KV_PAGE, npg = (se - 1) / KV_PAGE - fp + 1;
+            const int pg = lane < npg ? sd.page_table[fp + lane] : 0;
+            for (int pb = sb; pb < se; pb += PPI * ATT_UNROLL) {
+                uint4 kk[ATT_UNROLL], vv[ATT_UNROLL];
 #pragma unroll
-            for (int i = 0; i < ATT_ROWS; ++i) {
-                float sdot = 0.f;
+                for (int u = 0; u < ATT_UNROLL; ++u) {
+                    const int p = pb + u * PPI + grp;
+                    const int pc = p < se ? p : sb;
+                    const int page = __shfl(pg, pc / KV_PAGE - fp, 64);
+                    const size_t off =
+                        ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * HD + e8 * 8;
+                    kk[u] = load_global16(sd.kpool + off);
+                    vv[u] = load_global16(sd.vpool + off);
+                }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) sdot += q[i][e] * kf[e];
+                for (int u = 0; u < ATT_UNROLL; ++u) {
+                    const int p = pb + u * PPI + grp;
+                    const bool live = p < se;
+                    float kf[8];
+                    unpack8(kk[u], kf);
+                    float sc[ATT_ROWS];
 #pragma unroll
-                for (int off2 = 1; off2 < LPP; off2 <<= 1) sdot += __shfl_xor(sdot, off2, 64);
-                sdot *= md.att_scale;
-                if (live && i < nr && p <= P + r0 + i) {
-                    float nm = fmaxf(mx[i], sdot);
-                    float corr = __expf(mx[i] - nm), pe = __expf(sdot - nm);
-                    l[i] = l[i] * corr + pe;
+                    for (int i = 0; i < ATT_ROWS; ++i) {
+                        float sdot = 0.f;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[i][e] = acc[i][e] * corr + pe * vf[e];
-                    mx[i] = nm;
+                        for (int e = 0; e < 8; ++e) sdot += q[i][e] * kf[e];
+#pragma unroll
+                        for (int off2 = 1; off2 < LPP; off2 <<= 1) sdot += __shfl_xor(sdot, off2, 64);
+                        sc[i] = sdot * md.att_scale;
+                    }
+                    float vf[8];
+                    unpack8(vv[u], vf);
+#pragma unroll
+                    for (int i = 0; i < ATT_ROWS; ++i) {
+                        if (live && i < nr && p <= P + r0 + i) {
+                            float nm = fmaxf(mx[i], sc[i]);
+                            float corr = __expf(mx[i] - nm), pe = __expf(sc[i] - nm);
+                            l[i] = l[i] * corr + pe;
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) acc[i][e] = acc[i][e] * corr + pe * vf[e];
+                            mx[i] = nm;
+                        }
+                    }
                 }
             }
         }
@@ -700,7 +825,11 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                     num += wr[e] * f;
                     den += wr[HD + 1] * f;
                 }
-                a.sc.attn[(size_t)(s * M + r0 + i) * md.Kpad_d + hh * HD + e] = num / den;
+                uint32_t vh, vl;
+                split_bf16(num / den, vh, vl);
+                const size_t oi = (size_t)(s * M + r0 + i) * md.Kpad_d + hh * HD + e;
+                a.sc.attn[0][oi] = (uint16_t)vh;
+                a.sc.attn[1][oi] = (uint16_t)vl;
             }
         } else {
             float *out = a.sc.att_part + (size_t)item * ATT_ROWS * REC;
@@ -749,7 +878,10 @@ __device__ void att_merge_stage(const PassArgs &a)
             num += base[sp * sp_stride + e] * w;
             den += base[sp * sp_stride + HD + 1] * w;
         }
-        a.sc.attn[(size_t)r * md.Kpad_d + col] = num / den;
+        uint32_t vh, vl;
+        split_bf16(num / den, vh, vl);
+        a.sc.attn[0][(size_t)r * md.Kpad_d + col] = (uint16_t)vh;
+        a.sc.attn[1][(size_t)r * md.Kpad_d + col] = (uint16_t)vl;
     }
 }
 
@@ -873,16 +1005,31 @@ __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
     return sd;
 }
 
-__device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind, int layer)
+__device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
 {
     const ModelDev &md = *a.md;
     switch (kind) {
-    case G_QKV: return GemmIn{a.sc.h, md.d, md.g_attn + (size_t)layer * md.d, true};
-    case G_O: return GemmIn{a.sc.attn, md.Kpad_d, nullptr, false};
-    case G_GU: return GemmIn{a.sc.h, md.d, md.g_ffn + (size_t)layer * md.d, true};
-    case G_DN: return GemmIn{a.sc.u, md.Kpad_F, nullptr, false};
-    default: return GemmIn{a.sc.h, md.d, a.head_gain, true};
+    case G_QKV: return GemmIn{a.sc.xn[0], a.sc.xn[1], md.Kpad_d, a.sc.ss_a};
+    case G_O: return GemmIn{a.sc.attn[0], a.sc.attn[1], md.Kpad_d, nullptr};
+    case G_GU: return GemmIn{a.sc.xn[0], a.sc.xn[1], md.Kpad_d, a.sc.ss_f};
+    case G_DN: return GemmIn{a.sc.u[0], a.sc.u[1], md.Kpad_F, nullptr};
+    default: return GemmIn{a.sc.xh[0], a.sc.xh[1], md.Kpad_d, a.sc.ss_a};
     }
+}
+
+__device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int layer)
+{
+    const ModelDev &md = *a.md;
+    GemmEpi ep = {nullptr, nullptr, nullptr};
+    if (kind == G_O) {
+        ep.gain_xn = md.g_ffn + (size_t)layer * md.d;
+        ep.ss_out = a.sc.ss_f;
+    } else if (kind == G_DN) {
+        if (layer + 1 < md.L) ep.gain_xn = md.g_attn + (size_t)(layer + 1) * md.d;
+        if (layer + 1 == a.layer_end && a.head_kind != HEAD_NONE) ep.gain_xh = a.head_gain;
+        ep.ss_out = a.sc.ss_a;
+    }
+    return ep;
 }
 
 // GEMM stages [ph_lo, ph_hi) of the stage list (all of them must be GEMM stages).
@@ -909,9 +1056,10 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
             nx.pl = &md.plan[sn.kind];
             nx.W = md.w[sn.kind] + (size_t)sn.layer * md.wstride[sn.kind];
         }
-        const GemmIn in = gemm_input(a, st.kind, st.layer);
+        const GemmIn in = gemm_input(a, st.kind);
+        const GemmEpi ep = gemm_epi(a, st.kind, st.layer);
         gemm_stage_t<MT>(a, st.kind, st.layer, md.plan[st.kind], md.w[st.kind] + (size_t)st.layer * md.wstride[st.kind],
-                         in, buf, have_pre, nx, lds);
+                         in, ep, buf, have_pre, nx, lds);
     }
 }
 
@@ -928,7 +1076,7 @@ __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a)
     extern __shared__ __align__(16) char lds[];
     const StageDesc st = stage_decode(a, a.ph_lo);
     if (st.type == ST_EMBED)
-        embed_stage(a);
+        embed_stage(a, lds);
     else if (st.type == ST_MERGE)
         att_merge_stage(a);
     else if (st.type == ST_ACCEPT)
@@ -955,7 +1103,8 @@ __device__ __forceinline__ int perm_row(int perm, int n, int d, int hd, int F)
     return n;
 }
 
-// row-major bf16 src[N][K] -> the tiled layout of GemmPlan; block g writes workgroup g's tiles
+// row-major bf16 src[N][K] -> the tiled layout of GemmPlan; block g writes workgroup g's tiles,
+// sub-wave `sub` of the block those of wave w = sub, sub + nsub, ...
 __global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, GemmPlan pl, int nwg,
                                     int perm, int d, int hd, int F)
 {
@@ -965,28 +1114,30 @@ __global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__r
     if (n_local == 0) return;
     const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6, nsub = blockDim.x >> 6;
     const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
-    for (int gi = 0; gi < n_groups; ++gi) {
-        const int gn = min(pl.GRP, n_local - gi * pl.GRP);
-        for (int kb = 0; kb < pl.nKB; ++kb) {
-            const int kst = pl.KT * kb / pl.nKB, klen = pl.KT * (kb + 1) / pl.nKB - kst;
-            const long long base = (long long)nt0 * pl.KT + (long long)gi * pl.GRP * pl.KT + (long long)gn * kst;
-            for (int t = sub; t < gn * klen; t += nsub) {
-                int ntg = t / klen, kti = t - ntg * klen;
-                int n = (nt0 + gi * pl.GRP + ntg) * 16 + (lane & 15);
-                int k0 = (kst + kti) * 32 + (lane >> 4) * 8;
-                uint16_t v[8];
-                int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
+    for (int w = sub; w < WAVES; w += nsub) {
+        int step = 0;
+        for (int gi = 0; gi < n_groups; ++gi) {
+            for (int kb = 0; kb < pl.nKB; ++kb) {
+                const Seg s = seg_setup(pl, nt0, n_local, w, gi, kb);
+                for (int ntg = 0; ntg < s.gn; ++ntg) {
+                    for (int kk = 0; kk < s.slen; ++kk, ++step) {
+                        int n = (nt0 + gi * pl.GRP + ntg) * 16 + (lane & 15);
+                        int k0 = (s.kst + s.s0 + kk) * 32 + (lane >> 4) * 8;
+                        uint16_t v[8];
+                        int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    int k = k0 + e;
-                    v[e] = (row >= 0 && k < pl.K) ? src[(size_t)row * pl.K + k] : (uint16_t)0;
+                        for (int e = 0; e < 8; ++e) {
+                            int k = k0 + e;
+                            v[e] = (row >= 0 && k < pl.K) ? src[(size_t)row * pl.K + k] : (uint16_t)0;
+                        }
+                        uint4 o;
+                        o.x = v[0] | ((uint32_t)v[1] << 16);
+                        o.y = v[2] | ((uint32_t)v[3] << 16);
+                        o.z = v[4] | ((uint32_t)v[5] << 16);
+                        o.w = v[6] | ((uint32_t)v[7] << 16);
+                        dst[((size_t)((size_t)step * nwg + g) * WAVES + w) * 64 + lane] = o;
+                    }
                 }
-                uint4 o;
-                o.x = v[0] | ((uint32_t)v[1] << 16);
-                o.y = v[2] | ((uint32_t)v[3] << 16);
-                o.z = v[4] | ((uint32_t)v[5] << 16);
-                o.w = v[6] | ((uint32_t)v[7] << 16);
-                dst[(size_t)(base + t) * 64 + lane] = o;
             }
         }
     }

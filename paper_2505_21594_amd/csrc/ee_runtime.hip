@@ -131,6 +131,25 @@ static GemmPlan make_plan(int N, int K, int tpu, int nwg, int rows_max, size_t s
     return p;
 }
 
+// longest tile sequence of any wave (tile slots per wave in the interleaved layout)
+static int plan_steps(const GemmPlan &p, int nwg)
+{
+    int mx = 0;
+    for (int g = 0; g < nwg; ++g) {
+        int u0 = (int)((long long)p.U * g / nwg), u1 = (int)((long long)p.U * (g + 1) / nwg);
+        int n_local = (u1 - u0) * p.tpu;
+        for (int w = 0; w < WAVES; ++w) {
+            int per_tile = 0;
+            for (int b = 0; b < p.nKB; ++b) {
+                int kst = p.KT * b / p.nKB, klen = p.KT * (b + 1) / p.nKB - kst;
+                per_tile += klen * (w + 1) / WAVES - klen * w / WAVES;
+            }
+            mx = std::max(mx, n_local * per_tile);
+        }
+    }
+    return mx;
+}
+
 static size_t plan_slot_bytes(const GemmPlan &p, int rows_max) { return (size_t)WAVES * p.GRP * rows_max * 16 * sizeof(float); }
 
 // K-blocks so that one block of x_hat (hi and lo bf16 terms, all rows) fits `budget` bytes
@@ -342,8 +361,10 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     GemmPlan *plans[5] = {&md.plan[0], &md.plan[1], &md.plan[2], &md.plan[3], &md.plan[4]};
     size_t slots = 0;
     for (GemmPlan *p : plans) slots = std::max(slots, plan_slot_bytes(*p, max_rows));
-    const size_t zbuf = align_up((size_t)max_rows * md.plan[G_HEAD].GRP * 16 * sizeof(float), 256);
-    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + WAVES * 4 + 4 + 4 + 4), 256);
+    int max_grp = 1;
+    for (GemmPlan *p : plans) max_grp = std::max(max_grp, p->GRP);
+    const size_t zbuf = align_up((size_t)max_rows * max_grp * 16 * sizeof(float), 256);
+    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4), 256);
     const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float);
     if (slots + zbuf + misc + 4096 > lds_cap) {
         ee_model_free(m);
@@ -357,7 +378,9 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
             return fail(EE_EDEVICE, "ee_model_load: cannot fit one K-block of %d rows into %zu bytes of LDS", max_rows, x_budget);
         }
         x_bytes = std::max(x_bytes, (size_t)2 * max_rows * p->xs_stride * 2);
+        p->steps = plan_steps(*p, m->nwg);
     }
+    x_bytes = std::max(x_bytes, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
     x_bytes = align_up(std::max(x_bytes, att), 256);
     md.lds_slots_off = (int)x_bytes;
     md.lds_zbuf_off = (int)(x_bytes + slots);
@@ -402,8 +425,10 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.emb = dev_emb;
 
     // tiled weights: one allocation per GEMM kind, layers at a fixed stride
-    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].NT * md.plan[k].KT * 64;
+    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * m->nwg * WAVES * 64;
+    const long long s_head = md.wstride[G_HEAD];
     md.wstride[G_HEAD] = 0;
+    (void)s_head;
     const long long s_qkv = md.wstride[G_QKV], s_o = md.wstride[G_O], s_gu = md.wstride[G_GU], s_dn = md.wstride[G_DN];
     uint4 *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdn = nullptr, *wlm = nullptr;
     float *g_attn = nullptr, *g_ffn = nullptr, *g_final_d = nullptr;
@@ -412,7 +437,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].NT * md.plan[G_HEAD].KT * 64, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * m->nwg * WAVES * 64, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
@@ -587,8 +612,14 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     const ModelDev &md = m->host_md;
     S_TRY(dev_alloc(s->allocs, &sc.h, (size_t)rows_max * d));
     S_TRY(dev_alloc(s->allocs, &sc.q, (size_t)rows_max * d));
-    S_TRY(dev_alloc(s->allocs, &sc.attn, (size_t)rows_max * md.Kpad_d));
-    S_TRY(dev_alloc(s->allocs, &sc.u, (size_t)rows_max * md.Kpad_F));
+    for (int t = 0; t < 2; ++t) {
+        S_TRY(dev_alloc(s->allocs, &sc.xn[t], (size_t)rows_max * md.Kpad_d));
+        S_TRY(dev_alloc(s->allocs, &sc.xh[t], (size_t)rows_max * md.Kpad_d));
+        S_TRY(dev_alloc(s->allocs, &sc.attn[t], (size_t)rows_max * md.Kpad_d));
+        S_TRY(dev_alloc(s->allocs, &sc.u[t], (size_t)rows_max * md.Kpad_F));
+    }
+    S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
+    S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
         size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
         size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * 2;
@@ -640,6 +671,8 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
     sd.drafts = s->dev_drafts;
     sd.result = s->dev_result;
     sd.n_pages = s->n_pages;
+    sd.kv_len = s->kv_len;
+    sd.pending = s->pending;
     sd.pad_ = 0;
 }
 
