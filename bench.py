@@ -109,7 +109,8 @@ def main():
     ap.add_argument("--workload", default="llama7b_g4_ctx512", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=20250521)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--phase-launches", action="store_true", help="debug: one launch per phase")
+    ap.add_argument("--chain-launches", action="store_true",
+                    help="run consecutive GEMM stages in one persistent launch with grid barriers")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -127,7 +128,7 @@ def main():
     print(f"[bench] model on GPU in {time.time() - t:.1f}s, {model.n_workgroups} workgroups", file=sys.stderr, flush=True)
     rounds = W + K
     max_ctx = n_prompt + rounds * M + 2 * M + 16
-    flags = ee.PHASE_LAUNCHES if args.phase_launches else 0
+    flags = ee.CHAIN_LAUNCHES if args.chain_launches else 0
     sess = model.session(max_ctx, max_gamma=max(gamma, 1), flags=flags)
     prompt = eegen.prompt_tokens(args.seed, n_prompt, cfg.vocab)
     t = time.time()
@@ -179,7 +180,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "gamma": gamma, "exit_layers": ex, "prompt": n_prompt,
                    "batch": 1, "context_first": ctx_at[0], "context_last": ctx_at[-1],
-                   "launch_mode": "phase" if args.phase_launches else "persistent"},
+                   "launch_mode": "chain" if args.chain_launches else "stage"},
         "device_ms_per_pass": {"mean": mean_dev_ms, "median": statistics.median(dev_ms),
                                "p10": float(np.percentile(dev_ms, 10)), "p90": float(np.percentile(dev_ms, 90))},
         "verified_tokens_per_s": committed / wall,

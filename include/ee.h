@@ -66,8 +66,10 @@ extern "C" {
 /* ee_session_create flags */
 #define EE_KEEP_LOGITS 1u     /* keep every head's logits of the last pass (debug)      */
 #define EE_NO_AUTOCOMMIT 2u   /* final accept does not move kv_len / pending            */
-#define EE_PHASE_LAUNCHES 4u  /* debug: one kernel launch per phase instead of one
-                                 persistent launch per segment; same results           */
+#define EE_TRACE 8u           /* debug: record stage timestamps of the last pass          */
+#define EE_CHAIN_LAUNCHES 4u  /* consecutive GEMM stages share one persistent launch with
+                                 grid barriers (and fetch the next stage's weights across
+                                 them) instead of one launch per stage; same results      */
 
 typedef struct ee_model ee_model;     /* opaque; immutable after load                   */
 typedef struct ee_session ee_session; /* opaque; one KV cache, one stream               */
@@ -172,6 +174,12 @@ int ee_device_synchronize(int device);
 /* Measurement aid: `launches` launches of the pass kernel that execute `barriers`
    grid-wide barriers each and nothing else; mean microseconds per launch. */
 int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch);
+
+/* Debug (EE_TRACE sessions): wall-clock stamps, in 10 ns ticks, that workgroup 0 took in every
+   GEMM stage of the last verify pass; 8 values per stage (stage start, inputs staged, later
+   K-block staged, weights streamed, cross-wave reduce reached, epilogue done, stage end, grid
+   barrier entered). */
+int ee_debug_trace(ee_session *s, unsigned long long *out, int max_values, int *n_values);
 
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
    kernels assume and compares with the plain 16x32 . 32x16 product. */

@@ -26,14 +26,15 @@ EE_EINVAL, EE_ESTATE, EE_ECAPACITY, EE_EIO, EE_EFORMAT, EE_EDEVICE = -1, -2, -3,
 HOLD_LAST = 1
 KEEP_LOGITS = 1
 NO_AUTOCOMMIT = 2
-PHASE_LAUNCHES = 4
+CHAIN_LAUNCHES = 4
+TRACE = 8
 
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
-    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost",
+    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost", "ee_debug_trace",
 ]
 
 
@@ -103,6 +104,7 @@ def load_library():
     lib.ee_debug_mfma_layout.argtypes = [ci]
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
+    lib.ee_debug_trace.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
     for name in EXPORTS:
         if name != "ee_last_error":
             getattr(lib, name).restype = ci
@@ -244,6 +246,12 @@ class Session:
         us = ctypes.c_float()
         _check(self._l.ee_debug_launch_cost(self._h, launches, barriers, ctypes.byref(us)))
         return float(us.value)
+
+    def ee_debug_trace(self) -> np.ndarray:
+        buf = (ctypes.c_ulonglong * (1 << 14))()
+        n = ctypes.c_int()
+        _check(self._l.ee_debug_trace(self._h, buf, 1 << 14, ctypes.byref(n)))
+        return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, 8).copy()
 
     # plain reads of the pinned result block (no computation)
     def exit_result(self, exit_idx: int):

@@ -64,7 +64,7 @@ struct ModelDev {
 struct SessDev {
     int *state;                          // [0] kv_len, [1] pending token
     const int *page_table;               // logical page -> physical page
-    uint16_t *kpool, *vpool;             // [L][n_pages][H][KV_PAGE][hd] bf16
+    uint16_t *kpool, *vpool;             // [L][n_pages][H][KV_PAGE][2][hd] bf16: value = hi + lo
     const float2 *rope;                  // [max_ctx][hd/2] (cos, sin)
     const int *drafts;                   // device copy of this pass's drafts
     ee_verify_result *result;            // device address of the pinned result block
@@ -90,6 +90,7 @@ struct Scratch {
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
     unsigned *bar_flags; // [nwg]                grid barrier: last epoch each workgroup arrived at
     int *err;            // set to 1 when a bounded wait gave up
+    unsigned long long *trace;  // debug: wall-clock stamps of workgroup 0 (EE_TRACE sessions), else nullptr
 };
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
@@ -112,6 +113,7 @@ struct PassArgs {
     int ph_lo, ph_hi;                    // stages [ph_lo, ph_hi) of the segment's stage list run in this launch
     unsigned spin_limit;
     unsigned epoch_base;                 // barrier epoch before this launch
+    int trace_base;                      // debug: first stamp slot of this launch
     const SessDev *sess;                 // device array [n_sess]
 };
 

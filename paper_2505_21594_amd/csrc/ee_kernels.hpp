@@ -33,7 +33,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 constexpr int D = PF_DEPTH;
-constexpr int ATT_UNROLL = 4;  // wave-steps of attention whose loads are in flight together
+constexpr int ATT_UNROLL = 2;  // wave-steps of attention whose loads are in flight together
 
 // Pointers read from descriptors in memory are generic to the compiler, and generic loads go
 // through the flat path, whose completion also counts against the LDS counter: a wait for an
@@ -91,6 +91,13 @@ __device__ __forceinline__ int opaque(int x)
 {
     asm volatile("" : "+v"(x));
     return x;
+}
+// debug: stamp slot (stage-in-launch, k) with the 100 MHz wall clock, workgroup 0 only
+#define EE_TRACE_SLOTS 8
+__device__ __forceinline__ void trace_stamp(const PassArgs &a, int stage_in_launch, int k)
+{
+    if (a.sc.trace && blockIdx.x == 0 && threadIdx.x == 0)
+        a.sc.trace[a.trace_base + stage_in_launch * EE_TRACE_SLOTS + k] = wall_clock64();
 }
 // all vector memory operations of this wave have completed
 __device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -442,10 +449,13 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             } else {
                 const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
                 uint16_t *pool = sect == 1 ? sd.kpool : sd.vpool;
-                uint2 pk;
-                pk.x = f32_to_bf16(v[0]) | (f32_to_bf16(v[1]) << 16);
-                pk.y = f32_to_bf16(v[2]) | (f32_to_bf16(v[3]) << 16);
-                *reinterpret_cast<uint2 *>(pool + mi.kvoff[m] + (size_t)head * KV_PAGE * hd + e) = pk;
+                // cached value = hi + lo, two bf16 terms side by side in the position's record
+                uint32_t vh[4], vl[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) split_bf16(v[t], vh[t], vl[t]);
+                uint16_t *rec = pool + mi.kvoff[m] + (size_t)head * KV_PAGE * 2 * hd + e;
+                *reinterpret_cast<uint2 *>(rec) = make_uint2(vh[0] | (vh[1] << 16), vh[2] | (vh[3] << 16));
+                *reinterpret_cast<uint2 *>(rec + hd) = make_uint2(vl[0] | (vl[1] << 16), vl[2] | (vl[3] << 16));
             }
         } else {  // G_HEAD
             const float rs = mi.rstd[m];
@@ -507,7 +517,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
 template <int MT>
 __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan pl, const uint4 *__restrict__ W,
                              const GemmIn &in, const GemmEpi &ep, uint4 (&buf)[D], bool &have_pre, const NextGemm &next,
-                             char *lds)
+                             char *lds, int tsi)
 {
     const ModelDev &md = *a.md;
     const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -530,6 +540,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
         return;
     }
     if ((kind == G_O || kind == G_DN) && tid < rows) mi.rowss[tid] = 0.f;
+    trace_stamp(a, tsi, 0);
     // start the weight stream before anything else (unless the previous stage already did)
     if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
     if (kind == G_QKV) {
@@ -540,7 +551,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
             const int page = sd.page_table[pos / KV_PAGE];
             mi.pos[m] = pos;
-            mi.kvoff[m] = ((((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE + (pos % KV_PAGE)) * md.hd;
+            mi.kvoff[m] = ((((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE + (pos % KV_PAGE)) * 2 * md.hd;
         }
         const int half = md.hd >> 1;
         for (int i = tid; i < rows * half; i += WG_THREADS) {
@@ -569,6 +580,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                 stage_x(pl, in, rows, s.kst, s.klen, lds);
                 if (in.ss && gi == 0 && kb == 0) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
                 __syncthreads();
+                trace_stamp(a, tsi, 1 + min(kb, 1));
             }
 
             // ---- this wave's tiles of the segment
@@ -636,8 +648,11 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                 have_pre = prefetch_stage(next, a.nwg, buf);
             }
         }
+        trace_stamp(a, tsi, 3);
         __syncthreads();
+        trace_stamp(a, tsi, 4);
         gemm_epilogue(a, kind, layer, pl, nt0 + gi * pl.GRP, gn, rows, ep, mi, lds);
+        trace_stamp(a, tsi, 5);
         if (gi + 1 < n_groups) __syncthreads();
     }
     if (kind == G_O || kind == G_DN) {
@@ -742,23 +757,28 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             const int fp = sb / KV_PAGE, npg = (se - 1) / KV_PAGE - fp + 1;
             const int pg = lane < npg ? sd.page_table[fp + lane] : 0;
             for (int pb = sb; pb < se; pb += PPI * ATT_UNROLL) {
-                uint4 kk[ATT_UNROLL], vv[ATT_UNROLL];
+                uint4 kk[ATT_UNROLL], kl[ATT_UNROLL], vv[ATT_UNROLL], vl[ATT_UNROLL];
 #pragma unroll
                 for (int u = 0; u < ATT_UNROLL; ++u) {
                     const int p = pb + u * PPI + grp;
                     const int pc = p < se ? p : sb;
                     const int page = __shfl(pg, pc / KV_PAGE - fp, 64);
                     const size_t off =
-                        ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * HD + e8 * 8;
+                        ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * (2 * HD) + e8 * 8;
                     kk[u] = load_global16(sd.kpool + off);
+                    kl[u] = load_global16(sd.kpool + off + HD);
                     vv[u] = load_global16(sd.vpool + off);
+                    vl[u] = load_global16(sd.vpool + off + HD);
                 }
 #pragma unroll
                 for (int u = 0; u < ATT_UNROLL; ++u) {
                     const int p = pb + u * PPI + grp;
                     const bool live = p < se;
-                    float kf[8];
+                    float kf[8], lf[8];
                     unpack8(kk[u], kf);
+                    unpack8(kl[u], lf);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kf[e] += lf[e];
                     float sc[ATT_ROWS];
 #pragma unroll
                     for (int i = 0; i < ATT_ROWS; ++i) {
@@ -771,6 +791,9 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                     }
                     float vf[8];
                     unpack8(vv[u], vf);
+                    unpack8(vl[u], lf);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) vf[e] += lf[e];
 #pragma unroll
                     for (int i = 0; i < ATT_ROWS; ++i) {
                         if (live && i < nr && p <= P + r0 + i) {
@@ -1048,7 +1071,11 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
     uint4 buf[D];           // weight tiles in flight; carried from one stage into the next
     bool have_pre = false;  // buf holds the first tiles of the coming stage
     for (int ph = a.ph_lo; ph < a.ph_hi; ++ph) {
-        if (ph > a.ph_lo) grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
+        if (ph > a.ph_lo) {
+            wait_vmem();
+            trace_stamp(a, ph - a.ph_lo - 1, 7);
+            grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
+        }
         const StageDesc st = stage_decode(a, ph);
         NextGemm nx = {nullptr, nullptr};
         if (ph + 1 < a.ph_hi) {
@@ -1059,7 +1086,8 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
         const GemmIn in = gemm_input(a, st.kind);
         const GemmEpi ep = gemm_epi(a, st.kind, st.layer);
         gemm_stage_t<MT>(a, st.kind, st.layer, md.plan[st.kind], md.w[st.kind] + (size_t)st.layer * md.wstride[st.kind],
-                         in, ep, buf, have_pre, nx, lds);
+                         in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
+        trace_stamp(a, ph - a.ph_lo, 6);
     }
 }
 

@@ -79,6 +79,7 @@ struct ee_session {
     SessDev *host_sessdev;           // pinned staging for them
     Scratch sc;
     unsigned epoch;                  // grid-barrier epoch reached by the launches enqueued so far
+    int trace_n;                     // debug: stamp slots handed out in the current pass
     std::vector<void *> allocs;
     // host mirror of the session state
     int kv_len;
@@ -91,6 +92,7 @@ struct ee_session {
 
 // ------------------------------------------------------------------ planning
 
+constexpr int EE_TRACE_MAX = 1 << 14;
 typedef void (*pass_kernel_t)(PassArgs);
 
 static pass_kernel_t chain_kernel(int rows)
@@ -570,7 +572,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     for (int i = 0; i < EE_MAX_EXITS; ++i) S_HIP(hipEventCreate(&s->ev_exit[i]));
 
     s->n_pages = (max_ctx + KV_PAGE - 1) / KV_PAGE;
-    size_t kv_elems = (size_t)c.n_layers * s->n_pages * c.n_heads * KV_PAGE * c.head_dim;
+    size_t kv_elems = (size_t)c.n_layers * s->n_pages * c.n_heads * KV_PAGE * 2 * c.head_dim;  // hi and lo terms
     S_TRY(dev_alloc(s->allocs, &s->kpool, kv_elems));
     S_TRY(dev_alloc(s->allocs, &s->vpool, kv_elems));
     S_TRY(dev_alloc(s->allocs, &s->dev_page_table, (size_t)s->n_pages));
@@ -630,6 +632,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.bar_flags, (size_t)m->nwg));
     S_TRY(dev_alloc(s->allocs, &sc.err, 1));
+    if (flags & EE_TRACE) S_TRY(dev_alloc(s->allocs, &sc.trace, (size_t)EE_TRACE_MAX));
     s->epoch = 0;
     S_HIP(hipDeviceSynchronize());
 #undef S_TRY
@@ -697,7 +700,7 @@ static int stage_type(const PassArgs &a, int ph)
 }
 
 // Enqueues the stages of one segment.  Runs of consecutive GEMM stages go into one launch
-// of the chain kernel (grid barriers inside); with EE_PHASE_LAUNCHES every stage is a launch
+// of the chain kernel (grid barriers inside) with EE_CHAIN_LAUNCHES; otherwise every stage is a launch
 // of its own.  The chain kernel's barrier needs every workgroup resident: the grid is one
 // workgroup per compute unit and the LDS request keeps it to one per unit; the wait is
 // bounded, so a violated assumption ends in an error status, not in a hang.
@@ -706,7 +709,7 @@ static int launch_segment(ee_session *lead, PassArgs &a)
     const ee_model *m = lead->m;
     const int per_layer = 5 + (a.att_splits > 1 ? 1 : 0);
     const int n_phases = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 2 : 0);
-    const bool single = (lead->flags & EE_PHASE_LAUNCHES) != 0;
+    const bool single = (lead->flags & EE_CHAIN_LAUNCHES) == 0;
     int ph = 0;
     while (ph < n_phases) {
         const int type = stage_type(a, ph);
@@ -716,6 +719,8 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         a.ph_lo = ph;
         a.ph_hi = end;
         a.epoch_base = lead->epoch;
+        a.trace_base = lead->trace_n;
+        if (type == ST_GEMM) lead->trace_n = std::min(lead->trace_n + (end - ph) * EE_TRACE_SLOTS, EE_TRACE_MAX - 64 * EE_TRACE_SLOTS);
         pass_kernel_t k = type == ST_GEMM ? chain_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
         hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
         HIP_TRY(hipGetLastError());
@@ -931,6 +936,7 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     a.sess = lead->dev_sessdev;
 
     HIP_TRY(hipEventRecord(lead->ev_start, lead->stream));
+    lead->trace_n = 0;
     int layer = 0;
     for (int e = 0; e <= n_exits; ++e) {
         const bool fin = (e == n_exits);
@@ -1122,6 +1128,23 @@ extern "C" int ee_debug_launch_cost(ee_session *s, int launches, int barriers, f
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, s->ev_start, s->ev_final));
     *us_per_launch = ms * 1000.f / (float)launches;
+    return EE_OK;
+}
+
+// Debug (EE_TRACE sessions): wall-clock stamps (100 MHz ticks) that workgroup 0 took during
+// the GEMM stages of the last verify pass: n_stages x 8 values
+// {stage start, after staging, after staging of a later K-block, after the stream loop,
+//  after the reduce barrier, after the epilogue, stage end, before the grid barrier}.
+extern "C" int ee_debug_trace(ee_session *s, unsigned long long *out, int max_values, int *n_values)
+{
+    if (!s || !out || !n_values) return fail(EE_EINVAL, "null argument");
+    if (!(s->flags & EE_TRACE)) return fail(EE_ESTATE, "ee_debug_trace: session was created without EE_TRACE");
+    HIP_TRY(hipSetDevice(s->m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    int n = std::min(s->trace_n, max_values);
+    HIP_TRY(hipMemcpy(out, s->sc.trace, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    *n_values = n;
     return EE_OK;
 }
 

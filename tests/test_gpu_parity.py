@@ -89,14 +89,14 @@ def test_tiny_ragged_shapes(tiny_pair, n_prompt, gamma):
     _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"tiny P={n_prompt} gamma={gamma}")
 
 
-def test_tiny_phase_launches_bit_identical(tiny_pair):
-    """One launch per phase and one persistent launch per segment run the same
-    code in the same order: logits must be bit-identical, and so must two runs."""
+def test_tiny_launch_modes_bit_identical(tiny_pair):
+    """One launch per stage and persistent chain launches run the same code in
+    the same order: logits must be bit-identical, and so must two runs."""
     g, o = tiny_pair
     prompt = eegen.prompt_tokens(7, 40, o.vocab)
     drafts = eegen.prompt_tokens(8, 4, o.vocab)
     outs = []
-    for flags in (0, ee.PHASE_LAUNCHES, 0):
+    for flags in (0, ee.CHAIN_LAUNCHES, 0):
         gs = g.session(128, max_gamma=8, flags=ee.KEEP_LOGITS | flags)
         gs.ee_prefill(prompt)
         r = gs.verify_sync(drafts, TINY_EXITS)
