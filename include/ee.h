@@ -67,6 +67,8 @@ extern "C" {
 #define EE_KEEP_LOGITS 1u     /* keep every head's logits of the last pass (debug)      */
 #define EE_NO_AUTOCOMMIT 2u   /* final accept does not move kv_len / pending            */
 #define EE_TRACE 8u           /* debug: record stage timestamps of the last pass          */
+#define EE_TIME_LAUNCHES 16u  /* measurement: an event pair around every launch of a verify
+                                 pass (see ee_launch_times); perturbs the pass slightly    */
 #define EE_CHAIN_LAUNCHES 4u  /* consecutive GEMM stages share one persistent launch with
                                  grid barriers (and fetch the next stage's weights across
                                  them) instead of one launch per stage; same results      */
@@ -174,6 +176,21 @@ int ee_device_synchronize(int device);
 /* Measurement aid: `launches` launches of the pass kernel that execute `barriers`
    grid-wide barriers each and nothing else; mean microseconds per launch. */
 int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch);
+
+/* Measurement (EE_TIME_LAUNCHES sessions, pass led by `s`): for every kernel launch of the
+   last verify pass, in launch order, what it ran (EE_LAUNCH_* code) and the milliseconds
+   between the HIP events recorded on the session's stream right before and right after
+   it.  Waits for the pass.  Writes min(n, max_launches) entries to the host arrays. */
+#define EE_LAUNCH_QKV 0     /* attention-norm + Q/K/V projection + RoPE + KV write       */
+#define EE_LAUNCH_O 1       /* attention output projection + residual + FFN norm input   */
+#define EE_LAUNCH_GU 2      /* gate/up projections + SiLU * up                           */
+#define EE_LAUNCH_DN 3      /* down projection + residual + next norm inputs             */
+#define EE_LAUNCH_HEAD 4    /* exit or final head: norm + LM head + per-workgroup argmax */
+#define EE_LAUNCH_ATT 5     /* attention over the paged KV cache                         */
+#define EE_LAUNCH_EMBED 6   /* embedding gather                                          */
+#define EE_LAUNCH_ACCEPT 7  /* global argmax, accept rule, publication, KV commit        */
+#define EE_LAUNCH_CHAIN 8   /* several GEMM stages in one launch (EE_CHAIN_LAUNCHES)     */
+int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, int *n_launches);
 
 /* Debug (EE_TRACE sessions): wall-clock stamps, in 10 ns ticks, that workgroup 0 took in every
    GEMM stage of the last verify pass; 8 values per stage (stage start, inputs staged, later

@@ -28,6 +28,8 @@ KEEP_LOGITS = 1
 NO_AUTOCOMMIT = 2
 CHAIN_LAUNCHES = 4
 TRACE = 8
+TIME_LAUNCHES = 16
+LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "att", "embed", "accept", "chain")
 
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
@@ -35,6 +37,7 @@ EXPORTS = [
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost", "ee_debug_trace",
+    "ee_launch_times",
 ]
 
 
@@ -105,6 +108,7 @@ def load_library():
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
     lib.ee_debug_trace.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
+    lib.ee_launch_times.argtypes = [vp, i32p, P(ctypes.c_float), ci, P(ci)]
     for name in EXPORTS:
         if name != "ee_last_error":
             getattr(lib, name).restype = ci
@@ -252,6 +256,13 @@ class Session:
         n = ctypes.c_int()
         _check(self._l.ee_debug_trace(self._h, buf, 1 << 14, ctypes.byref(n)))
         return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, 8).copy()
+
+    def ee_launch_times(self):
+        """[(launch code, milliseconds)] of every launch of the last verify pass."""
+        cap = 4096
+        codes, ms, n = (ctypes.c_int32 * cap)(), (ctypes.c_float * cap)(), ctypes.c_int()
+        _check(self._l.ee_launch_times(self._h, codes, ms, cap, ctypes.byref(n)))
+        return [(int(codes[i]), float(ms[i])) for i in range(n.value)]
 
     # plain reads of the pinned result block (no computation)
     def exit_result(self, exit_idx: int):

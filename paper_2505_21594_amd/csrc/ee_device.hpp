@@ -12,8 +12,8 @@ constexpr int WAVES = 12;                // waves per workgroup: three per SIMD,
 constexpr int WG_THREADS = WAVES * 64;
 constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
 constexpr int KV_PAGE = 16;              // positions per KV page
-constexpr int ATT_ROWS = 4;              // query rows handled together in attention
-constexpr int ATT_MAX_SPLITS = 32;
+constexpr int ATT_ROWS = 8;              // query rows handled together in attention
+constexpr int ATT_MAX_SPLITS = 16;
 
 // Weight layout of one GEMM y = x . W^T, W[N][K] row-major in the model file.
 //
@@ -44,7 +44,7 @@ struct GemmPlan {
 
 enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };
 enum GemmKind { G_QKV = 0, G_O = 1, G_GU = 2, G_DN = 3, G_HEAD = 4 };
-enum StageType { ST_EMBED = 0, ST_GEMM = 1, ST_ATT = 2, ST_MERGE = 3, ST_ACCEPT = 4, ST_NONE = 5 };
+enum StageType { ST_EMBED = 0, ST_GEMM = 1, ST_ATT = 2, ST_ACCEPT = 3, ST_NONE = 4 };
 
 struct ModelDev {
     int L, d, H, hd, F, V;
@@ -85,7 +85,8 @@ struct Scratch {
     uint16_t *u[2];      // [rows_max][Kpad_F]   silu(gate)*up
     float *ss_a;         // [nwg][rows_max]      partial sums of h^2 after the FFN block / embedding
     float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
-    float *att_part;     // attention partials (only when the position range is split)
+    float *att_part;     // [items][ATT_ROWS][hd+2] attention partials (only when the position range is split)
+    int *att_count;      // [units] items of the unit that have delivered their partials; zero between launches
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
     unsigned *bar_flags; // [nwg]                grid barrier: last epoch each workgroup arrived at
@@ -110,11 +111,14 @@ struct PassArgs {
     const float *head_gain;
     int commit, keep_logits;
     int att_splits;
+    int H, d, Kpad_d;                    // copies of the model descriptor's fields for the attention kernel
+    float att_scale;
     int ph_lo, ph_hi;                    // stages [ph_lo, ph_hi) of the segment's stage list run in this launch
     unsigned spin_limit;
     unsigned epoch_base;                 // barrier epoch before this launch
     int trace_base;                      // debug: first stamp slot of this launch
     const SessDev *sess;                 // device array [n_sess]
+    SessDev sess0;                       // copy of sess[0]
 };
 
 }  // namespace ee

@@ -33,7 +33,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
 constexpr int D = PF_DEPTH;
-constexpr int ATT_UNROLL = 2;  // wave-steps of attention whose loads are in flight together
 
 // Pointers read from descriptors in memory are generic to the compiler, and generic loads go
 // through the flat path, whose completion also counts against the LDS counter: a wait for an
@@ -704,110 +703,124 @@ __device__ void embed_stage(const PassArgs &a, char *lds)
 
 constexpr float ATT_NEG = -1.0e30f;  // finite stand-in for "no position seen yet"
 
+__device__ __forceinline__ uint2 load_global8(const void *p)
+{
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+    u32x2_t v = *as_global(reinterpret_cast<const u32x2_t *>(p));
+    return make_uint2(v[0], v[1]);
+}
+
+// sum of the two bf16 terms of four consecutive cached values
+__device__ __forceinline__ void unpack4_sum(const uint2 &hi, const uint2 &lo, float *f)
+{
+    f[0] = __uint_as_float(hi.x << 16) + __uint_as_float(lo.x << 16);
+    f[1] = __uint_as_float(hi.x & 0xFFFF0000u) + __uint_as_float(lo.x & 0xFFFF0000u);
+    f[2] = __uint_as_float(hi.y << 16) + __uint_as_float(lo.y << 16);
+    f[3] = __uint_as_float(hi.y & 0xFFFF0000u) + __uint_as_float(lo.y & 0xFFFF0000u);
+}
+
 // Work item = (session, head, chunk of up to ATT_ROWS query rows, split of the position
-// range).  The 16 waves of the workgroup share the split's positions; a group of HD/8 lanes
-// handles one cached position per step (16-byte loads of K and V).  q and the cached k use
-// the same pair-interleaved order inside a head, so their dot product is unchanged.
-// With one split the normalised output is written directly; otherwise un-normalised
-// partials (accumulator, running max, running sum) go to scratch for the merge stage.
+// range); the host picks the number of splits so that the items cover the chip, because one
+// compute unit alone cannot pull a head's cache fast enough.  The waves of the workgroup
+// share the split's positions; HD/4 lanes handle one cached position per step, four values
+// each.  q and the cached k use the same pair-interleaved order inside a head, so their dot
+// product is unchanged.  With one split the normalised output is written directly.
+// Otherwise every item writes un-normalised partials (accumulator, running max, running sum)
+// and counts itself in the unit's counter; the item that arrives last merges the unit's
+// partials in split order (so the result does not depend on arrival order) and clears the
+// counter for the next launch.  Nothing waits.
 template <int HD>
 __device__ void att_stage(const PassArgs &a, int layer, char *lds)
 {
-    constexpr int LPP = HD / 8;    // lanes per position
+    constexpr int LPP = HD / 4;    // lanes per position
     constexpr int PPI = 64 / LPP;  // positions per wave step
     constexpr int REC = HD + 2;
-    const ModelDev &md = *a.md;
-    const int H = md.H, d = md.d, M = a.M;
+    constexpr int UNR = HD >= 128 ? 4 : 2;  // wave-steps whose loads are in flight together
+    const int H = a.H, d = a.d, Kpad_d = a.Kpad_d, M = a.M;  // copies in the launch arguments: no load before the first address
     const int n_chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     const int n_splits = a.att_splits;
     const int n_items = a.n_sess * H * n_chunks * n_splits;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = lane / LPP, e8 = lane % LPP;
+    const int grp = lane / LPP, e4 = lane % LPP;
     float *wbuf = reinterpret_cast<float *>(lds);  // [WAVES][ATT_ROWS][REC]
+    int *lastf = reinterpret_cast<int *>(wbuf + (size_t)WAVES * ATT_ROWS * REC);
 
+    trace_stamp(a, 0, 0);
     for (int item = blockIdx.x; item < n_items; item += a.nwg) {
         int unit = item / n_splits, sp = item - unit * n_splits;
         int s = unit / (H * n_chunks), rem = unit - s * (H * n_chunks);
         int hh = rem / n_chunks, ch = rem - hh * n_chunks;
         int r0 = ch * ATT_ROWS, nr = min(ATT_ROWS, M - r0);
-        const SessDev sd = a.sess[s];
-        const int P = a.mode == 1 ? a.pf_pos0 : sd.kv_len;  // position of the session's first row
+        // session 0's descriptor also travels by value in the launch arguments: no dependent load
+        const SessDev *sdp = a.sess + s;
+        const int *page_table = s == 0 ? a.sess0.page_table : sdp->page_table;
+        const uint16_t *kpool = s == 0 ? a.sess0.kpool : sdp->kpool;
+        const uint16_t *vpool = s == 0 ? a.sess0.vpool : sdp->vpool;
+        const int n_pages = s == 0 ? a.sess0.n_pages : sdp->n_pages;
+        const int P = a.mode == 1 ? a.pf_pos0 : (s == 0 ? a.sess0.kv_len : sdp->kv_len);  // position of the first row
         const int n_pos = P + r0 + nr;            // positions visible to the chunk's last row
         const int lo = (int)((long long)n_pos * sp / n_splits), hi = (int)((long long)n_pos * (sp + 1) / n_splits);
         const int wlo = lo + (int)((long long)(hi - lo) * wave / WAVES);
         const int whi = lo + (int)((long long)(hi - lo) * (wave + 1) / WAVES);
 
-        float q[ATT_ROWS][8], acc[ATT_ROWS][8], mx[ATT_ROWS], l[ATT_ROWS];
+        float q[ATT_ROWS][4], acc[ATT_ROWS][4], mx[ATT_ROWS], l[ATT_ROWS];
 #pragma unroll
         for (int i = 0; i < ATT_ROWS; ++i) {
             mx[i] = ATT_NEG;
             l[i] = 0.f;
-            const float *qp = a.sc.q + (size_t)(s * M + r0 + min(i, nr - 1)) * d + hh * HD + e8 * 8;
-            float4 qa = *reinterpret_cast<const float4 *>(qp), qb = *reinterpret_cast<const float4 *>(qp + 4);
-            q[i][0] = qa.x; q[i][1] = qa.y; q[i][2] = qa.z; q[i][3] = qa.w;
-            q[i][4] = qb.x; q[i][5] = qb.y; q[i][6] = qb.z; q[i][7] = qb.w;
+            const float *qp = a.sc.q + (size_t)(s * M + r0 + min(i, nr - 1)) * d + hh * HD + e4 * 4;
+            f32x4_t qa = *as_global(reinterpret_cast<const f32x4_t *>(qp));
+            q[i][0] = qa[0]; q[i][1] = qa[1]; q[i][2] = qa[2]; q[i][3] = qa[3];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[i][e] = 0.f;
+            for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
         }
 
-        // positions in super-chunks of up to 1024: one page-table entry per lane, then steps
-        // of ATT_UNROLL wave-steps whose K and V loads are all issued before any is used
+        // positions in super-chunks of up to 1024: one page-table entry per lane, then rounds
+        // of UNR wave-steps whose K and V loads are all issued before any is used
         for (int sb = wlo; sb < whi; sb += 1024) {
             const int se = min(whi, sb + 1024);
             const int fp = sb / KV_PAGE, npg = (se - 1) / KV_PAGE - fp + 1;
-            const int pg = lane < npg ? sd.page_table[fp + lane] : 0;
-            for (int pb = sb; pb < se; pb += PPI * ATT_UNROLL) {
-                uint4 kk[ATT_UNROLL], kl[ATT_UNROLL], vv[ATT_UNROLL], vl[ATT_UNROLL];
+            const int pg = lane < npg ? as_global(page_table)[fp + lane] : 0;
+            for (int pb = sb; pb < se; pb += PPI * UNR) {
+                uint2 kh[UNR], kl[UNR], vh[UNR], vl[UNR];
 #pragma unroll
-                for (int u = 0; u < ATT_UNROLL; ++u) {
+                for (int u = 0; u < UNR; ++u) {
                     const int p = pb + u * PPI + grp;
                     const int pc = p < se ? p : sb;
                     const int page = __shfl(pg, pc / KV_PAGE - fp, 64);
                     const size_t off =
-                        ((((size_t)layer * sd.n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * (2 * HD) + e8 * 8;
-                    kk[u] = load_global16(sd.kpool + off);
-                    kl[u] = load_global16(sd.kpool + off + HD);
-                    vv[u] = load_global16(sd.vpool + off);
-                    vl[u] = load_global16(sd.vpool + off + HD);
+                        ((((size_t)layer * n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * (2 * HD) + e4 * 4;
+                    kh[u] = load_global8(kpool + off);
+                    kl[u] = load_global8(kpool + off + HD);
+                    vh[u] = load_global8(vpool + off);
+                    vl[u] = load_global8(vpool + off + HD);
                 }
 #pragma unroll
-                for (int u = 0; u < ATT_UNROLL; ++u) {
+                for (int u = 0; u < UNR; ++u) {
                     const int p = pb + u * PPI + grp;
                     const bool live = p < se;
-                    float kf[8], lf[8];
-                    unpack8(kk[u], kf);
-                    unpack8(kl[u], lf);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) kf[e] += lf[e];
-                    float sc[ATT_ROWS];
+                    float kf[4], vf[4];
+                    unpack4_sum(kh[u], kl[u], kf);
+                    unpack4_sum(vh[u], vl[u], vf);
 #pragma unroll
                     for (int i = 0; i < ATT_ROWS; ++i) {
-                        float sdot = 0.f;
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) sdot += q[i][e] * kf[e];
+                        float sdot = q[i][0] * kf[0] + q[i][1] * kf[1] + q[i][2] * kf[2] + q[i][3] * kf[3];
 #pragma unroll
                         for (int off2 = 1; off2 < LPP; off2 <<= 1) sdot += __shfl_xor(sdot, off2, 64);
-                        sc[i] = sdot * md.att_scale;
-                    }
-                    float vf[8];
-                    unpack8(vv[u], vf);
-                    unpack8(vl[u], lf);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) vf[e] += lf[e];
-#pragma unroll
-                    for (int i = 0; i < ATT_ROWS; ++i) {
+                        const float sc = sdot * a.att_scale;
                         if (live && i < nr && p <= P + r0 + i) {
-                            float nm = fmaxf(mx[i], sc[i]);
-                            float corr = __expf(mx[i] - nm), pe = __expf(sc[i] - nm);
+                            float nm = fmaxf(mx[i], sc);
+                            float corr = __expf(mx[i] - nm), pe = __expf(sc - nm);
                             l[i] = l[i] * corr + pe;
 #pragma unroll
-                            for (int e = 0; e < 8; ++e) acc[i][e] = acc[i][e] * corr + pe * vf[e];
+                            for (int e = 0; e < 4; ++e) acc[i][e] = acc[i][e] * corr + pe * vf[e];
                             mx[i] = nm;
                         }
                     }
                 }
             }
         }
+        trace_stamp(a, 0, 1);
         // merge the position groups of the wave
 #pragma unroll
         for (int i = 0; i < ATT_ROWS; ++i) {
@@ -818,7 +831,7 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 float c0 = __expf(mx[i] - nm), c1 = __expf(om - nm);
                 l[i] = l[i] * c0 + ol * c1;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
+                for (int e = 0; e < 4; ++e) {
                     float oa = __shfl_xor(acc[i][e], off2, 64);
                     acc[i][e] = acc[i][e] * c0 + oa * c1;
                 }
@@ -826,15 +839,15 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             }
             if (grp == 0) {
                 float *w = wbuf + ((size_t)wave * ATT_ROWS + i) * REC;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) w[e8 * 8 + e] = acc[i][e];
-                if (e8 == 0) {
+                *reinterpret_cast<float4 *>(w + e4 * 4) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
+                if (e4 == 0) {
                     w[HD] = mx[i];
                     w[HD + 1] = l[i];
                 }
             }
         }
         __syncthreads();
+        trace_stamp(a, 0, 2);
         // merge the waves, fixed order
         if (n_splits == 1) {
             for (int t = tid; t < nr * HD; t += WG_THREADS) {
@@ -850,7 +863,7 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 }
                 uint32_t vh, vl;
                 split_bf16(num / den, vh, vl);
-                const size_t oi = (size_t)(s * M + r0 + i) * md.Kpad_d + hh * HD + e;
+                const size_t oi = (size_t)(s * M + r0 + i) * Kpad_d + hh * HD + e;
                 a.sc.attn[0][oi] = (uint16_t)vh;
                 a.sc.attn[1][oi] = (uint16_t)vl;
             }
@@ -870,41 +883,55 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                         r += wr[e] * __expf(wr[HD] - gm);
                     }
                 }
-                out[(size_t)i * REC + e] = r;
+                store_dev32(out + (size_t)i * REC + e, r);
+            }
+            trace_stamp(a, 0, 3);
+            wait_vmem();      // this item's partials are visible device-wide ...
+            __syncthreads();  // ... for every wave, before it is counted
+            if (tid == 0) {
+                int before = __hip_atomic_fetch_add(a.sc.att_count + unit, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                *lastf = before == n_splits - 1 ? 1 : 0;
+            }
+            __syncthreads();
+            trace_stamp(a, 0, 4);
+            if (*lastf) {
+                const float *base = a.sc.att_part + (size_t)unit * n_splits * ATT_ROWS * REC;
+                const size_t sp_stride = (size_t)ATT_ROWS * REC;
+                for (int t = tid; t < nr * HD; t += WG_THREADS) {
+                    int i = t / HD, e = t - i * HD;
+                    const float *row = base + (size_t)i * REC;
+                    // all loads first, so that they are in flight together
+                    float pm[ATT_MAX_SPLITS], pv[ATT_MAX_SPLITS], pl[ATT_MAX_SPLITS];
+#pragma unroll
+                    for (int k = 0; k < ATT_MAX_SPLITS; ++k) {
+                        const float *r = row + min(k, n_splits - 1) * sp_stride;
+                        pm[k] = load_dev32(r + HD);
+                        pv[k] = load_dev32(r + e);
+                        pl[k] = load_dev32(r + HD + 1);
+                    }
+                    float gm = ATT_NEG;
+#pragma unroll
+                    for (int k = 0; k < ATT_MAX_SPLITS; ++k)
+                        if (k < n_splits) gm = fmaxf(gm, pm[k]);
+                    float num = 0.f, den = 0.f;
+#pragma unroll
+                    for (int k = 0; k < ATT_MAX_SPLITS; ++k)
+                        if (k < n_splits) {
+                            float f = __expf(pm[k] - gm);
+                            num += pv[k] * f;
+                            den += pl[k] * f;
+                        }
+                    uint32_t vh, vl;
+                    split_bf16(num / den, vh, vl);
+                    const size_t oi = (size_t)(s * M + r0 + i) * Kpad_d + hh * HD + e;
+                    a.sc.attn[0][oi] = (uint16_t)vh;
+                    a.sc.attn[1][oi] = (uint16_t)vl;
+                }
+                if (tid == 0) __hip_atomic_store(a.sc.att_count + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         __syncthreads();
-    }
-}
-
-// merge the splits, normalise, write the attention output (only when n_splits > 1)
-__device__ void att_merge_stage(const PassArgs &a)
-{
-    const ModelDev &md = *a.md;
-    const int d = md.d, HD = md.hd, H = md.H, M = a.M, rows = a.rows;
-    const int REC = HD + 2;
-    const int n_chunks = (M + ATT_ROWS - 1) / ATT_ROWS, n_splits = a.att_splits;
-    const int gsz = a.nwg * WG_THREADS;
-    for (int it = blockIdx.x * WG_THREADS + threadIdx.x; it < rows * d; it += gsz) {
-        int r = it / d, col = it - r * d;
-        int s = r / M, i = r - s * M;
-        int ch = i / ATT_ROWS, ii = i - ch * ATT_ROWS;
-        int hh = col / HD, e = col - hh * HD;
-        int unit = (s * H + hh) * n_chunks + ch;
-        const float *base = a.sc.att_part + ((size_t)unit * n_splits * ATT_ROWS + ii) * REC;
-        const size_t sp_stride = (size_t)ATT_ROWS * REC;
-        float gm = ATT_NEG;
-        for (int sp = 0; sp < n_splits; ++sp) gm = fmaxf(gm, base[sp * sp_stride + HD]);
-        float num = 0.f, den = 0.f;
-        for (int sp = 0; sp < n_splits; ++sp) {
-            float w = __expf(base[sp * sp_stride + HD] - gm);
-            num += base[sp * sp_stride + e] * w;
-            den += base[sp * sp_stride + HD + 1] * w;
-        }
-        uint32_t vh, vl;
-        split_bf16(num / den, vh, vl);
-        a.sc.attn[0][(size_t)r * md.Kpad_d + col] = (uint16_t)vh;
-        a.sc.attn[1][(size_t)r * md.Kpad_d + col] = (uint16_t)vl;
+        trace_stamp(a, 0, 5);
     }
 }
 
@@ -981,9 +1008,9 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
 
 // ------------------------------------------------------------------ kernels of the pass
 //
-// Stage list of a segment: [EMBED] { QKV ATT [MERGE] O GU DN } x layers [HEAD ACCEPT].
+// Stage list of a segment: [EMBED] { QKV ATT O GU DN } x layers [HEAD ACCEPT].
 // Consecutive GEMM stages run inside one launch of the chain kernel with a grid barrier
-// between them; attention, embedding, merge and accept are launches of their own.
+// between them; attention, embedding and accept are launches of their own.
 
 struct StageDesc {
     int type, kind, layer;
@@ -992,8 +1019,7 @@ struct StageDesc {
 __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
 {
     StageDesc sd = {ST_NONE, 0, 0};
-    const bool split = a.att_splits > 1;
-    const int per_layer = 5 + (split ? 1 : 0);
+    const int per_layer = 5;
     int idx = ph - (a.do_embed ? 1 : 0);
     if (idx < 0) {
         sd.type = ST_EMBED;
@@ -1008,11 +1034,9 @@ __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
             sd.kind = G_QKV;
         } else if (r == 1) {
             sd.type = ST_ATT;
-        } else if (split && r == 2) {
-            sd.type = ST_MERGE;
         } else {
             sd.type = ST_GEMM;
-            sd.kind = G_O + (r - (split ? 3 : 2));
+            sd.kind = G_O + (r - 2);
         }
         return sd;
     }
@@ -1098,15 +1122,13 @@ __global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a)
     att_stage<HD>(a, stage_decode(a, a.ph_lo).layer, lds);
 }
 
-// embedding, attention merge, accept: stage ph_lo
+// embedding, accept: stage ph_lo
 __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a)
 {
     extern __shared__ __align__(16) char lds[];
     const StageDesc st = stage_decode(a, a.ph_lo);
     if (st.type == ST_EMBED)
         embed_stage(a, lds);
-    else if (st.type == ST_MERGE)
-        att_merge_stage(a);
     else if (st.type == ST_ACCEPT)
         accept_stage(a, lds);
 }

@@ -80,6 +80,8 @@ struct ee_session {
     Scratch sc;
     unsigned epoch;                  // grid-barrier epoch reached by the launches enqueued so far
     int trace_n;                     // debug: stamp slots handed out in the current pass
+    std::vector<hipEvent_t> lt_events;   // EE_TIME_LAUNCHES: event pairs around every launch of the pass
+    std::vector<int> lt_codes;           // what each timed launch ran (EE_LAUNCH_* code)
     std::vector<void *> allocs;
     // host mirror of the session state
     int kv_len;
@@ -367,7 +369,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     for (GemmPlan *p : plans) max_grp = std::max(max_grp, p->GRP);
     const size_t zbuf = align_up((size_t)max_rows * max_grp * 16 * sizeof(float), 256);
     const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4), 256);
-    const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float);
+    const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
     if (slots + zbuf + misc + 4096 > lds_cap) {
         ee_model_free(m);
         return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
@@ -498,15 +500,14 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 
 // ------------------------------------------------------------------ sessions
 
-// Splits of the position range per attention unit: one while a single workgroup can
-// walk the cache of a head in a few microseconds, more for long contexts (then a
-// merge stage follows the attention stage).
+// Splits of the position range per attention unit: enough items to occupy every compute
+// unit (one unit alone pulls a head's cache too slowly), at least 32 positions each.
 static int attention_splits(const ee_model *m, int n_sess, int M, int n_pos_max)
 {
-    if (n_pos_max <= 1536) return 1;
     int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     int units = n_sess * m->cfg.n_heads * chunks;
-    int s = std::min((n_pos_max + 1023) / 1024, m->nwg / std::max(units, 1));
+    int s = std::min(m->nwg / std::max(units, 1), n_pos_max / 32);
+    if (const char *e = getenv("EE_ATT_SPLITS")) s = atoi(e);
     return std::max(1, std::min(s, ATT_MAX_SPLITS));
 }
 
@@ -525,6 +526,7 @@ extern "C" int ee_session_free(ee_session *s)
     if (s->ev_final) hipEventDestroy(s->ev_final);
     for (hipEvent_t e : s->ev_exit)
         if (e) hipEventDestroy(e);
+    for (hipEvent_t e : s->lt_events) hipEventDestroy(e);
     if (s->stream) hipStreamDestroy(s->stream);
     delete s;
     return EE_OK;
@@ -623,9 +625,11 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
+        // items = units * splits with splits <= max(1, nwg / units)
         size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
-        size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * 2;
+        size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * ATT_MAX_SPLITS;
         S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
+        S_TRY(dev_alloc(s->allocs, &sc.att_count, max_units));
     }
     if (flags & EE_KEEP_LOGITS)
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
@@ -679,11 +683,10 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
     sd.pad_ = 0;
 }
 
-// host mirror of the kernels' stage list: [EMBED] { QKV ATT [MERGE] O GU DN } x layers [HEAD ACCEPT]
+// host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [HEAD ACCEPT]
 static int stage_type(const PassArgs &a, int ph)
 {
-    const bool split = a.att_splits > 1;
-    const int per_layer = 5 + (split ? 1 : 0);
+    const int per_layer = 5;
     int idx = ph - (a.do_embed ? 1 : 0);
     if (idx < 0) return ST_EMBED;
     const int nl = a.layer_end - a.layer_begin;
@@ -691,12 +694,27 @@ static int stage_type(const PassArgs &a, int ph)
         int r = idx % per_layer;
         if (r == 0) return ST_GEMM;
         if (r == 1) return ST_ATT;
-        if (split && r == 2) return ST_MERGE;
         return ST_GEMM;
     }
     idx -= per_layer * nl;
     if (a.head_kind != HEAD_NONE) return idx == 0 ? ST_GEMM : ST_ACCEPT;
     return ST_NONE;
+}
+
+// what a single-stage launch runs, as an EE_LAUNCH_* code
+static int launch_code(const PassArgs &a, int ph, int end)
+{
+    const int type = stage_type(a, ph);
+    if (type == ST_EMBED) return EE_LAUNCH_EMBED;
+    if (type == ST_ATT) return EE_LAUNCH_ATT;
+    if (type == ST_ACCEPT) return EE_LAUNCH_ACCEPT;
+    if (end - ph > 1) return EE_LAUNCH_CHAIN;
+    const int per_layer = 5;
+    int idx = ph - (a.do_embed ? 1 : 0);
+    if (idx >= per_layer * (a.layer_end - a.layer_begin)) return EE_LAUNCH_HEAD;
+    int r = idx % per_layer;
+    if (r == 0) return EE_LAUNCH_QKV;
+    return EE_LAUNCH_O + (r - (per_layer - 3));
 }
 
 // Enqueues the stages of one segment.  Runs of consecutive GEMM stages go into one launch
@@ -707,7 +725,7 @@ static int stage_type(const PassArgs &a, int ph)
 static int launch_segment(ee_session *lead, PassArgs &a)
 {
     const ee_model *m = lead->m;
-    const int per_layer = 5 + (a.att_splits > 1 ? 1 : 0);
+    const int per_layer = 5;
     const int n_phases = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 2 : 0);
     const bool single = (lead->flags & EE_CHAIN_LAUNCHES) == 0;
     int ph = 0;
@@ -720,10 +738,22 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         a.ph_hi = end;
         a.epoch_base = lead->epoch;
         a.trace_base = lead->trace_n;
-        if (type == ST_GEMM) lead->trace_n = std::min(lead->trace_n + (end - ph) * EE_TRACE_SLOTS, EE_TRACE_MAX - 64 * EE_TRACE_SLOTS);
+        lead->trace_n = std::min(lead->trace_n + (end - ph) * EE_TRACE_SLOTS, EE_TRACE_MAX - 64 * EE_TRACE_SLOTS);
         pass_kernel_t k = type == ST_GEMM ? chain_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
+        const bool timed = (lead->flags & EE_TIME_LAUNCHES) && a.mode == 0;
+        if (timed) {
+            const size_t i = lead->lt_codes.size();
+            while (lead->lt_events.size() < 2 * (i + 1)) {
+                hipEvent_t ev;
+                HIP_TRY(hipEventCreate(&ev));
+                lead->lt_events.push_back(ev);
+            }
+            lead->lt_codes.push_back(launch_code(a, ph, end));
+            HIP_TRY(hipEventRecord(lead->lt_events[2 * i], lead->stream));
+        }
         hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
         HIP_TRY(hipGetLastError());
+        if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->stream));
         lead->epoch += (unsigned)(end - ph - 1);
         ph = end;
     }
@@ -736,6 +766,10 @@ static void base_args(const ee_session *lead, PassArgs &a)
     a.md = lead->m->dev_md;
     a.sc = lead->sc;
     a.nwg = lead->m->nwg;
+    a.H = lead->m->host_md.H;
+    a.d = lead->m->host_md.d;
+    a.Kpad_d = lead->m->host_md.Kpad_d;
+    a.att_scale = lead->m->host_md.att_scale;
     a.keep_logits = (lead->flags & EE_KEEP_LOGITS) ? 1 : 0;
     a.spin_limit = 1u << 20;
     if (const char *e = getenv("EE_SPIN_LIMIT")) a.spin_limit = (unsigned)strtoul(e, nullptr, 10);
@@ -827,6 +861,7 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
         a.head_gain = m->host_md.g_final;
         a.att_splits = attention_splits(m, 1, rows, start + rows);
         a.sess = s->dev_sessdev;
+        a.sess0 = s->host_sessdev[0];
         if ((rc = launch_segment(s, a)) != EE_OK) return rc;
     }
     HIP_TRY(hipStreamSynchronize(s->stream));
@@ -934,9 +969,11 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     HIP_TRY(hipMemcpyAsync(lead->dev_sessdev, lead->host_sessdev, (size_t)n_sessions * sizeof(SessDev),
                            hipMemcpyHostToDevice, lead->stream));
     a.sess = lead->dev_sessdev;
+    a.sess0 = lead->host_sessdev[0];
 
     HIP_TRY(hipEventRecord(lead->ev_start, lead->stream));
     lead->trace_n = 0;
+    lead->lt_codes.clear();
     int layer = 0;
     for (int e = 0; e <= n_exits; ++e) {
         const bool fin = (e == n_exits);
@@ -1145,6 +1182,24 @@ extern "C" int ee_debug_trace(ee_session *s, unsigned long long *out, int max_va
     int n = std::min(s->trace_n, max_values);
     HIP_TRY(hipMemcpy(out, s->sc.trace, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
     *n_values = n;
+    return EE_OK;
+}
+
+// EE_TIME_LAUNCHES sessions: what every launch of the last verify pass ran and how long the
+// stream spent between the events recorded right before and right after it.
+extern "C" int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, int *n_launches)
+{
+    if (!s || !codes || !ms || !n_launches) return fail(EE_EINVAL, "null argument");
+    if (!(s->flags & EE_TIME_LAUNCHES)) return fail(EE_ESTATE, "ee_launch_times: session was created without EE_TIME_LAUNCHES");
+    HIP_TRY(hipSetDevice(s->m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    const int n = std::min((int)s->lt_codes.size(), max_launches);
+    for (int i = 0; i < n; ++i) {
+        codes[i] = s->lt_codes[i];
+        HIP_TRY(hipEventElapsedTime(&ms[i], s->lt_events[2 * i], s->lt_events[2 * i + 1]));
+    }
+    *n_launches = n;
     return EE_OK;
 }
 
