@@ -12,7 +12,8 @@ constexpr int WAVES = 12;                // waves per workgroup: three per SIMD,
 constexpr int WG_THREADS = WAVES * 64;
 constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
 constexpr int KV_PAGE = 16;              // positions per KV page
-constexpr int ATT_ROWS = 8;              // query rows handled together in attention
+constexpr int ATT_ROWS = 16;             // query rows of one attention item (one MFMA tile)
+constexpr int ATT_TILES = 8;             // KV pages (score tiles) a wave keeps in registers per item
 constexpr int ATT_MAX_SPLITS = 16;
 
 // Weight layout of one GEMM y = x . W^T, W[N][K] row-major in the model file.
@@ -64,7 +65,8 @@ struct ModelDev {
 struct SessDev {
     int *state;                          // [0] kv_len, [1] pending token
     const int *page_table;               // logical page -> physical page
-    uint16_t *kpool, *vpool;             // [L][n_pages][H][KV_PAGE][2][hd] bf16: value = hi + lo
+    uint16_t *kpool, *vpool;             // per (layer, page, head) a record of KV_PAGE*2*hd bf16, value = hi + lo:
+                                         // K [position][term][hd], V [term][hd][position]
     const float2 *rope;                  // [max_ctx][hd/2] (cos, sin)
     const int *drafts;                   // device copy of this pass's drafts
     ee_verify_result *result;            // device address of the pinned result block

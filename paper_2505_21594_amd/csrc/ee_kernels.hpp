@@ -181,7 +181,7 @@ struct Misc {  // views into the misc region of the LDS block
     float *rstd;       // [rows_max]
     float *rowss;      // [rows_max]  this workgroup's sum of h^2 per row (O / DN stages)
     int *pos;          // [rows_max]
-    long long *kvoff;  // [rows_max]  element offset of (layer, page, slot, head 0) in the KV pools
+    long long *kvoff;  // [rows_max]  element offset of the row's (layer, page, head 0) record in the KV pools
     float2 *rope;      // [rows_max][hd/2]
     float *bestv;      // [rows_max]
     int *besti;        // [rows_max]
@@ -446,15 +446,26 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             if (sect == 0) {
                 *reinterpret_cast<float4 *>(a.sc.q + (size_t)m * d + c) = make_float4(v[0], v[1], v[2], v[3]);
             } else {
+                // cached value = hi + lo, two bf16 terms.  K: [position][term][hd]; V transposed
+                // inside the page: [term][hd][position] (see the attention stage)
                 const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
-                uint16_t *pool = sect == 1 ? sd.kpool : sd.vpool;
-                // cached value = hi + lo, two bf16 terms side by side in the position's record
                 uint32_t vh[4], vl[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) split_bf16(v[t], vh[t], vl[t]);
-                uint16_t *rec = pool + mi.kvoff[m] + (size_t)head * KV_PAGE * 2 * hd + e;
-                *reinterpret_cast<uint2 *>(rec) = make_uint2(vh[0] | (vh[1] << 16), vh[2] | (vh[3] << 16));
-                *reinterpret_cast<uint2 *>(rec + hd) = make_uint2(vl[0] | (vl[1] << 16), vl[2] | (vl[3] << 16));
+                const size_t rec = mi.kvoff[m] + (size_t)head * KV_PAGE * 2 * hd;  // this (page, head) record
+                const int slot = mi.pos[m] % KV_PAGE;
+                if (sect == 1) {
+                    uint16_t *kr = sd.kpool + rec + (size_t)slot * 2 * hd + e;
+                    *reinterpret_cast<uint2 *>(kr) = make_uint2(vh[0] | (vh[1] << 16), vh[2] | (vh[3] << 16));
+                    *reinterpret_cast<uint2 *>(kr + hd) = make_uint2(vl[0] | (vl[1] << 16), vl[2] | (vl[3] << 16));
+                } else {
+                    uint16_t *vr = sd.vpool + rec + slot;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        vr[(size_t)(e + t) * KV_PAGE] = (uint16_t)vh[t];
+                        vr[(size_t)(hd + e + t) * KV_PAGE] = (uint16_t)vl[t];
+                    }
+                }
             }
         } else {  // G_HEAD
             const float rs = mi.rstd[m];
@@ -550,7 +561,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
             const int page = sd.page_table[pos / KV_PAGE];
             mi.pos[m] = pos;
-            mi.kvoff[m] = ((((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE + (pos % KV_PAGE)) * 2 * md.hd;
+            mi.kvoff[m] = (((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
         }
         const int half = md.hd >> 1;
         for (int i = tid; i < rows * half; i += WG_THREADS) {
@@ -719,31 +730,46 @@ __device__ __forceinline__ void unpack4_sum(const uint2 &hi, const uint2 &lo, fl
     f[3] = __uint_as_float(hi.y & 0xFFFF0000u) + __uint_as_float(lo.y & 0xFFFF0000u);
 }
 
-// Work item = (session, head, chunk of up to ATT_ROWS query rows, split of the position
-// range); the host picks the number of splits so that the items cover the chip, because one
-// compute unit alone cannot pull a head's cache fast enough.  The waves of the workgroup
-// share the split's positions; HD/4 lanes handle one cached position per step, four values
-// each.  q and the cached k use the same pair-interleaved order inside a head, so their dot
-// product is unchanged.  With one split the normalised output is written directly.
-// Otherwise every item writes un-normalised partials (accumulator, running max, running sum)
-// and counts itself in the unit's counter; the item that arrives last merges the unit's
-// partials in split order (so the result does not depend on arrival order) and clears the
-// counter for the next launch.  Nothing waits.
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+
+__device__ __forceinline__ bf16x8_t pack_bf16x8(const uint32_t *h)
+{
+    return __builtin_bit_cast(bf16x8_t, make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)));
+}
+
+// Work item = (session, head, chunk of up to ATT_ROWS = 16 query rows, split of the cache's
+// pages); the host picks the number of splits so that the items cover the chip and no wave
+// gets more than ATT_TILES pages.  A wave takes whole pages (16 positions), page
+// pg_lo + wave + t * WAVES being its tile t, and runs both products on the matrix cores:
+//   scores  S[pos][row] = K . q^T   v_mfma_f32_16x16x32_bf16, A = 16 cached positions x 32
+//           values straight from the page (lane l: position l & 15, values (l >> 4) * 8 ..),
+//           B = the rows' q; three MFMAs per 32 values (k_hi q_hi + k_lo q_hi + k_hi q_lo);
+//   output  O[row][dim] = p . V     v_mfma_f32_16x16x16bf16_1k, A = p in the layout the score
+//           MFMA left it in (lane l: row l & 15, positions (l >> 4) * 4 ..), B = V, which the
+//           cache stores transposed inside a page ([term][dim][position]) so that a lane's
+//           four positions are 8 contiguous bytes; p and V as two bf16 terms, three MFMAs.
+// All of a wave's score tiles stay in registers, so the softmax is two-pass inside the wave
+// (no rescaling).  q and the cached k use the same pair-interleaved order inside a head, so
+// their dot product is unchanged.  The waves' un-normalised results (accumulator, max, sum)
+// are merged through LDS in wave order.  With one split the normalised output is written
+// directly; otherwise every item writes its partial and counts itself in the unit's counter,
+// and the item that arrives last merges the unit's partials in split order (the result does
+// not depend on arrival order) and clears the counter for the next launch.  Nothing waits.
 template <int HD>
 __device__ void att_stage(const PassArgs &a, int layer, char *lds)
 {
-    constexpr int LPP = HD / 4;    // lanes per position
-    constexpr int PPI = 64 / LPP;  // positions per wave step
+    constexpr int KT = HD / 32;  // 32-value steps of a score
+    constexpr int NT = HD / 16;  // 16-column tiles of the output
     constexpr int REC = HD + 2;
-    constexpr int UNR = HD >= 128 ? 4 : 2;  // wave-steps whose loads are in flight together
     const int H = a.H, d = a.d, Kpad_d = a.Kpad_d, M = a.M;  // copies in the launch arguments: no load before the first address
     const int n_chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     const int n_splits = a.att_splits;
     const int n_items = a.n_sess * H * n_chunks * n_splits;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int grp = lane / LPP, e4 = lane % LPP;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lm = lane & 15, quad = lane >> 4;
     float *wbuf = reinterpret_cast<float *>(lds);  // [WAVES][ATT_ROWS][REC]
     int *lastf = reinterpret_cast<int *>(wbuf + (size_t)WAVES * ATT_ROWS * REC);
+    const size_t rec_page = (size_t)KV_PAGE * 2 * HD;  // elements of one (page, head) record
 
     trace_stamp(a, 0, 0);
     for (int item = blockIdx.x; item < n_items; item += a.nwg) {
@@ -758,93 +784,115 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
         const uint16_t *vpool = s == 0 ? a.sess0.vpool : sdp->vpool;
         const int n_pages = s == 0 ? a.sess0.n_pages : sdp->n_pages;
         const int P = a.mode == 1 ? a.pf_pos0 : (s == 0 ? a.sess0.kv_len : sdp->kv_len);  // position of the first row
-        const int n_pos = P + r0 + nr;            // positions visible to the chunk's last row
-        const int lo = (int)((long long)n_pos * sp / n_splits), hi = (int)((long long)n_pos * (sp + 1) / n_splits);
-        const int wlo = lo + (int)((long long)(hi - lo) * wave / WAVES);
-        const int whi = lo + (int)((long long)(hi - lo) * (wave + 1) / WAVES);
+        const int n_pos = P + r0 + nr;  // positions visible to the chunk's last row
+        const int n_pg = (n_pos + KV_PAGE - 1) / KV_PAGE;
+        const int pg_lo = n_pg * sp / n_splits, pg_hi = n_pg * (sp + 1) / n_splits;
+        const int T = max(0, (pg_hi - pg_lo - wave + WAVES - 1) / WAVES);  // tiles of this wave, <= ATT_TILES
+        const int my_pg = lane < T ? as_global(page_table)[pg_lo + wave + lane * WAVES] : 0;
 
-        float q[ATT_ROWS][4], acc[ATT_ROWS][4], mx[ATT_ROWS], l[ATT_ROWS];
+        // the rows' q as MFMA B operands, two bf16 terms (rows past the chunk repeat its last row)
+        const int mrow = min(lm, nr - 1);
+        bf16x8_t qh[KT], ql[KT];
+        {
+            const float *qp = a.sc.q + (size_t)(s * M + r0 + mrow) * d + hh * HD + quad * 8;
 #pragma unroll
-        for (int i = 0; i < ATT_ROWS; ++i) {
-            mx[i] = ATT_NEG;
-            l[i] = 0.f;
-            const float *qp = a.sc.q + (size_t)(s * M + r0 + min(i, nr - 1)) * d + hh * HD + e4 * 4;
-            f32x4_t qa = *as_global(reinterpret_cast<const f32x4_t *>(qp));
-            q[i][0] = qa[0]; q[i][1] = qa[1]; q[i][2] = qa[2]; q[i][3] = qa[3];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][e] = 0.f;
-        }
-
-        // positions in super-chunks of up to 1024: one page-table entry per lane, then rounds
-        // of UNR wave-steps whose K and V loads are all issued before any is used
-        for (int sb = wlo; sb < whi; sb += 1024) {
-            const int se = min(whi, sb + 1024);
-            const int fp = sb / KV_PAGE, npg = (se - 1) / KV_PAGE - fp + 1;
-            const int pg = lane < npg ? as_global(page_table)[fp + lane] : 0;
-            for (int pb = sb; pb < se; pb += PPI * UNR) {
-                uint2 kh[UNR], kl[UNR], vh[UNR], vl[UNR];
-#pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int p = pb + u * PPI + grp;
-                    const int pc = p < se ? p : sb;
-                    const int page = __shfl(pg, pc / KV_PAGE - fp, 64);
-                    const size_t off =
-                        ((((size_t)layer * n_pages + page) * H + hh) * KV_PAGE + (pc % KV_PAGE)) * (2 * HD) + e4 * 4;
-                    kh[u] = load_global8(kpool + off);
-                    kl[u] = load_global8(kpool + off + HD);
-                    vh[u] = load_global8(vpool + off);
-                    vl[u] = load_global8(vpool + off + HD);
-                }
-#pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int p = pb + u * PPI + grp;
-                    const bool live = p < se;
-                    float kf[4], vf[4];
-                    unpack4_sum(kh[u], kl[u], kf);
-                    unpack4_sum(vh[u], vl[u], vf);
-#pragma unroll
-                    for (int i = 0; i < ATT_ROWS; ++i) {
-                        float sdot = q[i][0] * kf[0] + q[i][1] * kf[1] + q[i][2] * kf[2] + q[i][3] * kf[3];
-#pragma unroll
-                        for (int off2 = 1; off2 < LPP; off2 <<= 1) sdot += __shfl_xor(sdot, off2, 64);
-                        const float sc = sdot * a.att_scale;
-                        if (live && i < nr && p <= P + r0 + i) {
-                            float nm = fmaxf(mx[i], sc);
-                            float corr = __expf(mx[i] - nm), pe = __expf(sc - nm);
-                            l[i] = l[i] * corr + pe;
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[i][e] = acc[i][e] * corr + pe * vf[e];
-                            mx[i] = nm;
-                        }
-                    }
-                }
-            }
-        }
-        trace_stamp(a, 0, 1);
-        // merge the position groups of the wave
-#pragma unroll
-        for (int i = 0; i < ATT_ROWS; ++i) {
-#pragma unroll
-            for (int off2 = LPP; off2 < 64; off2 <<= 1) {
-                float om = __shfl_xor(mx[i], off2, 64), ol = __shfl_xor(l[i], off2, 64);
-                float nm = fmaxf(mx[i], om);
-                float c0 = __expf(mx[i] - nm), c1 = __expf(om - nm);
-                l[i] = l[i] * c0 + ol * c1;
+            for (int kt = 0; kt < KT; ++kt) {
+                f32x4_t x0 = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32));
+                f32x4_t x1 = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32 + 4));
+                uint32_t h[8], l[8];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float oa = __shfl_xor(acc[i][e], off2, 64);
-                    acc[i][e] = acc[i][e] * c0 + oa * c1;
+                    split_bf16(x0[e], h[e], l[e]);
+                    split_bf16(x1[e], h[4 + e], l[4 + e]);
                 }
-                mx[i] = nm;
+                qh[kt] = pack_bf16x8(h);
+                ql[kt] = pack_bf16x8(l);
             }
-            if (grp == 0) {
-                float *w = wbuf + ((size_t)wave * ATT_ROWS + i) * REC;
-                *reinterpret_cast<float4 *>(w + e4 * 4) = make_float4(acc[i][0], acc[i][1], acc[i][2], acc[i][3]);
-                if (e4 == 0) {
-                    w[HD] = mx[i];
-                    w[HD + 1] = l[i];
+        }
+
+        // pass 1: score tiles
+        f32x4_t S[ATT_TILES];
+        const int last_pos = P + r0 + mrow;  // last position this lane's row may see
+#pragma unroll
+        for (int t = 0; t < ATT_TILES; ++t) {
+            S[t] = (f32x4_t){ATT_NEG, ATT_NEG, ATT_NEG, ATT_NEG};
+            if (t < T) {
+                const int page = __builtin_amdgcn_readlane(my_pg, t);
+                const uint16_t *kb = kpool + (((size_t)layer * n_pages + page) * H + hh) * rec_page + (size_t)lm * (2 * HD) + quad * 8;
+                uint4 kh[KT], kl[KT];
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    kh[kt] = load_global16(kb + kt * 32);
+                    kl[kt] = load_global16(kb + HD + kt * 32);
+                }
+                f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    const bf16x8_t Ah = __builtin_bit_cast(bf16x8_t, kh[kt]), Al = __builtin_bit_cast(bf16x8_t, kl[kt]);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ah, qh[kt], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Al, qh[kt], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(Ah, ql[kt], acc, 0, 0, 0);
+                }
+                const int pos0 = (pg_lo + wave + t * WAVES) * KV_PAGE + quad * 4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) S[t][r] = pos0 + r <= last_pos ? acc[r] * a.att_scale : ATT_NEG;
+            }
+        }
+        if (a.sc.trace) trace_stamp(a, 0, 1);
+        float mx = ATT_NEG;
+#pragma unroll
+        for (int t = 0; t < ATT_TILES; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mx = fmaxf(mx, S[t][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+
+        // pass 2: probabilities and output tiles
+        f32x4_t O[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) O[nt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+        float lsum = 0.f;
+#pragma unroll
+        for (int t = 0; t < ATT_TILES; ++t) {
+            if (t < T) {
+                const int page = __builtin_amdgcn_readlane(my_pg, t);
+                const uint16_t *vb = vpool + (((size_t)layer * n_pages + page) * H + hh) * rec_page + (size_t)lm * KV_PAGE + quad * 4;
+                uint2 vh[NT], vl[NT];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    vh[nt] = load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
+                    vl[nt] = load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
+                }
+                uint32_t ph[4], pl[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float pr = S[t][r] > 0.5f * ATT_NEG ? __expf(S[t][r] - mx) : 0.f;
+                    lsum += pr;
+                    split_bf16(pr, ph[r], pl[r]);
+                }
+                const s16x4_t Ph = __builtin_bit_cast(s16x4_t, make_uint2(ph[0] | (ph[1] << 16), ph[2] | (ph[3] << 16)));
+                const s16x4_t Pl = __builtin_bit_cast(s16x4_t, make_uint2(pl[0] | (pl[1] << 16), pl[2] | (pl[3] << 16)));
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const s16x4_t Vh = __builtin_bit_cast(s16x4_t, vh[nt]), Vl = __builtin_bit_cast(s16x4_t, vl[nt]);
+                    O[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph, Vh, O[nt], 0, 0, 0);
+                    O[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Pl, Vh, O[nt], 0, 0, 0);
+                    O[nt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(Ph, Vl, O[nt], 0, 0, 0);
                 }
             }
+        }
+        lsum += __shfl_xor(lsum, 16, 64);
+        lsum += __shfl_xor(lsum, 32, 64);
+        // this wave's record: lane holds O[row quad*4 + r][column nt*16 + lm]; max and sum per row lm
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (quad * 4 + r < nr) wbuf[((size_t)wave * ATT_ROWS + quad * 4 + r) * REC + nt * 16 + lm] = O[nt][r];
+        if (quad == 0 && lm < nr) {
+            float *w = wbuf + ((size_t)wave * ATT_ROWS + lm) * REC;
+            w[HD] = mx;
+            w[HD + 1] = lsum;
         }
         __syncthreads();
         trace_stamp(a, 0, 2);
@@ -1216,6 +1264,17 @@ __global__ void mfma_layout_probe_kernel(const uint4 *a, const uint4 *b, float *
     bf16x8_t B = __builtin_bit_cast(bf16x8_t, b[threadIdx.x]);
     f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, B, acc, 0, 0, 0);
+    for (int r = 0; r < 4; ++r) out[threadIdx.x * 4 + r] = acc[r];
+}
+
+// the same for v_mfma_f32_16x16x16bf16_1k: A[i][k] from lane (i + 16*(k/4)) element k%4,
+// B[k][j] likewise with j, D as above
+__global__ void mfma16_layout_probe_kernel(const uint2 *a, const uint2 *b, float *out)
+{
+    s16x4_t A = __builtin_bit_cast(s16x4_t, a[threadIdx.x]);
+    s16x4_t B = __builtin_bit_cast(s16x4_t, b[threadIdx.x]);
+    f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
+    acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(A, B, acc, 0, 0, 0);
     for (int r = 0; r < 4; ++r) out[threadIdx.x * 4 + r] = acc[r];
 }
 

@@ -500,15 +500,18 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 
 // ------------------------------------------------------------------ sessions
 
-// Splits of the position range per attention unit: enough items to occupy every compute
-// unit (one unit alone pulls a head's cache too slowly), at least 32 positions each.
+// Splits of the cache's pages per attention unit: enough items to occupy every compute unit
+// (one unit alone pulls a head's cache too slowly), at least one page per split, and no more
+// than ATT_TILES pages per wave.
 static int attention_splits(const ee_model *m, int n_sess, int M, int n_pos_max)
 {
-    int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
-    int units = n_sess * m->cfg.n_heads * chunks;
-    int s = std::min(m->nwg / std::max(units, 1), n_pos_max / 32);
+    const int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
+    const int units = n_sess * m->cfg.n_heads * chunks;
+    const int pages = (n_pos_max + KV_PAGE - 1) / KV_PAGE;
+    const int forced = (pages + ATT_TILES * WAVES - 1) / (ATT_TILES * WAVES);
+    int s = std::min(m->nwg / std::max(units, 1), pages);
     if (const char *e = getenv("EE_ATT_SPLITS")) s = atoi(e);
-    return std::max(1, std::min(s, ATT_MAX_SPLITS));
+    return std::min(std::max(std::max(1, s), forced), ATT_MAX_SPLITS);
 }
 
 extern "C" int ee_session_free(ee_session *s)
@@ -538,7 +541,10 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     *out = nullptr;
     if (max_gamma < 1 || max_gamma > EE_MAX_M - 1) return fail(EE_EINVAL, "ee_session_create: max_gamma %d not in [1,%d]", max_gamma, EE_MAX_M - 1);
     if (max_gamma + 1 > m->cfg.max_rows) return fail(EE_EINVAL, "ee_session_create: max_gamma+1 exceeds the model's max_rows %d", m->cfg.max_rows);
-    if (max_ctx < max_gamma + 2 || max_ctx > (1 << 20)) return fail(EE_EINVAL, "ee_session_create: max_ctx %d out of range", max_ctx);
+    // attention keeps at most ATT_TILES pages per wave and ATT_MAX_SPLITS splits per head
+    const int ctx_cap = ATT_MAX_SPLITS * ATT_TILES * WAVES * KV_PAGE;
+    if (max_ctx < max_gamma + 2 || max_ctx > ctx_cap)
+        return fail(EE_EINVAL, "ee_session_create: max_ctx %d out of range (at most %d)", max_ctx, ctx_cap);
     HIP_TRY(hipSetDevice(m->device));
     ee_session *s = new (std::nothrow) ee_session();
     if (!s) return fail(EE_EDEVICE, "out of host memory");
@@ -625,9 +631,10 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
-        // items = units * splits with splits <= max(1, nwg / units)
-        size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
-        size_t max_items = std::max<size_t>(max_units, (size_t)m->nwg) * ATT_MAX_SPLITS;
+        // items = units * splits, splits <= max(nwg / units, pages / (ATT_TILES * WAVES) rounded up)
+        const size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
+        const size_t forced = ((size_t)s->n_pages + ATT_TILES * WAVES - 1) / (ATT_TILES * WAVES);
+        const size_t max_items = max_units * forced + (size_t)m->nwg;
         S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
         S_TRY(dev_alloc(s->allocs, &sc.att_count, max_units));
     }
@@ -1256,6 +1263,35 @@ extern "C" int ee_debug_mfma_layout(int device)
             for (int k = 0; k < 32; ++k) ref += A[i][k] * B[k][j];
             if (out[l * 4 + r] != ref) ++bad;
         }
-    if (bad) return fail(EE_EDEVICE, "MFMA lane layout differs from the assumed one in %d of 256 elements", bad);
+    if (bad) return fail(EE_EDEVICE, "MFMA 16x16x32 lane layout differs from the assumed one in %d of 256 elements", bad);
+
+    // v_mfma_f32_16x16x16bf16_1k: the first 16 k of the same matrices, four k per lane
+    uint16_t ga[64 * 4], gb[64 * 4];
+    for (int l = 0; l < 64; ++l)
+        for (int e = 0; e < 4; ++e) {
+            ga[l * 4 + e] = bf(A[l & 15][(l >> 4) * 4 + e]);
+            gb[l * 4 + e] = bf(B[(l >> 4) * 4 + e][l & 15]);
+        }
+    uint2 *ea = nullptr, *eb = nullptr;
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&ea), sizeof ga));
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&eb), sizeof gb));
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&dout), 256 * sizeof(float)));
+    HIP_TRY(hipMemcpy(ea, ga, sizeof ga, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(eb, gb, sizeof gb, hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(mfma16_layout_probe_kernel, dim3(1), dim3(64), 0, 0, ea, eb, dout);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpy(out, dout, sizeof out, hipMemcpyDeviceToHost));
+    hipFree(ea);
+    hipFree(eb);
+    hipFree(dout);
+    bad = 0;
+    for (int l = 0; l < 64; ++l)
+        for (int r = 0; r < 4; ++r) {
+            int i = (l >> 4) * 4 + r, j = l & 15;
+            float ref = 0.f;
+            for (int k = 0; k < 16; ++k) ref += A[i][k] * B[k][j];
+            if (out[l * 4 + r] != ref) ++bad;
+        }
+    if (bad) return fail(EE_EDEVICE, "MFMA 16x16x16 lane layout differs from the assumed one in %d of 256 elements", bad);
     return EE_OK;
 }
