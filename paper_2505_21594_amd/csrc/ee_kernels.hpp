@@ -45,11 +45,19 @@ __device__ __forceinline__ const EE_GLOBAL T *as_global(const T *p)
     return (const EE_GLOBAL T *)(p);
 }
 
-// 16-byte weight load.  Plain loads: on this part non-temporal loads measured about 10 %
-// slower for the same access pattern.
-__device__ __forceinline__ uint4 load_stream16(const uint4 *p)
+// 16-byte weight load of a tile: buffer load with the stage's weights as the resource, the
+// lane's 16 bytes as the vector offset and the tile's byte offset as the scalar offset, so the
+// stream needs no per-tile address arithmetic in vector registers.  Plain cache policy: on
+// this part non-temporal loads measured about 10 % slower for the same access pattern.
+typedef __amdgpu_buffer_rsrc_t WRes;
+__device__ __forceinline__ WRes weight_resource(const uint4 *W)
 {
-    u32x4_t v = *as_global(reinterpret_cast<const u32x4_t *>(p));
+    // raw buffer, no stride, maximal range (offsets stay inside the stage's allocation)
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(W), 0, 0x7FFFFFFF, 0x00020000);
+}
+__device__ __forceinline__ uint4 load_tile16(WRes r, int lane_off, int tile_off)
+{
+    u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, tile_off, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
@@ -253,18 +261,21 @@ __device__ __forceinline__ Seg seg_setup(const GemmPlan &pl, int nt0, int n_loca
     return s;
 }
 
-// address of the wave's tile number `step` (see GemmPlan): slot (step*nwg + g)*WAVES + wave
-__device__ __forceinline__ const uint4 *tile_ptr(const uint4 *W, int nwg, int wave, int step)
+// byte offset of the wave's tile number `step` (see GemmPlan): slot (step*nwg + g)*WAVES + wave;
+// at most the stage's bytes, below 2^31
+__device__ __forceinline__ int tile_off(int nwg, int wave, int step)
 {
-    return W + ((size_t)((size_t)step * nwg + blockIdx.x) * WAVES + wave) * 64 + (threadIdx.x & 63);
+    return ((step * nwg + (int)blockIdx.x) * WAVES + wave) * 1024;
 }
 
 // first min(D, s.n) tiles of the wave's sequence in segment s
 __device__ __forceinline__ void seg_prefetch(const uint4 *__restrict__ W, int nwg, int wave, const Seg &s, uint4 (&pre)[D])
 {
+    const WRes res = weight_resource(W);
+    const int lane_off = (threadIdx.x & 63) * 16;
 #pragma unroll
     for (int j = 0; j < D; ++j)
-        if (j < s.n) pre[j] = load_stream16(tile_ptr(W, nwg, wave, s.step0 + j));
+        if (j < s.n) pre[j] = load_tile16(res, lane_off, tile_off(nwg, wave, s.step0 + j));
 }
 
 struct NextGemm {  // the GEMM stage that follows in the same launch
@@ -312,30 +323,27 @@ __device__ __forceinline__ void store_split4(uint16_t *hi_p, uint16_t *lo_p, siz
     store_dev64(lo_p + idx, make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16)));
 }
 
-// copy K-block (kst, klen) of the input's two bf16 terms into LDS: xs_hi | xs_lo, [rows][xs_stride]
-__device__ __forceinline__ void stage_x(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int klen, char *lds)
+// Wave-private staging of the GEMM input: the wave copies the k-slice it multiplies with,
+// [kst + s0, kst + s0 + slen) k-tiles of every row and of both bf16 terms, from memory
+// straight into LDS (layout xs_hi | xs_lo, each [rows][xs_stride]).  No registers hold the
+// data and no other wave reads this slice, so no workgroup barrier is needed: the wave waits
+// for its own loads (wait_vmem) and goes on.  One load instruction moves up to 64 x 16 bytes
+// of one row to consecutive LDS addresses.  DEV = true reads with device scope (the input was
+// written earlier in the same launch by other workgroups).
+#define EE_LDS __attribute__((address_space(3)))
+template <bool DEV>
+__device__ __forceinline__ void stage_x_wave(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int s0, int slen,
+                                             char *lds, int lane)
 {
-    uint16_t *xs_hi = reinterpret_cast<uint16_t *>(lds);
-    const int c8 = klen * 4;           // 16-byte chunks per row
-    const int total = rows * c8 * 2;   // both terms
-    constexpr int UB = 6;              // chunks per thread whose loads are issued together
-    const int half = rows * c8;
-    for (int i0 = opaque(threadIdx.x); i0 < total; i0 += WG_THREADS * UB) {
-        uint4 v[UB];
-        int dst[UB];
-#pragma unroll
-        for (int u = 0; u < UB; ++u) {
-            const int i = min(i0 + u * WG_THREADS, total - 1);  // clamped: the load is always in bounds
-            const int term = i >= half ? 1 : 0;
-            const int j = i - term * half;
-            const int row = j / c8, c = j - row * c8;
-            const uint16_t *src = (term ? in.lo : in.hi) + (size_t)row * in.ldx + (size_t)kst * 32 + c * 8;
-            v[u] = load_dev128(src);
-            dst[u] = (term * rows + row) * pl.xs_stride + c * 8;
-        }
-#pragma unroll
-        for (int u = 0; u < UB; ++u)
-            if (i0 + u * WG_THREADS < total) *reinterpret_cast<uint4 *>(xs_hi + dst[u]) = v[u];
+    const int nchunk = slen * 4;  // 16-byte chunks of the slice in one row
+    for (int tr = 0; tr < 2 * rows; ++tr) {
+        const int term = tr >= rows ? 1 : 0, row = tr - term * rows;
+        const uint16_t *src = (term ? in.lo : in.hi) + (size_t)row * in.ldx + (size_t)(kst + s0) * 32;
+        char *dst = lds + ((size_t)tr * pl.xs_stride + (size_t)s0 * 32) * 2;
+        for (int c0 = 0; c0 < nchunk; c0 += 64)
+            if (c0 + lane < nchunk)
+                __builtin_amdgcn_global_load_lds((const EE_GLOBAL void *)(src + (size_t)(c0 + lane) * 8),
+                                                 (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, DEV ? 16 : 0);
     }
 }
 
@@ -587,9 +595,12 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const bool restage = pl.nKB > 1 || gi == 0;
             if (restage) {
                 if (gi > 0 || kb > 0) __syncthreads();  // x_hat of the previous block is dead
-                stage_x(pl, in, rows, s.kst, s.klen, lds);
+                if (a.ph_hi - a.ph_lo > 1)
+                    stage_x_wave<true>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
+                else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
+                    stage_x_wave<false>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
                 if (in.ss && gi == 0 && kb == 0) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
-                __syncthreads();
+                wait_vmem();  // this wave's slice is in LDS (and its first weight tiles have arrived)
                 trace_stamp(a, tsi, 1 + min(kb, 1));
             }
 
@@ -608,14 +619,16 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                     }
             }
             int ntg = 0, kk = 0;  // compute cursor
-            const uint4 *wp = tile_ptr(W, a.nwg, wave, s.step0);
-            const size_t wstep = (size_t)a.nwg * WAVES * 64;  // one step further in the wave's sequence
+            const WRes wres = weight_resource(W);
+            const int lane_off = lane * 16;
+            const int woff = tile_off(a.nwg, wave, s.step0);
+            const int wstep = a.nwg * WAVES * 1024;  // bytes from one tile of the wave's sequence to the next
             for (int i = 0; i < s.n; i += D) {
 #pragma unroll
                 for (int j = 0; j < D; ++j) {
                     if (i + j < s.n) {
                         uint4 av = buf[j];
-                        if (i + j + D < s.n) buf[j] = load_stream16(wp + (size_t)(i + j + D) * wstep);
+                        if (i + j + D < s.n) buf[j] = load_tile16(wres, lane_off, woff + (i + j + D) * wstep);
                         bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
                         const int xo = (s.s0 + kk) * 32 + bk;
 #pragma unroll
