@@ -10,7 +10,7 @@ namespace ee {
 
 constexpr int WAVES = 12;                // waves per workgroup: three per SIMD, 168 VGPRs each
 constexpr int WG_THREADS = WAVES * 64;
-constexpr int PF_DEPTH = 8;               // weight tiles (1 KB each) in flight per wave
+constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
 constexpr int KV_PAGE = 16;              // positions per KV page
 constexpr int ATT_ROWS = 16;             // query rows of one attention item (one MFMA tile)
 constexpr int ATT_TILES = 8;             // KV pages (score tiles) a wave keeps in registers per item
@@ -99,7 +99,10 @@ struct Scratch {
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
 struct PassArgs {
-    const ModelDev *md;                  // device copy of the model descriptor
+    const ModelDev *md;                  // device copy of the model descriptor (tables indexed by stage kind)
+    ModelDev mdv;                        // the descriptor by value (fields with constant names only)
+    GemmPlan plan0;                      // plan and weights of the launch's first GEMM stage
+    const uint4 *W0;
     Scratch sc;
     int nwg;
     int n_sess, M, rows;                 // rows = n_sess * M

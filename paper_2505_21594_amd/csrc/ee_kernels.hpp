@@ -52,8 +52,11 @@ __device__ __forceinline__ const EE_GLOBAL T *as_global(const T *p)
 typedef __amdgpu_buffer_rsrc_t WRes;
 __device__ __forceinline__ WRes weight_resource(const uint4 *W)
 {
-    // raw buffer, no stride, maximal range (offsets stay inside the stage's allocation)
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint4 *>(W), 0, 0x7FFFFFFF, 0x00020000);
+    // raw buffer, no stride, maximal range (offsets stay inside the stage's allocation).  The
+    // pointer is the same in every lane; saying so keeps the resource in scalar registers.
+    const unsigned long long p = reinterpret_cast<unsigned long long>(W);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)p), hi = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(((unsigned long long)hi << 32) | lo), 0, 0x7FFFFFFF, 0x00020000);
 }
 __device__ __forceinline__ uint4 load_tile16(WRes r, int lane_off, int tile_off)
 {
@@ -376,7 +379,7 @@ struct GemmEpi {           // what the O / DN epilogue produces besides h
 __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const GemmPlan &pl, int nt_first,
                                               int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds)
 {
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     const float *slots = reinterpret_cast<const float *>(lds + md.lds_slots_off);
     const int tid = opaque(threadIdx.x);
     const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
@@ -537,7 +540,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                              const GemmIn &in, const GemmEpi &ep, uint4 (&buf)[D], bool &have_pre, const NextGemm &next,
                              char *lds, int tsi)
 {
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rows = a.rows;
     const Misc mi = misc_views(md, lds);
@@ -695,7 +698,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
 // columns [g*cw, (g+1)*cw) and also emits the first layer's GEMM input and its share of h^2
 __device__ void embed_stage(const PassArgs &a, char *lds)
 {
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     const int d = md.d, rows = a.rows, tid = threadIdx.x;
     const int cw = ((d + a.nwg - 1) / a.nwg + 3) & ~3;  // columns per workgroup, multiple of 4
     const int n0 = blockIdx.x * cw;
@@ -1002,7 +1005,7 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
 __device__ void accept_stage(const PassArgs &a, char *lds)
 {
     if (blockIdx.x != 0) return;
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     const int rows = a.rows, M = a.M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int *tok = reinterpret_cast<int *>(lds);
@@ -1115,7 +1118,7 @@ __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
 
 __device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
 {
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     switch (kind) {
     case G_QKV: return GemmIn{a.sc.xn[0], a.sc.xn[1], md.Kpad_d, a.sc.ss_a};
     case G_O: return GemmIn{a.sc.attn[0], a.sc.attn[1], md.Kpad_d, nullptr};
@@ -1127,7 +1130,7 @@ __device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
 
 __device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int layer)
 {
-    const ModelDev &md = *a.md;
+    const ModelDev &md = a.mdv;
     GemmEpi ep = {nullptr, nullptr, nullptr};
     if (kind == G_O) {
         ep.gain_xn = md.g_ffn + (size_t)layer * md.d;
@@ -1146,7 +1149,10 @@ template <int MT>
 __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
 {
     extern __shared__ __align__(16) char lds[];
-    const ModelDev &md = *a.md;
+    // The tables indexed by the stage kind are read from the descriptor in device memory; the
+    // first stage's entries (the only ones of a one-stage launch) come with the launch
+    // arguments, so that nothing has to be loaded before the first weight address is known.
+    const ModelDev *mdp = a.md;
     unsigned nbar = 0;
     if (a.mode == 2) {  // measurement aid: layer_end grid barriers and nothing else
         for (int i = 0; i < a.layer_end; ++i)
@@ -1165,13 +1171,16 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
         NextGemm nx = {nullptr, nullptr};
         if (ph + 1 < a.ph_hi) {
             const StageDesc sn = stage_decode(a, ph + 1);
-            nx.pl = &md.plan[sn.kind];
-            nx.W = md.w[sn.kind] + (size_t)sn.layer * md.wstride[sn.kind];
+            nx.pl = &mdp->plan[sn.kind];
+            nx.W = mdp->w[sn.kind] + (size_t)sn.layer * mdp->wstride[sn.kind];
         }
         const GemmIn in = gemm_input(a, st.kind);
         const GemmEpi ep = gemm_epi(a, st.kind, st.layer);
-        gemm_stage_t<MT>(a, st.kind, st.layer, md.plan[st.kind], md.w[st.kind] + (size_t)st.layer * md.wstride[st.kind],
-                         in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
+        if (ph == a.ph_lo)
+            gemm_stage_t<MT>(a, st.kind, st.layer, a.plan0, a.W0, in, ep, buf, have_pre, nx, lds, 0);
+        else
+            gemm_stage_t<MT>(a, st.kind, st.layer, mdp->plan[st.kind], mdp->w[st.kind] + (size_t)st.layer * mdp->wstride[st.kind],
+                             in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
         trace_stamp(a, ph - a.ph_lo, 6);
     }
 }

@@ -747,6 +747,13 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         a.trace_base = lead->trace_n;
         lead->trace_n = std::min(lead->trace_n + (end - ph) * EE_TRACE_SLOTS, EE_TRACE_MAX - 64 * EE_TRACE_SLOTS);
         pass_kernel_t k = type == ST_GEMM ? chain_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
+        if (type == ST_GEMM) {  // the first stage's plan and weights travel with the launch
+            const int code = launch_code(a, ph, ph + 1);  // EE_LAUNCH_QKV .. EE_LAUNCH_HEAD = GemmKind
+            const int idx = ph - (a.do_embed ? 1 : 0);
+            const int layer = code == EE_LAUNCH_HEAD ? 0 : a.layer_begin + idx / per_layer;
+            a.plan0 = m->host_md.plan[code];
+            a.W0 = m->host_md.w[code] + (size_t)layer * m->host_md.wstride[code];
+        }
         const bool timed = (lead->flags & EE_TIME_LAUNCHES) && a.mode == 0;
         if (timed) {
             const size_t i = lead->lt_codes.size();
@@ -771,6 +778,7 @@ static void base_args(const ee_session *lead, PassArgs &a)
 {
     memset(&a, 0, sizeof a);
     a.md = lead->m->dev_md;
+    a.mdv = lead->m->host_md;
     a.sc = lead->sc;
     a.nwg = lead->m->nwg;
     a.H = lead->m->host_md.H;
