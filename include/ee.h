@@ -198,6 +198,10 @@ int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, 
    barrier entered). */
 int ee_debug_trace(ee_session *s, unsigned long long *out, int max_values, int *n_values);
 
+/* Debug (EE_TRACE sessions): the same clock at the start and at the end of every workgroup of
+   every launch of the last verify pass, in launch order: launches x workgroups x 2 values. */
+int ee_debug_trace_workgroups(ee_session *s, unsigned long long *out, int max_values, int *n_values);
+
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
    kernels assume and compares with the plain 16x32 . 32x16 product. */
 int ee_debug_mfma_layout(int device);

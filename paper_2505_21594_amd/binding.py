@@ -37,7 +37,7 @@ EXPORTS = [
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost", "ee_debug_trace",
-    "ee_launch_times",
+    "ee_launch_times", "ee_debug_trace_workgroups",
 ]
 
 
@@ -108,6 +108,7 @@ def load_library():
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
     lib.ee_debug_trace.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
+    lib.ee_debug_trace_workgroups.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
     lib.ee_launch_times.argtypes = [vp, i32p, P(ctypes.c_float), ci, P(ci)]
     for name in EXPORTS:
         if name != "ee_last_error":
@@ -256,6 +257,13 @@ class Session:
         n = ctypes.c_int()
         _check(self._l.ee_debug_trace(self._h, buf, 1 << 14, ctypes.byref(n)))
         return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, 8).copy()
+
+    def ee_debug_trace_workgroups(self) -> np.ndarray:
+        cap = 2048 * self.model.n_workgroups * 2
+        buf = (ctypes.c_ulonglong * cap)()
+        n = ctypes.c_int()
+        _check(self._l.ee_debug_trace_workgroups(self._h, buf, cap, ctypes.byref(n)))
+        return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, self.model.n_workgroups, 2).copy()
 
     def ee_launch_times(self):
         """[(launch code, milliseconds)] of every launch of the last verify pass."""

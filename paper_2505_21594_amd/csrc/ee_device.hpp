@@ -43,6 +43,24 @@ struct GemmPlan {
     int steps;       // tile slots per wave (longest wave sequence)
 };
 
+// Units [u0, u1) of workgroup g.  Workgroups are dealt to the chip's 8 XCDs round-robin (XCD =
+// g % 8) and every XCD has its own path to memory, so the units are first split evenly over
+// the XCDs and then over the XCD's workgroups: with U not a multiple of nwg, a plain split
+// over g loads some XCDs up to 20 % more than others and the launch ends with them.
+constexpr int NUM_XCD = 8;
+__host__ __device__ inline void unit_range(int U, int nwg, int g, int &u0, int &u1)
+{
+    if (nwg % NUM_XCD != 0) {
+        u0 = (int)((long long)U * g / nwg);
+        u1 = (int)((long long)U * (g + 1) / nwg);
+        return;
+    }
+    const int x = g % NUM_XCD, j = g / NUM_XCD, per = nwg / NUM_XCD;
+    const int x0 = (int)((long long)U * x / NUM_XCD), x1 = (int)((long long)U * (x + 1) / NUM_XCD);
+    u0 = x0 + (int)((long long)(x1 - x0) * j / per);
+    u1 = x0 + (int)((long long)(x1 - x0) * (j + 1) / per);
+}
+
 enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };
 enum GemmKind { G_QKV = 0, G_O = 1, G_GU = 2, G_DN = 3, G_HEAD = 4 };
 enum StageType { ST_EMBED = 0, ST_GEMM = 1, ST_ATT = 2, ST_ACCEPT = 3, ST_NONE = 4 };

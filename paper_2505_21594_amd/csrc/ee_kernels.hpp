@@ -44,6 +44,13 @@ __device__ __forceinline__ const EE_GLOBAL T *as_global(const T *p)
 {
     return (const EE_GLOBAL T *)(p);
 }
+// The same for stores.  One generic (flat) access anywhere in a kernel also makes the compiler
+// treat the order of returning loads as unknown and wait for all of them at every use.
+template <typename T>
+__device__ __forceinline__ EE_GLOBAL T *as_global_mut(T *p)
+{
+    return (EE_GLOBAL T *)(p);
+}
 
 // 16-byte weight load of a tile: buffer load with the stage's weights as the resource, the
 // lane's 16 bytes as the vector offset and the tile's byte offset as the scalar offset, so the
@@ -104,13 +111,26 @@ __device__ __forceinline__ int opaque(int x)
 }
 // debug: stamp slot (stage-in-launch, k) with the 100 MHz wall clock, workgroup 0 only
 #define EE_TRACE_SLOTS 8
+#define EE_TRACE_WG_BASE (1 << 14)  // per-workgroup stamps follow workgroup 0's slots
 __device__ __forceinline__ void trace_stamp(const PassArgs &a, int stage_in_launch, int k)
 {
     if (a.sc.trace && blockIdx.x == 0 && threadIdx.x == 0)
         a.sc.trace[a.trace_base + stage_in_launch * EE_TRACE_SLOTS + k] = wall_clock64();
 }
+// debug: every workgroup stamps the start (k = 0) and the end (k = 1) of the launch
+__device__ __forceinline__ void trace_stamp_wg(const PassArgs &a, int k)
+{
+    if (a.sc.trace && threadIdx.x == 0)
+        a.sc.trace[EE_TRACE_WG_BASE + ((size_t)(a.trace_base / EE_TRACE_SLOTS) * a.nwg + blockIdx.x) * 2 + k] = wall_clock64();
+}
 // all vector memory operations of this wave have completed
-__device__ __forceinline__ void wait_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// (the builtin, not inline assembly: the compiler's own bookkeeping of loads in flight sees it,
+// so code after it is not made to wait again for loads that this wait has already covered)
+__device__ __forceinline__ void wait_vmem()
+{
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
+    asm volatile("" ::: "memory");
+}
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -172,18 +192,22 @@ __device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsi
 
 // ------------------------------------------------------------------ rows
 
+// Fields of session s's descriptor.  Session 0's descriptor also travels by value in the launch
+// arguments, so the common one-session pass needs no load from memory to find them.
+#define EE_SESS(a, s, field) ((s) == 0 ? (a).sess0.field : (a).sess[s].field)
+
 __device__ __forceinline__ int row_pos(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_pos0 + r;
     int s = r / a.M;
-    return a.sess[s].kv_len + (r - s * a.M);
+    return EE_SESS(a, s, kv_len) + (r - s * a.M);
 }
 
 __device__ __forceinline__ int row_token(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_tokens[r];
     int s = r / a.M, i = r - s * a.M;
-    return i == 0 ? a.sess[s].pending : a.sess[s].drafts[i - 1];
+    return i == 0 ? EE_SESS(a, s, pending) : EE_SESS(a, s, drafts)[i - 1];
 }
 
 // ------------------------------------------------------------------ LDS map
@@ -231,7 +255,8 @@ struct Seg {  // one (group, K-block) of a workgroup's tile sequence, seen from 
 
 __device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int &nt0, int &n_local)
 {
-    int u0 = (int)((long long)pl.U * g / nwg), u1 = (int)((long long)pl.U * (g + 1) / nwg);
+    int u0, u1;
+    unit_range(pl.U, nwg, g, u0, u1);
     nt0 = u0 * pl.tpu;
     n_local = (u1 - u0) * pl.tpu;
 }
@@ -459,18 +484,19 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             } else {
                 // cached value = hi + lo, two bf16 terms.  K: [position][term][hd]; V transposed
                 // inside the page: [term][hd][position] (see the attention stage)
-                const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
+                const int ses = a.mode == 1 ? 0 : m / a.M;
                 uint32_t vh[4], vl[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) split_bf16(v[t], vh[t], vl[t]);
                 const size_t rec = mi.kvoff[m] + (size_t)head * KV_PAGE * 2 * hd;  // this (page, head) record
                 const int slot = mi.pos[m] % KV_PAGE;
                 if (sect == 1) {
-                    uint16_t *kr = sd.kpool + rec + (size_t)slot * 2 * hd + e;
-                    *reinterpret_cast<uint2 *>(kr) = make_uint2(vh[0] | (vh[1] << 16), vh[2] | (vh[3] << 16));
-                    *reinterpret_cast<uint2 *>(kr + hd) = make_uint2(vl[0] | (vl[1] << 16), vl[2] | (vl[3] << 16));
+                    EE_GLOBAL uint16_t *kr = as_global_mut(EE_SESS(a, ses, kpool)) + rec + (size_t)slot * 2 * hd + e;
+                    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+                    *reinterpret_cast<EE_GLOBAL u32x2_t *>(kr) = (u32x2_t){vh[0] | (vh[1] << 16), vh[2] | (vh[3] << 16)};
+                    *reinterpret_cast<EE_GLOBAL u32x2_t *>(kr + hd) = (u32x2_t){vl[0] | (vl[1] << 16), vl[2] | (vl[3] << 16)};
                 } else {
-                    uint16_t *vr = sd.vpool + rec + slot;
+                    EE_GLOBAL uint16_t *vr = as_global_mut(EE_SESS(a, ses, vpool)) + rec + slot;
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         vr[(size_t)(e + t) * KV_PAGE] = (uint16_t)vh[t];
@@ -564,24 +590,6 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     trace_stamp(a, tsi, 0);
     // start the weight stream before anything else (unless the previous stage already did)
     if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
-    if (kind == G_QKV) {
-        // per-row position, KV slot and RoPE factors for the epilogue
-        if (tid < rows) {
-            const int m = tid;
-            const int pos = row_pos(a, m);
-            const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
-            const int page = sd.page_table[pos / KV_PAGE];
-            mi.pos[m] = pos;
-            mi.kvoff[m] = (((long long)layer * sd.n_pages + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
-        }
-        const int half = md.hd >> 1;
-        for (int i = tid; i < rows * half; i += WG_THREADS) {
-            int m = i / half, j = i - m * half;
-            const SessDev &sd = a.sess[a.mode == 1 ? 0 : m / a.M];
-            mi.rope[i] = sd.rope[(size_t)row_pos(a, m) * half + j];
-        }
-    }
-
     const uint16_t *xs_hi = reinterpret_cast<const uint16_t *>(lds);
     const uint16_t *xs_lo = xs_hi + (size_t)rows * pl.xs_stride;
     float *slots = reinterpret_cast<float *>(lds + md.lds_slots_off);
@@ -603,6 +611,25 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                 else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
                     stage_x_wave<false>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
                 if (in.ss && gi == 0 && kb == 0) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
+                if (kind == G_QKV && gi == 0 && kb == 0) {
+                    // per-row position, KV record and RoPE factors for the epilogue (read after the
+                    // workgroup barrier that precedes it)
+                    if (tid < rows) {
+                        const int m = tid;
+                        const int pos = row_pos(a, m);
+                        const int ses = a.mode == 1 ? 0 : m / a.M;
+                        const int page = as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
+                        mi.pos[m] = pos;
+                        mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
+                    }
+                    const int half = md.hd >> 1;
+                    for (int i = tid; i < rows * half; i += WG_THREADS) {
+                        int m = i / half, j = i - m * half;
+                        const int ses = a.mode == 1 ? 0 : m / a.M;
+                        const unsigned long long cs = *as_global(reinterpret_cast<const unsigned long long *>(EE_SESS(a, ses, rope) + (size_t)row_pos(a, m) * half + j));
+                        mi.rope[i] = make_float2(__uint_as_float((unsigned)cs), __uint_as_float((unsigned)(cs >> 32)));
+                    }
+                }
                 wait_vmem();  // this wave's slice is in LDS (and its first weight tiles have arrived)
                 trace_stamp(a, tsi, 1 + min(kb, 1));
             }
@@ -626,44 +653,60 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const int lane_off = lane * 16;
             const int woff = tile_off(a.nwg, wave, s.step0);
             const int wstep = a.nwg * WAVES * 1024;  // bytes from one tile of the wave's sequence to the next
-            for (int i = 0; i < s.n; i += D) {
+            const int woff_last = woff + (s.n - 1) * wstep;
+            // one tile: two MFMAs (both bf16 terms of the input); at the end of an n-tile's run
+            // the partial tile goes to the wave's slot in LDS
+            auto tile_step = [&](const uint4 &av) __attribute__((always_inline)) {
+                bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
+                const int xo = (s.s0 + kk) * 32 + bk;
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    uint4 bh = *reinterpret_cast<const uint4 *>(xs_hi + brow[mt] + xo);
+                    uint4 bl = *reinterpret_cast<const uint4 *>(xs_lo + brow[mt] + xo);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
+                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
+                }
+                if (++kk == s.slen) {
+                    // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        int m = mt * 16 + (lane & 15);
+                        if (m < rows) {
+                            float4 *dst = reinterpret_cast<float4 *>(
+                                slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
+                            float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
+                            if (kb > 0) {
+                                float4 o = *dst;
+                                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                            }
+                            *dst = v;
+                        }
+                        acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+                    }
+                    kk = 0;
+                    ++ntg;
+                }
+            };
+            // Full blocks of D tiles: every load is unconditional (the look-ahead is clamped to
+            // the segment's last tile), so the compiler can count the loads in flight and each
+            // use waits for exactly its own tile.  Loads under a condition make it wait for all
+            // of them, which halves what one wave can pull.
+            // Nothing may be in flight when the loop is entered, else (e.g. with the stores
+            // of an earlier epilogue still counted) the compiler falls back to waiting for all.
+            wait_vmem();
+            int i = 0;
+            for (; i + D <= s.n; i += D) {
 #pragma unroll
                 for (int j = 0; j < D; ++j) {
-                    if (i + j < s.n) {
-                        uint4 av = buf[j];
-                        if (i + j + D < s.n) buf[j] = load_tile16(wres, lane_off, woff + (i + j + D) * wstep);
-                        bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
-                        const int xo = (s.s0 + kk) * 32 + bk;
-#pragma unroll
-                        for (int mt = 0; mt < MT; ++mt) {
-                            uint4 bh = *reinterpret_cast<const uint4 *>(xs_hi + brow[mt] + xo);
-                            uint4 bl = *reinterpret_cast<const uint4 *>(xs_lo + brow[mt] + xo);
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
-                        }
-                        if (++kk == s.slen) {
-                            // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
-#pragma unroll
-                            for (int mt = 0; mt < MT; ++mt) {
-                                int m = mt * 16 + (lane & 15);
-                                if (m < rows) {
-                                    float4 *dst = reinterpret_cast<float4 *>(
-                                        slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
-                                    float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
-                                    if (kb > 0) {
-                                        float4 o = *dst;
-                                        v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                                    }
-                                    *dst = v;
-                                }
-                                acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-                            }
-                            kk = 0;
-                            ++ntg;
-                        }
-                    }
+                    // use the tile, then refill its registers: issuing the load first would need a
+                    // second set of registers and a copy (with a wait) at the end of the block
+                    tile_step(buf[j]);
+                    buf[j] = load_tile16(wres, lane_off, min(woff + (i + j + D) * wstep, woff_last));
                 }
             }
+#pragma unroll
+            for (int j = 0; j < D; ++j)
+                if (i + j < s.n) tile_step(buf[j]);
             // ---- fetch ahead: next segment of this stage, or the first tiles of the next GEMM stage
             const bool last_seg = (gi == n_groups - 1) && (kb == pl.nKB - 1);
             if (!last_seg) {
@@ -826,6 +869,17 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             }
         }
 
+        // V of the wave's first tile is fetched together with its K (most waves have one tile)
+        uint2 v0h[NT], v0l[NT];
+        if (T > 0) {
+            const int page = __builtin_amdgcn_readlane(my_pg, 0);
+            const uint16_t *vb = vpool + (((size_t)layer * n_pages + page) * H + hh) * rec_page + (size_t)lm * KV_PAGE + quad * 4;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                v0h[nt] = load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
+                v0l[nt] = load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
+            }
+        }
         // pass 1: score tiles
         f32x4_t S[ATT_TILES];
         const int last_pos = P + r0 + mrow;  // last position this lane's row may see
@@ -876,8 +930,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 uint2 vh[NT], vl[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    vh[nt] = load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
-                    vl[nt] = load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
+                    vh[nt] = t == 0 ? v0h[nt] : load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
+                    vl[nt] = t == 0 ? v0l[nt] : load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
                 }
                 uint32_t ph[4], pl[4];
 #pragma unroll
@@ -1159,6 +1213,7 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
             grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
         return;
     }
+    trace_stamp_wg(a, 0);
     uint4 buf[D];           // weight tiles in flight; carried from one stage into the next
     bool have_pre = false;  // buf holds the first tiles of the coming stage
     for (int ph = a.ph_lo; ph < a.ph_hi; ++ph) {
@@ -1183,13 +1238,16 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
                              in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
         trace_stamp(a, ph - a.ph_lo, 6);
     }
+    trace_stamp_wg(a, 1);
 }
 
 template <int HD>
 __global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a)
 {
     extern __shared__ __align__(16) char lds[];
+    trace_stamp_wg(a, 0);
     att_stage<HD>(a, stage_decode(a, a.ph_lo).layer, lds);
+    trace_stamp_wg(a, 1);
 }
 
 // embedding, accept: stage ph_lo
@@ -1197,10 +1255,12 @@ __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a)
 {
     extern __shared__ __align__(16) char lds[];
     const StageDesc st = stage_decode(a, a.ph_lo);
+    trace_stamp_wg(a, 0);
     if (st.type == ST_EMBED)
         embed_stage(a, lds);
     else if (st.type == ST_ACCEPT)
         accept_stage(a, lds);
+    trace_stamp_wg(a, 1);
 }
 
 // ------------------------------------------------------------------ load-time kernels

@@ -109,7 +109,8 @@ static int plan_max_local(int U, int tpu, int nwg)
 {
     int mx = 0;
     for (int g = 0; g < nwg; ++g) {
-        int u0 = (int)((long long)U * g / nwg), u1 = (int)((long long)U * (g + 1) / nwg);
+        int u0, u1;
+        unit_range(U, nwg, g, u0, u1);
         mx = std::max(mx, (u1 - u0) * tpu);
     }
     return mx;
@@ -140,7 +141,8 @@ static int plan_steps(const GemmPlan &p, int nwg)
 {
     int mx = 0;
     for (int g = 0; g < nwg; ++g) {
-        int u0 = (int)((long long)p.U * g / nwg), u1 = (int)((long long)p.U * (g + 1) / nwg);
+        int u0, u1;
+        unit_range(p.U, nwg, g, u0, u1);
         int n_local = (u1 - u0) * p.tpu;
         for (int w = 0; w < WAVES; ++w) {
             int per_tile = 0;
@@ -643,7 +645,8 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.bar_flags, (size_t)m->nwg));
     S_TRY(dev_alloc(s->allocs, &sc.err, 1));
-    if (flags & EE_TRACE) S_TRY(dev_alloc(s->allocs, &sc.trace, (size_t)EE_TRACE_MAX));
+    if (flags & EE_TRACE)  // workgroup 0's stage stamps, then (start, end) of every workgroup in every launch
+        S_TRY(dev_alloc(s->allocs, &sc.trace, (size_t)EE_TRACE_MAX + (size_t)(EE_TRACE_MAX / EE_TRACE_SLOTS) * m->nwg * 2));
     s->epoch = 0;
     S_HIP(hipDeviceSynchronize());
 #undef S_TRY
@@ -1215,6 +1218,21 @@ extern "C" int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max
         HIP_TRY(hipEventElapsedTime(&ms[i], s->lt_events[2 * i], s->lt_events[2 * i + 1]));
     }
     *n_launches = n;
+    return EE_OK;
+}
+
+// Debug (EE_TRACE sessions): (start, end) stamps of every workgroup in every launch of the last
+// verify pass, in launch order: n_launches x n_workgroups x 2 values.
+extern "C" int ee_debug_trace_workgroups(ee_session *s, unsigned long long *out, int max_values, int *n_values)
+{
+    if (!s || !out || !n_values) return fail(EE_EINVAL, "null argument");
+    if (!(s->flags & EE_TRACE)) return fail(EE_ESTATE, "ee_debug_trace_workgroups: session was created without EE_TRACE");
+    HIP_TRY(hipSetDevice(s->m->device));
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    int n = std::min(s->trace_n / EE_TRACE_SLOTS * s->m->nwg * 2, max_values);
+    HIP_TRY(hipMemcpy(out, s->sc.trace + EE_TRACE_MAX, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    *n_values = n;
     return EE_OK;
 }
 
