@@ -30,11 +30,13 @@ import eegen  # noqa: E402
 HBM_PEAK_GBS = 8000.0
 
 WORKLOADS = {
-    # name: (model config, prompt, gamma, exits, p_corrupt, max_rows)
-    "llama7b_g4_ctx512": (eegen.LLAMA7B, 512, 4, (8, 16), 0.3),
-    "llama7b_g8_ctx2048": (eegen.LLAMA7B, 2048, 8, (8, 16, 24), 0.5),
-    "llama13b_g5_ctx1024": (eegen.LLAMA13B, 1024, 5, (20,), 0.3),
-    "tiny_g4_ctx64": (eegen.TINY, 64, 4, (2,), 0.3),
+    # name: (model config, model file tag, prompt tokens, gamma, exits, corruption p (None: per session in
+    #        [0.1, 0.6]), sessions, embedding-prefix rows)
+    "llama7b_g4_ctx512": (eegen.LLAMA7B, "llama7b", 512, 4, (8, 16), 0.3, 1, 0),
+    "llama7b_g8_ctx2048": (eegen.LLAMA7B, "llama7b", 2048, 8, (8, 16, 24), 0.5, 1, 0),
+    "llama13b_g5_ctx1024": (eegen.LLAMA13B, "llama13b", 1024, 5, (20,), 0.3, 1, 0),
+    "llama7b_b8_vlm": (eegen.LLAMA7B, "llama7b", 64, 4, (16,), None, 8, 576),
+    "tiny_g4_ctx64": (eegen.TINY, "tiny", 64, 4, (2,), 0.3, 1, 0),
 }
 
 
@@ -62,28 +64,90 @@ def launch_bytes(cfg, code, P, M, B=1):
     }.get(code, 0)
 
 
-def per_launch_roofline(ee, model, cfg, prompt, first, drafts_per_round, ex, M, flags, passes):
+def per_launch_roofline(ee, run, passes):
     """Event pairs around every launch of `passes` further verify passes of the same
-    trajectory (a second session, so that the timed region above stays unperturbed).
+    trajectory (a second set of sessions, so that the timed region stays unperturbed).
     Returns per-launch-kind mean duration and achieved bandwidth."""
-    sess = model.session(len(prompt) + (passes + 2) * M + 16, max_gamma=M - 1, flags=flags | ee.TIME_LAUNCHES)
-    sess.ee_prefill(prompt)
+    sessions = run.make_sessions(extra_flags=ee.TIME_LAUNCHES, rounds=passes)
     acc = {}
     for r in range(passes):
-        P = sess.ee_kv_len()
-        sess.verify_sync(drafts_per_round[r], ex)
+        P = sum(s.ee_kv_len() for s in sessions) / len(sessions)
+        run.verify(sessions, r)
         if r == 0:
             continue  # first pass after prefill: cold instruction caches
-        for code, ms in sess.ee_launch_times():
+        for code, ms in sessions[0].ee_launch_times():
             name = ee.LAUNCH_NAMES[code]
             a = acc.setdefault(name, [0, 0.0, 0.0])
             a[0] += 1
             a[1] += ms
-            a[2] += launch_bytes(cfg, name, P, M)
-    sess.free()
+            a[2] += launch_bytes(run.cfg, name, P, run.M, run.B)
+    for s in sessions:
+        s.free()
     return {k: {"launches_per_pass": v[0] / (passes - 1), "avg_launch_us": v[1] / v[0] * 1e3,
                 "algorithmic_bytes_per_launch": v[2] / v[0],
                 "achieved_GBps": (v[2] / (v[1] * 1e-3) / 1e9) if v[2] else None} for k, v in acc.items()}
+
+
+class Run:
+    """One workload: the model, its sessions' prompts and every round's drafts."""
+
+    def __init__(self, ee, model, cfg, seed, n_prompt, gamma, exits, p, B, n_emb, flags):
+        self.ee, self.model, self.cfg, self.seed = ee, model, cfg, seed
+        self.n_prompt, self.gamma, self.M, self.exits, self.B, self.n_emb, self.flags = n_prompt, gamma, gamma + 1, list(exits), B, n_emb, flags
+        self.p = [p if p is not None else eegen.session_corruption_p(seed, b) for b in range(B)]
+        self.prompts = [eegen.prompt_tokens(seed, n_prompt, cfg.vocab, session=b) for b in range(B)]
+        self.embs = [eegen.embedding_prefix(seed, n_emb, cfg.d_model, session=b) if n_emb else None for b in range(B)]
+        self.drafts = []  # [round][session]
+
+    def make_sessions(self, extra_flags=0, rounds=0):
+        max_ctx = self.n_emb + self.n_prompt + (rounds + 2) * self.M + 16
+        out = []
+        for b in range(self.B):
+            s = self.model.session(max_ctx, max_gamma=self.gamma, flags=self.flags | extra_flags)
+            s.first = s.ee_prefill(self.prompts[b], emb=self.embs[b])
+            s.base = self.n_emb + self.n_prompt
+            out.append(s)
+        return out
+
+    def verify(self, sessions, r, wait=True):
+        if self.B == 1:
+            sessions[0].ee_verify(self.drafts[r][0], self.exits)
+        else:
+            self.ee.ee_verify_batch(sessions, self.drafts[r], self.exits)
+        if wait:
+            sessions[0].ee_wait_final()
+            for s in sessions[1:]:
+                s.ee_wait_final()
+
+    def rehearse(self, sessions, rounds):
+        """Untimed: walk the trajectory once to build every round's drafts (each session's greedy
+        continuation, corrupted), then roll the sessions back to their prompts."""
+        for r in range(rounds):
+            row = []
+            for b, s in enumerate(sessions):
+                g = gpu_greedy(s, self.gamma)
+                row.append(eegen.corrupt_drafts(g, self.p[b], self.cfg.vocab, self.seed, r, session=b))
+            self.drafts.append(row)
+            self.verify(sessions, r)
+        for s in sessions:
+            s.ee_kv_truncate(s.base)
+            s.ee_set_pending(s.first)
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` on `workload` from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a plain copy kernel's reading), or None."""
+    d = os.path.join(ROOT, "profiles")
+    try:
+        for f in sorted(os.listdir(d)):
+            if f.startswith("hbm_traffic"):
+                for line in open(os.path.join(d, f)):
+                    t = line.split()
+                    if len(t) == 4 and t[0] == "traffic" and t[1] == kernel and t[2] == workload:
+                        return float(t[3])
+    except OSError:
+        pass
+    return None
 
 
 def model_file(cfg, name, seed, workdir):
@@ -152,73 +216,68 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chain-launches", action="store_true",
                     help="run consecutive GEMM stages in one persistent launch with grid barriers")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run 20 plain copies of 1 GiB (reference reading for the HBM traffic counters)")
     args = ap.parse_args()
+    if args.copy_calibration:
+        import paper_2505_21594_amd as ee
+        ee.ee_debug_copy(0, 1 << 30, 20)
+        print(json.dumps({"copy_calibration": {"kernel": "ee_copy_kernel", "bytes_read": 1 << 30, "bytes_written": 1 << 30, "launches": 20}}))
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import paper_2505_21594_amd as ee
 
-    cfg, n_prompt, gamma, exits, p_corrupt = WORKLOADS[args.workload]
+    cfg, tag, n_prompt, gamma, exits, p_corrupt, B, n_emb = WORKLOADS[args.workload]
     M = gamma + 1
     K, W = args.steps, args.warmup
-    path = model_file(cfg, args.workload.split("_")[0], args.seed, pick_workdir())
+    path = model_file(cfg, tag, args.seed, pick_workdir())
 
     t = time.time()
-    model = ee.Model(path, device=0, max_rows=M)
+    model = ee.Model(path, device=0, max_rows=B * M)
     print(f"[bench] model on GPU in {time.time() - t:.1f}s, {model.n_workgroups} workgroups", file=sys.stderr, flush=True)
     rounds = W + K
-    max_ctx = n_prompt + rounds * M + 2 * M + 16
     flags = ee.CHAIN_LAUNCHES if args.chain_launches else 0
-    sess = model.session(max_ctx, max_gamma=max(gamma, 1), flags=flags)
-    prompt = eegen.prompt_tokens(args.seed, n_prompt, cfg.vocab)
+    run = Run(ee, model, cfg, args.seed, n_prompt, gamma, exits, p_corrupt, B, n_emb, flags)
     t = time.time()
-    first = sess.ee_prefill(prompt)
-    print(f"[bench] prefill of {n_prompt} tokens in {time.time() - t:.2f}s", file=sys.stderr, flush=True)
-
-    # Untimed rehearsal: walk the whole trajectory once to build every round's drafts
-    # (greedy continuation, corrupted), then roll the session back to the prompt.
-    drafts_per_round = []
-    for r in range(rounds):
-        g = gpu_greedy(sess, gamma)
-        d = eegen.corrupt_drafts(g, p_corrupt, cfg.vocab, args.seed, r)
-        drafts_per_round.append(d)
-        sess.verify_sync(d, exits)
-    sess.ee_kv_truncate(n_prompt)
-    sess.ee_set_pending(first)
-
-    ex = list(exits)
+    sessions = run.make_sessions(rounds=rounds)
+    print(f"[bench] prefill of {B} x {n_emb + n_prompt} rows in {time.time() - t:.2f}s", file=sys.stderr, flush=True)
+    run.rehearse(sessions, rounds)
+    ex = run.exits
     for r in range(W):
-        sess.verify_sync(drafts_per_round[r], ex)
+        run.verify(sessions, r)
 
     ee.ee_device_synchronize(0)
+    lead = sessions[0]
     dev_ms, exit_ms, accepted, ctx_at = [], [], [], []
     t0 = time.perf_counter()
     for r in range(W, rounds):
-        ctx_at.append(sess.ee_kv_len())
-        sess.ee_verify(drafts_per_round[r], ex)
-        sess.ee_wait_final()
-        accepted.append(sess.final_result().accept_len)
-        dev_ms.append(sess.ee_pass_time_ms(len(ex)))
-        exit_ms.append([sess.ee_pass_time_ms(e) for e in range(len(ex))])
+        ctx_at.append(sum(s.ee_kv_len() for s in sessions) / B)
+        run.verify(sessions, r)
+        accepted.append(sum(s.final_result().accept_len for s in sessions))
+        dev_ms.append(lead.ee_pass_time_ms(len(ex)))
+        exit_ms.append([lead.ee_pass_time_ms(e) for e in range(len(ex))])
     ee.ee_device_synchronize(0)
     wall = time.perf_counter() - t0
 
-    kinds = per_launch_roofline(ee, model, cfg, prompt, first, drafts_per_round, ex, M, flags, min(rounds, 9))
+    kinds = per_launch_roofline(ee, run, min(rounds, 9))
     gemm = [k for k in ("qkv", "o", "gu", "dn", "head", "chain") if k in kinds]
     g_n = sum(kinds[k]["launches_per_pass"] for k in gemm)
     g_ms = sum(kinds[k]["launches_per_pass"] * kinds[k]["avg_launch_us"] for k in gemm) * 1e-3
     g_bytes = sum(kinds[k]["launches_per_pass"] * kinds[k]["algorithmic_bytes_per_launch"] for k in gemm)
     if "chain" in kinds:  # chained launches: every GEMM byte of the pass
-        g_bytes = sum(algorithmic_bytes(cfg, len(ex), P, M) - launch_bytes(cfg, "att", P, M) * cfg.n_layers
-                      - launch_bytes(cfg, "embed", P, M) for P in ctx_at) / len(ctx_at)
+        g_bytes = sum(algorithmic_bytes(cfg, len(ex), P, M, B) - launch_bytes(cfg, "att", P, M, B) * cfg.n_layers
+                      - launch_bytes(cfg, "embed", P, M, B) for P in ctx_at) / len(ctx_at)
 
     mean_dev_ms = sum(dev_ms) / len(dev_ms)
-    bytes_per_pass = [algorithmic_bytes(cfg, len(ex), P, M) for P in ctx_at]
+    bytes_per_pass = [algorithmic_bytes(cfg, len(ex), P, M, B) for P in ctx_at]
     mean_bytes = sum(bytes_per_pass) / len(bytes_per_pass)
     pass_gbps = mean_bytes / (mean_dev_ms * 1e-3) / 1e9
     achieved = g_bytes / (g_ms * 1e-3) / 1e9
-    committed = sum(a + 1 for a in accepted)
+    committed = sum(a + B for a in accepted)
+    kernel_name = "ee_gemm_chain_kernel<%d>" % ((B * M + 15) // 16)
     out = {
         "metric": "verify passes/s (Llama2-7B-shape, gamma=4, ctx 512)" if args.workload == "llama7b_g4_ctx512"
         else f"verify passes/s ({args.workload})",
@@ -229,16 +288,17 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "gamma": gamma, "exit_layers": ex, "prompt": n_prompt,
-                   "batch": 1, "context_first": ctx_at[0], "context_last": ctx_at[-1],
+                   "batch": B, "embedding_prefix_rows": n_emb, "context_first": ctx_at[0], "context_last": ctx_at[-1],
                    "launch_mode": "chain" if args.chain_launches else "stage"},
         "device_ms_per_pass": {"mean": mean_dev_ms, "median": statistics.median(dev_ms),
                                "p10": float(np.percentile(dev_ms, 10)), "p90": float(np.percentile(dev_ms, 90))},
         "verified_tokens_per_s": committed / wall,
-        "mean_accept_len": sum(accepted) / len(accepted),
+        "mean_accept_len": sum(accepted) / len(accepted) / B,
         "exit_lead_ms": [mean_dev_ms - sum(e[i] for e in exit_ms) / len(exit_ms) for i in range(len(ex))],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "ee_gemm_chain_kernel<1>" if M <= 16 else "ee_gemm_chain_kernel",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None if args.chain_launches else measured_traffic(kernel_name, args.workload),
+                     "kernel": kernel_name,
                      "launches_per_pass": g_n, "algorithmic_bytes_per_launch": g_bytes / g_n,
                      "avg_launch_us": g_ms / g_n * 1e3,
                      "how": "HIP events on the session stream right before and after every launch, "
@@ -247,7 +307,8 @@ def main():
                      "whole_pass": {"algorithmic_bytes": mean_bytes, "device_ms": mean_dev_ms,
                                     "achieved": pass_gbps, "frac": pass_gbps / HBM_PEAK_GBS}},
     }
-    sess.free()
+    for sx in sessions:
+        sx.free()
     model.free()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(path, cfg, gamma, exits, args.seed)

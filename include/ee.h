@@ -170,6 +170,11 @@ int ee_pending(ee_session *s, int32_t *out);
    (0..n_exits-1 = exit heads in order, n_exits = final head) as float[gamma+1][vocab]. */
 int ee_debug_logits(ee_session *s, int head_idx, float *out);
 
+/* Measurement aid: `reps` launches of a plain copy kernel (ee_copy_kernel) that moves `bytes`
+   bytes each between two device buffers it allocates and frees: under the profiler's HBM
+   traffic counters this is the reading of a known number of bytes read and written. */
+int ee_debug_copy(int device, size_t bytes, int reps);
+
 /* hipDeviceSynchronize on `device`: every pass enqueued so far has finished. */
 int ee_device_synchronize(int device);
 

@@ -37,7 +37,7 @@ EXPORTS = [
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost", "ee_debug_trace",
-    "ee_launch_times", "ee_debug_trace_workgroups",
+    "ee_launch_times", "ee_debug_trace_workgroups", "ee_debug_copy",
 ]
 
 
@@ -108,6 +108,7 @@ def load_library():
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
     lib.ee_debug_trace.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
+    lib.ee_debug_copy.argtypes = [ci, ctypes.c_size_t, ci]
     lib.ee_debug_trace_workgroups.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
     lib.ee_launch_times.argtypes = [vp, i32p, P(ctypes.c_float), ci, P(ci)]
     for name in EXPORTS:
@@ -289,6 +290,10 @@ class Session:
         self.ee_verify(draft_tokens, exit_layers)
         self.ee_wait_final()
         return self.final_result()
+
+
+def ee_debug_copy(device: int, nbytes: int, reps: int) -> None:
+    _check(load_library().ee_debug_copy(device, nbytes, reps))
 
 
 def ee_verify_batch(sessions: List[Session], drafts: List[Sequence[int]], exit_layers: Sequence[int] = ()) -> None:

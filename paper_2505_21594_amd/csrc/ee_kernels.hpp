@@ -1349,6 +1349,12 @@ __global__ void mfma_layout_probe_kernel(const uint4 *a, const uint4 *b, float *
     for (int r = 0; r < 4; ++r) out[threadIdx.x * 4 + r] = acc[r];
 }
 
+// plain copy of n 16-byte words: the reference for what the HBM traffic counters read per byte
+__global__ void __launch_bounds__(256) ee_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) dst[i] = src[i];
+}
+
 // the same for v_mfma_f32_16x16x16bf16_1k: A[i][k] from lane (i + 16*(k/4)) element k%4,
 // B[k][j] likewise with j, D as above
 __global__ void mfma16_layout_probe_kernel(const uint2 *a, const uint2 *b, float *out)

@@ -387,11 +387,11 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         p->steps = plan_steps(*p, m->nwg);
     }
     x_bytes = std::max(x_bytes, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
-    x_bytes = align_up(std::max(x_bytes, att), 256);
+    x_bytes = align_up(x_bytes, 256);
     md.lds_slots_off = (int)x_bytes;
     md.lds_zbuf_off = (int)(x_bytes + slots);
     md.lds_misc_off = (int)(x_bytes + slots + zbuf);
-    size_t lds = x_bytes + slots + zbuf + misc;
+    size_t lds = std::max(x_bytes + slots + zbuf + misc, att);  // attention uses the block on its own
     // more than half of the CU's LDS keeps it to one workgroup per compute unit
     lds = std::max(lds, std::min((size_t)84 * 1024, lds_cap));
     m->lds_budget = lds;
@@ -1233,6 +1233,30 @@ extern "C" int ee_debug_trace_workgroups(ee_session *s, unsigned long long *out,
     int n = std::min(s->trace_n / EE_TRACE_SLOTS * s->m->nwg * 2, max_values);
     HIP_TRY(hipMemcpy(out, s->sc.trace + EE_TRACE_MAX, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
     *n_values = n;
+    return EE_OK;
+}
+
+// Measurement aid: `reps` launches of a plain copy kernel (ee_copy_kernel) moving `bytes` bytes
+// each between two freshly allocated device buffers.  Profiled with the HBM traffic counters it
+// gives the counter reading of a known number of bytes read and written.
+extern "C" int ee_debug_copy(int device, size_t bytes, int reps)
+{
+    HIP_TRY(hipSetDevice(device));
+    if (bytes < 16 || reps < 1) return fail(EE_EINVAL, "ee_debug_copy: bytes %zu, reps %d", bytes, reps);
+    void *src = nullptr, *dst = nullptr;
+    HIP_TRY(hipMalloc(&src, bytes));
+    if (hipMalloc(&dst, bytes) != hipSuccess) {
+        hipFree(src);
+        return fail(EE_EDEVICE, "ee_debug_copy: out of memory");
+    }
+    hipMemset(src, 0x3C, bytes);
+    hipMemset(dst, 0, bytes);
+    for (int r = 0; r < reps; ++r)
+        hipLaunchKernelGGL(ee_copy_kernel, dim3(4096), dim3(256), 0, 0, static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
+    hipError_t e = hipDeviceSynchronize();
+    hipFree(src);
+    hipFree(dst);
+    if (e != hipSuccess) return fail(EE_EDEVICE, "ee_debug_copy: %s", hipGetErrorString(e));
     return EE_OK;
 }
 
