@@ -101,6 +101,11 @@ typedef struct {
     int32_t device_status;                          /* 0, or != 0 if a device-side wait
                                                        gave up (pass result invalid)    */
     int32_t reserved[15];
+    /* Confidence score of every row (paper Eq. 4): the largest entry of softmax(z) of the head's
+       logits, the value the paper's sender and client queues order exit results by.  Readable
+       together with the tokens of the same head. */
+    float final_conf[EE_MAX_M];
+    float exit_conf[EE_MAX_EXITS][EE_MAX_M];
 } ee_verify_result;
 
 const char *ee_last_error(void);

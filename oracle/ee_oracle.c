@@ -152,6 +152,24 @@ static int argmax_lowest(const real *z, int n)
     return best;
 }
 
+/* Confidence score of one row (paper Eq. 4): the largest entry of softmax(z), the definition
+   written out: p_j = exp(z_j - max z) / sum_i exp(z_i - max z), then the maximum of p. */
+static double max_softmax(const real *z, int n)
+{
+    real mx = z[0];
+    for (int i = 1; i < n; ++i)
+        if (z[i] > mx) mx = z[i];
+    real sum = 0;
+    for (int i = 0; i < n; ++i)
+        sum += (real)exp((double)(z[i] - mx));
+    real best = 0;
+    for (int i = 0; i < n; ++i) {
+        real p = (real)exp((double)(z[i] - mx)) / sum;
+        if (p > best) best = p;
+    }
+    return (double)best;
+}
+
 /* Accept rule (Eq. 2): delta = longest prefix with drafts[j] == a[j]; next = a[delta] */
 static void accept_rule(const int32_t *drafts, int gamma, const int32_t *a, int32_t *delta,
                         int32_t *next)
@@ -531,8 +549,11 @@ int eo_verify(eo_session *s, const int32_t *drafts, int gamma, const int32_t *ex
     out->n_exits = n_exits;
     for (int e = 0; e <= n_exits; ++e) {
         int32_t *a = e < n_exits ? out->exit_tokens[e] : out->final_tokens;
-        for (int i = 0; i < M; ++i)
+        double *conf = e < n_exits ? out->exit_conf[e] : out->final_conf;
+        for (int i = 0; i < M; ++i) {
             a[i] = argmax_lowest(hr.logits[e] + (size_t)i * V, V);
+            conf[i] = max_softmax(hr.logits[e] + (size_t)i * V, V);
+        }
         if (e < n_exits)
             accept_rule(drafts, gamma, a, &out->exit_accept_len[e], NULL);
         else

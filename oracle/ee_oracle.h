@@ -61,6 +61,9 @@ typedef struct {
     int32_t final_tokens[EO_MAX_M];                  /* final-head argmax at rows 0..gamma */
     int32_t exit_accept_len[EO_MAX_EXITS];           /* delta^(e)                         */
     int32_t exit_tokens[EO_MAX_EXITS][EO_MAX_M];     /* exit-head argmax at rows 0..gamma */
+    /* confidence score of every row (paper Eq. 4): max over the vocabulary of softmax(z) */
+    double final_conf[EO_MAX_M];
+    double exit_conf[EO_MAX_EXITS][EO_MAX_M];
 } eo_result;
 
 /* Optional per-stage capture for kernel-level comparisons; any pointer may be

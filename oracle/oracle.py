@@ -40,7 +40,9 @@ class _Result(ctypes.Structure):
                 ("accept_len", ctypes.c_int32), ("next_token", ctypes.c_int32),
                 ("final_tokens", ctypes.c_int32 * EO_MAX_M),
                 ("exit_accept_len", ctypes.c_int32 * EO_MAX_EXITS),
-                ("exit_tokens", (ctypes.c_int32 * EO_MAX_M) * EO_MAX_EXITS)]
+                ("exit_tokens", (ctypes.c_int32 * EO_MAX_M) * EO_MAX_EXITS),
+                ("final_conf", ctypes.c_double * EO_MAX_M),
+                ("exit_conf", (ctypes.c_double * EO_MAX_M) * EO_MAX_EXITS)]
 
 
 class _Trace(ctypes.Structure):
@@ -120,6 +122,8 @@ class VerifyResult:
     final_tokens: np.ndarray            # [gamma+1]
     exit_accept_len: np.ndarray         # [n_exits]
     exit_tokens: np.ndarray             # [n_exits][gamma+1]
+    final_conf: np.ndarray = None       # [gamma+1] max softmax probability per row, final head
+    exit_conf: np.ndarray = None        # [n_exits][gamma+1] the same for every exit head
     logits: Optional[np.ndarray] = None  # [n_exits+1][gamma+1][V] float64 (final head last)
     trace: Optional[dict] = None
 
@@ -222,6 +226,9 @@ class Session:
             exit_accept_len=np.array(res.exit_accept_len[:ex.size], dtype=np.int32),
             exit_tokens=np.array([list(res.exit_tokens[e][:M]) for e in range(ex.size)],
                                  dtype=np.int32).reshape(ex.size, M),
+            final_conf=np.array(res.final_conf[:M], dtype=np.float64),
+            exit_conf=np.array([list(res.exit_conf[e][:M]) for e in range(ex.size)],
+                               dtype=np.float64).reshape(ex.size, M),
             logits=logits, trace=trace)
 
     def kv_truncate(self, new_len: int):

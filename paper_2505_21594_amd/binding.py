@@ -61,7 +61,8 @@ class VerifyResultC(ctypes.Structure):
                 ("final_tokens", ctypes.c_int32 * EE_MAX_M),
                 ("exit_accept_len", ctypes.c_int32 * EE_MAX_EXITS),
                 ("exit_tokens", (ctypes.c_int32 * EE_MAX_M) * EE_MAX_EXITS),
-                ("device_status", ctypes.c_int32), ("reserved", ctypes.c_int32 * 15)]
+                ("device_status", ctypes.c_int32), ("reserved", ctypes.c_int32 * 15),
+                ("final_conf", ctypes.c_float * EE_MAX_M), ("exit_conf", (ctypes.c_float * EE_MAX_M) * EE_MAX_EXITS)]
 
 
 _lib = None
@@ -148,6 +149,8 @@ class VerifyOutput:
     final_tokens: np.ndarray
     exit_accept_len: np.ndarray
     exit_tokens: np.ndarray
+    final_conf: np.ndarray = None   # [gamma+1] float32
+    exit_conf: np.ndarray = None    # [n_exits][gamma+1] float32
 
 
 class Model:
@@ -278,13 +281,19 @@ class Session:
         r, M = self._res.contents, self._gamma + 1
         return np.array(r.exit_tokens[exit_idx][:M], dtype=np.int32), int(r.exit_accept_len[exit_idx])
 
+    def exit_conf(self, exit_idx: int) -> np.ndarray:
+        r, M = self._res.contents, self._gamma + 1
+        return np.array(r.exit_conf[exit_idx][:M], dtype=np.float32)
+
     def final_result(self) -> VerifyOutput:
         r, M, E = self._res.contents, self._gamma + 1, self._n_exits
         return VerifyOutput(
             gamma=self._gamma, accept_len=int(r.accept_len), next_token=int(r.next_token),
             final_tokens=np.array(r.final_tokens[:M], dtype=np.int32),
             exit_accept_len=np.array(r.exit_accept_len[:E], dtype=np.int32),
-            exit_tokens=np.array([list(r.exit_tokens[e][:M]) for e in range(E)], dtype=np.int32).reshape(E, M))
+            exit_tokens=np.array([list(r.exit_tokens[e][:M]) for e in range(E)], dtype=np.int32).reshape(E, M),
+            final_conf=np.array(r.final_conf[:M], dtype=np.float32),
+            exit_conf=np.array([list(r.exit_conf[e][:M]) for e in range(E)], dtype=np.float32).reshape(E, M))
 
     def verify_sync(self, draft_tokens: Sequence[int], exit_layers: Sequence[int] = ()) -> VerifyOutput:
         self.ee_verify(draft_tokens, exit_layers)

@@ -109,6 +109,7 @@ struct Scratch {
     int *att_count;      // [units] items of the unit that have delivered their partials; zero between launches
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
+    float *cand_sum;     // [nwg][rows_max]      sum over the workgroup's columns of exp(logit - candidate value)
     unsigned *bar_flags; // [nwg]                grid barrier: last epoch each workgroup arrived at
     int *err;            // set to 1 when a bounded wait gave up
     unsigned long long *trace;  // debug: wall-clock stamps of workgroup 0 (EE_TRACE sessions), else nullptr

@@ -220,6 +220,7 @@ struct Misc {  // views into the misc region of the LDS block
     float2 *rope;      // [rows_max][hd/2]
     float *bestv;      // [rows_max]
     int *besti;        // [rows_max]
+    float *sume;       // [rows_max]  sum of exp(logit - bestv) over the columns seen so far
 };
 
 __device__ __forceinline__ Misc misc_views(const ModelDev &md, char *lds)
@@ -240,6 +241,8 @@ __device__ __forceinline__ Misc misc_views(const ModelDev &md, char *lds)
     m.bestv = reinterpret_cast<float *>(p);
     p += (size_t)R * 4;
     m.besti = reinterpret_cast<int *>(p);
+    p += (size_t)R * 4;
+    m.sume = reinterpret_cast<float *>(p);
     return m;
 }
 
@@ -553,9 +556,22 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                     bi = oi;
                 }
             }
-            if (lane == 0 && cand_better(bv, bi, mi.bestv[m], mi.besti[m])) {
-                mi.bestv[m] = bv;
-                mi.besti[m] = bi;
+            // sum of exp(z - bv) over the group's columns (masked columns hold -inf and add 0):
+            // the softmax denominator for the confidence score (paper Eq. 4), kept relative to the
+            // running maximum like the argmax candidate
+            float se = 0.f;
+            for (int c = lane; c < gn * 16; c += 64) se += __expf(zbuf[(size_t)m * pl.GRP * 16 + c] - bv);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) se += __shfl_xor(se, off, 64);
+            if (lane == 0 && bv > -INFINITY) {  // (a group of masked columns only contributes nothing)
+                const float ov = mi.bestv[m];
+                if (cand_better(bv, bi, ov, mi.besti[m])) {
+                    mi.sume[m] = mi.sume[m] * __expf(ov - bv) + se;  // exp(-inf) = 0 the first time
+                    mi.bestv[m] = bv;
+                    mi.besti[m] = bi;
+                } else {
+                    mi.sume[m] += se * __expf(bv - ov);
+                }
             }
         }
     }
@@ -577,12 +593,15 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
         if (tid < rows) {
             mi.bestv[tid] = -INFINITY;
             mi.besti[tid] = 0x7FFFFFFF;
+            mi.sume[tid] = 0.f;
         }
     }
     if (n_local == 0) {  // nothing to stream here (uniform over the workgroup)
         have_pre = prefetch_stage(next, a.nwg, buf);
-        if (kind == G_HEAD && tid < rows)
+        if (kind == G_HEAD && tid < rows) {
             a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(-INFINITY), 0x7FFFFFFF);
+            a.sc.cand_sum[(size_t)blockIdx.x * md.rows_max + tid] = 0.f;
+        }
         if ((kind == G_O || kind == G_DN) && tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
         return;
     }
@@ -730,8 +749,10 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     }
     if (kind == G_HEAD) {
         __syncthreads();
-        if (tid < rows)
+        if (tid < rows) {
             a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(mi.bestv[tid]), mi.besti[tid]);
+            a.sc.cand_sum[(size_t)blockIdx.x * md.rows_max + tid] = mi.sume[tid];
+        }
     }
 }
 
@@ -1063,6 +1084,7 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
     const int rows = a.rows, M = a.M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int *tok = reinterpret_cast<int *>(lds);
+    float *conf = reinterpret_cast<float *>(lds) + EE_MAX_ROWS;
     for (int m = wave; m < rows; m += WAVES) {
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
@@ -1083,7 +1105,20 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
                 bi = oi;
             }
         }
-        if (lane == 0) tok[m] = bi;
+        // confidence (paper Eq. 4): max softmax = 1 / sum_j exp(z_j - z_max), from the
+        // workgroups' sums, each rescaled from its own maximum to the global one
+        float se = 0.f;
+        for (int g = lane; g < a.nwg; g += 64) {
+            const float vg = __int_as_float(a.sc.cand[(size_t)g * md.rows_max + m].x);
+            const float sg = a.sc.cand_sum[(size_t)g * md.rows_max + m];
+            if (sg > 0.f) se += sg * __expf(vg - bv);
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) se += __shfl_xor(se, off, 64);
+        if (lane == 0) {
+            tok[m] = bi;
+            conf[m] = 1.0f / se;
+        }
     }
     __syncthreads();
     const int s = threadIdx.x;
@@ -1091,6 +1126,7 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
         const SessDev &sd = a.sess[s];
         ee_verify_result *res = sd.result;
         const int *t = tok + s * M;
+        const float *cf = conf + s * M;
         int dev_err = __hip_atomic_load(a.sc.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.head_kind == HEAD_PREFILL) {
             int last = t[M - 1];
@@ -1107,10 +1143,16 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
             for (int i = 0; i < EE_MAX_M - 1; ++i)
                 if (delta == i && i < gamma && dr[i] == t[i]) delta = i + 1;
             if (a.head_kind == HEAD_EXIT) {
-                for (int i = 0; i < M; ++i) res->exit_tokens[a.head_idx][i] = t[i];
+                for (int i = 0; i < M; ++i) {
+                    res->exit_tokens[a.head_idx][i] = t[i];
+                    res->exit_conf[a.head_idx][i] = cf[i];
+                }
                 res->exit_accept_len[a.head_idx] = delta;
             } else {
-                for (int i = 0; i < M; ++i) res->final_tokens[i] = t[i];
+                for (int i = 0; i < M; ++i) {
+                    res->final_tokens[i] = t[i];
+                    res->final_conf[i] = cf[i];
+                }
                 res->accept_len = delta;
                 res->next_token = t[delta];
                 res->device_status = dev_err;

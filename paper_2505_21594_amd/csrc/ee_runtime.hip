@@ -370,7 +370,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     int max_grp = 1;
     for (GemmPlan *p : plans) max_grp = std::max(max_grp, p->GRP);
     const size_t zbuf = align_up((size_t)max_rows * max_grp * 16 * sizeof(float), 256);
-    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4), 256);
+    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4 + 4), 256);
     const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
     if (slots + zbuf + misc + 4096 > lds_cap) {
         ee_model_free(m);
@@ -643,6 +643,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     if (flags & EE_KEEP_LOGITS)
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
+    S_TRY(dev_alloc(s->allocs, &sc.cand_sum, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.bar_flags, (size_t)m->nwg));
     S_TRY(dev_alloc(s->allocs, &sc.err, 1));
     if (flags & EE_TRACE)  // workgroup 0's stage stamps, then (start, end) of every workgroup in every launch

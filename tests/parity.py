@@ -44,6 +44,14 @@ def check_pass(o: eo.VerifyResult, g_final, g_logits, drafts, what=""):
         while k < len(drafts) and drafts[k] == gt[k]:
             k += 1
         assert gd == k, f"{what}: head {e}: accept_len {gd} inconsistent with its tokens (first mismatch {k})"
+    # Confidence score (paper Eq. 4).  ln(conf) = z_max - logsumexp(z) moves by at most twice the
+    # largest logit error, so the logit tolerance bounds the relative error of the score.
+    for e in range(E + 1):
+        oc = o.exit_conf[e] if e < E else o.final_conf
+        gc = g_final.exit_conf[e] if e < E else g_final.final_conf
+        rel = float(np.abs(np.log(gc.astype(np.float64)) - np.log(oc)).max())
+        assert rel <= 2 * LOGIT_TOL, f"{what}: head {e}: confidence differs by a factor exp({rel:.3g})"
+        assert np.all(gc > 0) and np.all(gc <= 1.0 + 1e-6)
     if firm[: o.accept_len + 1].all():
         assert g_final.next_token == o.next_token, f"{what}: next_token {g_final.next_token} != {o.next_token}"
     assert g_final.next_token == g_final.final_tokens[g_final.accept_len]

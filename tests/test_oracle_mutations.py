@@ -39,9 +39,14 @@ MUTATIONS = {
                                    None),
     "embedding_row_stride": ("h[(size_t)i * d + kx] = bf16_val(m->emb[(size_t)tok[i] * d + kx]);",
                              "h[(size_t)i * d + kx] = bf16_val(m->emb[(size_t)tok[i] + (size_t)kx * m->c.vocab]);"),
+    "confidence_not_normalised": ("real p = (real)exp((double)(z[i] - mx)) / sum;", "real p = (real)exp((double)(z[i] - mx));"),
+    "confidence_of_wrong_head": ("double *conf = e < n_exits ? out->exit_conf[e] : out->final_conf;",
+                                 None),
 }
 MUTATIONS["q_k_weights_swapped"] = ("linear(w->wq, d, d, x, M, q);\n        linear(w->wk, d, d, x, M, k);",
                                     "linear(w->wk, d, d, x, M, q);\n        linear(w->wq, d, d, x, M, k);")
+MUTATIONS["confidence_of_wrong_head"] = ("conf[i] = max_softmax(hr.logits[e] + (size_t)i * V, V);",
+                                         "conf[i] = max_softmax(hr.logits[n_exits] + (size_t)i * V, V);")
 MUTATIONS["down_proj_transposed_shape"] = ("y[(size_t)m * N + n] = dot_w(W + (size_t)n * K, x + (size_t)m * K, K);",
                                            "y[(size_t)m * N + n] = dot_w(W + (size_t)n * K, x + (size_t)m * K, K - 1);")
 

@@ -271,6 +271,35 @@ def test_closed_form_zero_output_projections(model_dir):
     assert list(r.final_tokens) == list((_rms(emb[rows], gf, eps) @ wlm.T).argmax(-1))
 
 
+def test_confidence_score_against_library_softmax(tiny_wide):
+    """Eq. 4: every row's score equals max(softmax(z)) computed by the library routine
+    from the logits the same pass returned, for the exit head and the final head."""
+    import torch
+    m = tiny_wide
+    s = m.session(64)
+    s.prefill(eegen.prompt_tokens(81, 17, m.vocab))
+    r = s.verify(eegen.prompt_tokens(82, 4, m.vocab), EXITS, commit=False, want_logits=True)
+    ref = torch.softmax(torch.from_numpy(r.logits), dim=-1).max(dim=-1).values.numpy()   # [E+1][M]
+    np.testing.assert_allclose(r.exit_conf[0], ref[0], rtol=2e-5, atol=0)
+    np.testing.assert_allclose(r.final_conf, ref[1], rtol=2e-5, atol=0)
+    # and it is the probability of the token the head reports
+    p = torch.softmax(torch.from_numpy(r.logits[1]), dim=-1).numpy()
+    np.testing.assert_allclose(r.final_conf, p[np.arange(p.shape[0]), r.final_tokens], rtol=2e-5, atol=0)
+
+
+def test_confidence_score_closed_forms(model_dir):
+    """All-zero LM head => uniform distribution => score 1/V for every row and head;
+    a duplicated best row of W_lm => two equal largest logits => score <= 1/2."""
+    path = _mk(model_dir, "tiny_zero_lm", gains="uniform", zero=("w_lm",))
+    m = eo.Model(path)
+    s = m.session(32)
+    s.prefill(eegen.prompt_tokens(83, 6, m.vocab))
+    r = s.verify(eegen.prompt_tokens(84, 4, m.vocab), EXITS, commit=False)
+    np.testing.assert_allclose(r.final_conf, 1.0 / m.vocab, rtol=1e-6)
+    np.testing.assert_allclose(r.exit_conf[0], 1.0 / m.vocab, rtol=1e-6)
+    assert list(r.final_tokens) == [0] * 5   # all logits equal: lowest id
+
+
 def test_rope_properties(tiny_wide_path, tiny_wide):
     """Position 0 is the identity; rotation keeps each pair's norm; layer-1
     q_i . k_j of a constant-token sequence depends on i-j only."""
