@@ -123,6 +123,28 @@ __device__ __forceinline__ void trace_stamp_wg(const PassArgs &a, int k)
     if (a.sc.trace && threadIdx.x == 0)
         a.sc.trace[EE_TRACE_WG_BASE + ((size_t)(a.trace_base / EE_TRACE_SLOTS) * a.nwg + blockIdx.x) * 2 + k] = wall_clock64();
 }
+// The launch arguments are several hundred bytes; the compiler fetches their fields where it
+// needs them, and every first touch of another 64-byte line is a miss of the scalar cache that
+// the wave has to wait out: about 0.22 us each, eight or more in a row at the start of every
+// launch.  This reads one word of every line at once, so the misses overlap, and returns the
+// argument block through a pointer the compiler cannot trace back, so that none of its own
+// fetches can be scheduled before these.
+template <int LINE, int LINES>
+__device__ __forceinline__ void warm_line(unsigned long long ka)
+{
+    if constexpr (LINE < LINES) {
+        unsigned t;
+        asm volatile("s_load_dword %0, %1, %2" : "=s"(t) : "s"(ka), "n"(LINE * 64) : "memory");
+        warm_line<LINE + 1, LINES>(ka);
+    }
+}
+__device__ __forceinline__ const PassArgs &warmed_arguments()
+{
+    unsigned long long ka = reinterpret_cast<unsigned long long>((const void *)__builtin_amdgcn_kernarg_segment_ptr());
+    warm_line<0, (sizeof(PassArgs) + 63 - 4) / 64>(ka);  // last word read lies inside the block
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(ka)::"memory");
+    return *(const PassArgs *)(const __attribute__((address_space(4))) PassArgs *)ka;
+}
 // all vector memory operations of this wave have completed
 // (the builtin, not inline assembly: the compiler's own bookkeeping of loads in flight sees it,
 // so code after it is not made to wait again for loads that this wait has already covered)
@@ -194,7 +216,15 @@ __device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsi
 
 // Fields of session s's descriptor.  Session 0's descriptor also travels by value in the launch
 // arguments, so the common one-session pass needs no load from memory to find them.
-#define EE_SESS(a, s, field) ((s) == 0 ? (a).sess0.field : (a).sess[s].field)
+// (written so that the two sources are never merged into one pointer of unknown address space)
+template <typename T>
+__device__ __forceinline__ T sess_pick(bool first, const T &own, const T *other)
+{
+    T v = own;
+    if (!first) v = *as_global(other);
+    return v;
+}
+#define EE_SESS(a, s, field) sess_pick((s) == 0, (a).sess0.field, &(a).sess[s].field)
 
 __device__ __forceinline__ int row_pos(const PassArgs &a, int r)
 {
@@ -858,12 +888,11 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
         int hh = rem / n_chunks, ch = rem - hh * n_chunks;
         int r0 = ch * ATT_ROWS, nr = min(ATT_ROWS, M - r0);
         // session 0's descriptor also travels by value in the launch arguments: no dependent load
-        const SessDev *sdp = a.sess + s;
-        const int *page_table = s == 0 ? a.sess0.page_table : sdp->page_table;
-        const uint16_t *kpool = s == 0 ? a.sess0.kpool : sdp->kpool;
-        const uint16_t *vpool = s == 0 ? a.sess0.vpool : sdp->vpool;
-        const int n_pages = s == 0 ? a.sess0.n_pages : sdp->n_pages;
-        const int P = a.mode == 1 ? a.pf_pos0 : (s == 0 ? a.sess0.kv_len : sdp->kv_len);  // position of the first row
+        const int *page_table = EE_SESS(a, s, page_table);
+        const uint16_t *kpool = EE_SESS(a, s, kpool);
+        const uint16_t *vpool = EE_SESS(a, s, vpool);
+        const int n_pages = EE_SESS(a, s, n_pages);
+        const int P = a.mode == 1 ? a.pf_pos0 : EE_SESS(a, s, kv_len);  // position of the first row
         const int n_pos = P + r0 + nr;  // positions visible to the chunk's last row
         const int n_pg = (n_pos + KV_PAGE - 1) / KV_PAGE;
         const int pg_lo = n_pg * sp / n_splits, pg_hi = n_pg * (sp + 1) / n_splits;
@@ -1242,9 +1271,10 @@ __device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int lay
 // GEMM stages [ph_lo, ph_hi) of the stage list (all of them must be GEMM stages).
 // MT = 16-row tiles of the pass (rows <= 16 * MT).
 template <int MT>
-__global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
+__global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
+    const PassArgs &a = warmed_arguments();
     // The tables indexed by the stage kind are read from the descriptor in device memory; the
     // first stage's entries (the only ones of a one-stage launch) come with the launch
     // arguments, so that nothing has to be loaded before the first weight address is known.
@@ -1284,18 +1314,20 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a)
 }
 
 template <int HD>
-__global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a)
+__global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
+    const PassArgs &a = warmed_arguments();
     trace_stamp_wg(a, 0);
     att_stage<HD>(a, stage_decode(a, a.ph_lo).layer, lds);
     trace_stamp_wg(a, 1);
 }
 
 // embedding, accept: stage ph_lo
-__global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a)
+__global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
+    const PassArgs &a = warmed_arguments();
     const StageDesc st = stage_decode(a, a.ph_lo);
     trace_stamp_wg(a, 0);
     if (st.type == ST_EMBED)
