@@ -408,14 +408,19 @@ __device__ __forceinline__ void stage_x_wave(const GemmPlan &pl, const GemmIn &i
     }
 }
 
-// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order
+// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order.  DEV: the partial
+// sums were written earlier in the same launch (device-scope loads); otherwise ordinary loads,
+// which the XCD's L2 serves to all but the first workgroup: every workgroup reads the same
+// few kilobytes, and past the L2 that is thousands of requests for the same lines.
+template <bool DEV>
 __device__ __forceinline__ void load_rstd(const float *ss, int nwg, int rows_max, int rows, int d, float eps,
                                           float *rstd_lds)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     for (int m = wave; m < rows; m += WAVES) {
         float s = 0.f;
-        for (int g = lane; g < nwg; g += 64) s += load_dev32(ss + (size_t)g * rows_max + m);
+        for (int g = lane; g < nwg; g += 64)
+            s += DEV ? load_dev32(ss + (size_t)g * rows_max + m) : *as_global(ss + (size_t)g * rows_max + m);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
         if (lane == 0) rstd_lds[m] = 1.0f / sqrtf(s / (float)d + eps);
@@ -659,7 +664,12 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                     stage_x_wave<true>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
                 else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
                     stage_x_wave<false>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
-                if (in.ss && gi == 0 && kb == 0) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
+                if (in.ss && gi == 0 && kb == 0) {
+                    if (a.ph_hi - a.ph_lo > 1)
+                        load_rstd<true>(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
+                    else
+                        load_rstd<false>(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
+                }
                 if (kind == G_QKV && gi == 0 && kb == 0) {
                     // per-row position, KV record and RoPE factors for the epilogue (read after the
                     // workgroup barrier that precedes it)
