@@ -659,7 +659,10 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             const Seg s = seg_setup(pl, nt0, n_local, wave, gi, kb);
             const bool restage = pl.nKB > 1 || gi == 0;
             if (restage) {
-                if (gi > 0 || kb > 0) __syncthreads();  // x_hat of the previous block is dead
+                // A wave overwrites only its own slice of the previous block when every block has
+                // the same length (the slices then coincide); otherwise slices shift between
+                // blocks and the other waves must be done with theirs first.
+                if ((gi > 0 || kb > 0) && pl.KT % pl.nKB != 0) __syncthreads();
                 if (a.ph_hi - a.ph_lo > 1)
                     stage_x_wave<true>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
                 else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
