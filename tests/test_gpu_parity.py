@@ -316,3 +316,26 @@ def test_exit_results_visible_before_final(mid_pair):
     t0, t1, tf = gs.ee_pass_time_ms(0), gs.ee_pass_time_ms(1), gs.ee_pass_time_ms(2)
     assert 0 < t0 < t1 < tf
     gs.free()
+
+
+@pytest.mark.parametrize("splits,prompt_len", [(1, 300), (2, 500), (3, 200)])
+def test_attention_several_pages_per_wave(mid_pair, splits, prompt_len, monkeypatch):
+    """Few attention splits on a longer context: a wave then walks several KV pages per item
+    (the split count is read per pass; normally it is chosen so that a wave gets about one)."""
+    g, o = mid_pair
+    monkeypatch.setenv("EE_ATT_SPLITS", str(splits))
+    prompt = eegen.prompt_tokens(900 + splits, prompt_len, o.vocab)
+    drafts = eegen.prompt_tokens(901 + splits, 7, o.vocab)
+    exempt, err, _ = _one_round(g, o, prompt, drafts, [1, 2], what=f"splits={splits} P={prompt_len}")
+    assert err <= 3e-2
+
+
+def test_gamma_extremes_and_page_boundary(tiny_pair):
+    """gamma = 1 and gamma = 15 (the most rows of one attention item), prompts that end right
+    before, on and after a page boundary."""
+    g, o = tiny_pair
+    for P in (15, 16, 17, 31, 32):
+        for gamma in (1, 15):
+            prompt = eegen.prompt_tokens(700 + P, P, o.vocab)
+            drafts = eegen.prompt_tokens(701 + P + gamma, gamma, o.vocab)
+            _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"P={P} gamma={gamma}")
