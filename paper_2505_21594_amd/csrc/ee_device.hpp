@@ -91,7 +91,7 @@ struct SessDev {
     int n_pages;
     int kv_len;                          // positions cached before this pass (host mirror of state[0])
     int pending;                         // token of row 0 (host mirror of state[1])
-    int pad_;
+    int contig_base;                     // >= 0: logical page i is physical page contig_base + i (no table lookup needed)
 };
 
 struct Scratch {

@@ -680,7 +680,8 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                         const int m = tid;
                         const int pos = row_pos(a, m);
                         const int ses = a.mode == 1 ? 0 : m / a.M;
-                        const int page = as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
+                        const int cbase = EE_SESS(a, ses, contig_base);
+                        const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
                         mi.pos[m] = pos;
                         mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
                     }
@@ -910,7 +911,12 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
         const int n_pg = (n_pos + KV_PAGE - 1) / KV_PAGE;
         const int pg_lo = n_pg * sp / n_splits, pg_hi = n_pg * (sp + 1) / n_splits;
         const int T = max(0, (pg_hi - pg_lo - wave + WAVES - 1) / WAVES);  // tiles of this wave, <= ATT_TILES
-        const int my_pg = lane < T ? as_global(page_table)[pg_lo + wave + lane * WAVES] : 0;
+        const int cbase = EE_SESS(a, s, contig_base);
+        int my_pg = 0;  // physical page of this wave's tile number `lane`
+        if (cbase >= 0)
+            my_pg = cbase + pg_lo + wave + lane * WAVES;  // consecutive pages: no lookup, K can be requested together with q
+        else if (lane < T)
+            my_pg = as_global(page_table)[pg_lo + wave + lane * WAVES];
 
         // the rows' q as MFMA B operands, two bf16 terms (rows past the chunk repeat its last row)
         const int mrow = min(lm, nr - 1);

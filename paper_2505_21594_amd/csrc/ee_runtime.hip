@@ -590,7 +590,9 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     memset(s->host_page_table, 0, (size_t)s->n_pages * sizeof(int));
     // LIFO free list: the first logical page gets the highest physical page, so
     // the mapping is never the identity
-    for (int p = 0; p < s->n_pages; ++p) s->free_pages.push_back(p);
+    for (int p = s->n_pages - 1; p >= 0; --p) s->free_pages.push_back(p);  // handed out in ascending order
+    if (getenv("EE_SCATTER_PAGES"))  // test aid: hand pages out in descending order, so that the page table is really needed
+        std::reverse(s->free_pages.begin(), s->free_pages.end());
     s->pages_used = 0;
 
     // RoPE table in double on the host: angle = pos * base^(-2j/hd)
@@ -691,7 +693,14 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
     sd.n_pages = s->n_pages;
     sd.kv_len = s->kv_len;
     sd.pending = s->pending;
-    sd.pad_ = 0;
+    // the common case: the session's pages are consecutive (a fresh pool hands them out in
+    // ascending order and a rollback returns them in the order that restores it)
+    sd.contig_base = s->pages_used > 0 ? s->host_page_table[0] : 0;
+    for (int i = 1; i < s->pages_used; ++i)
+        if (s->host_page_table[i] != s->host_page_table[0] + i) {
+            sd.contig_base = -1;
+            break;
+        }
 }
 
 // host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [HEAD ACCEPT]

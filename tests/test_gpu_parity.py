@@ -339,3 +339,13 @@ def test_gamma_extremes_and_page_boundary(tiny_pair):
             prompt = eegen.prompt_tokens(700 + P, P, o.vocab)
             drafts = eegen.prompt_tokens(701 + P + gamma, gamma, o.vocab)
             _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"P={P} gamma={gamma}")
+
+
+def test_scattered_pages_use_the_page_table(tiny_pair, mid_pair, monkeypatch):
+    """A fresh session's pages are consecutive and the kernels then skip the table lookup;
+    with the pages handed out in descending order the lookup path runs."""
+    monkeypatch.setenv("EE_SCATTER_PAGES", "1")
+    for (g, o), exits in ((tiny_pair, TINY_EXITS), (mid_pair, [1, 2])):
+        prompt = eegen.prompt_tokens(1200, 75, o.vocab)
+        drafts = eegen.prompt_tokens(1201, 6, o.vocab)
+        _one_round(g, o, prompt, drafts, exits, what="scattered pages")
