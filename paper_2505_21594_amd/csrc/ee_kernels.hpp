@@ -918,36 +918,41 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
         else if (lane < T)
             my_pg = as_global(page_table)[pg_lo + wave + lane * WAVES];
 
-        // the rows' q as MFMA B operands, two bf16 terms (rows past the chunk repeat its last row)
+        // Requests first, uses after: the rows' q and the K of the wave's first tile (most waves
+        // have one tile) travel together; with consecutive pages nothing had to be loaded to
+        // know where K is.
         const int mrow = min(lm, nr - 1);
-        bf16x8_t qh[KT], ql[KT];
+        f32x4_t qraw[KT][2];
         {
             const float *qp = a.sc.q + (size_t)(s * M + r0 + mrow) * d + hh * HD + quad * 8;
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
-                f32x4_t x0 = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32));
-                f32x4_t x1 = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32 + 4));
-                uint32_t h[8], l[8];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    split_bf16(x0[e], h[e], l[e]);
-                    split_bf16(x1[e], h[4 + e], l[4 + e]);
-                }
-                qh[kt] = pack_bf16x8(h);
-                ql[kt] = pack_bf16x8(l);
+                qraw[kt][0] = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32));
+                qraw[kt][1] = *as_global(reinterpret_cast<const f32x4_t *>(qp + kt * 32 + 4));
             }
         }
-
-        // V of the wave's first tile is fetched together with its K (most waves have one tile)
-        uint2 v0h[NT], v0l[NT];
+        uint4 k0h[KT], k0l[KT];
         if (T > 0) {
             const int page = __builtin_amdgcn_readlane(my_pg, 0);
-            const uint16_t *vb = vpool + (((size_t)layer * n_pages + page) * H + hh) * rec_page + (size_t)lm * KV_PAGE + quad * 4;
+            const uint16_t *kb = kpool + (((size_t)layer * n_pages + page) * H + hh) * rec_page + (size_t)lm * (2 * HD) + quad * 8;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                v0h[nt] = load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
-                v0l[nt] = load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
+            for (int kt = 0; kt < KT; ++kt) {
+                k0h[kt] = load_global16(kb + kt * 32);
+                k0l[kt] = load_global16(kb + HD + kt * 32);
             }
+        }
+        // q as MFMA B operands, two bf16 terms (rows past the chunk repeat its last row)
+        bf16x8_t qh[KT], ql[KT];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+            uint32_t h[8], l[8];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                split_bf16(qraw[kt][0][e], h[e], l[e]);
+                split_bf16(qraw[kt][1][e], h[4 + e], l[4 + e]);
+            }
+            qh[kt] = pack_bf16x8(h);
+            ql[kt] = pack_bf16x8(l);
         }
         // pass 1: score tiles
         f32x4_t S[ATT_TILES];
@@ -961,8 +966,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 uint4 kh[KT], kl[KT];
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt) {
-                    kh[kt] = load_global16(kb + kt * 32);
-                    kl[kt] = load_global16(kb + HD + kt * 32);
+                    kh[kt] = t == 0 ? k0h[kt] : load_global16(kb + kt * 32);
+                    kl[kt] = t == 0 ? k0l[kt] : load_global16(kb + HD + kt * 32);
                 }
                 f32x4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -999,8 +1004,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 uint2 vh[NT], vl[NT];
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
-                    vh[nt] = t == 0 ? v0h[nt] : load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
-                    vl[nt] = t == 0 ? v0l[nt] : load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
+                    vh[nt] = load_global8(vb + (size_t)(nt * 16) * KV_PAGE);
+                    vl[nt] = load_global8(vb + (size_t)(HD + nt * 16) * KV_PAGE);
                 }
                 uint32_t ph[4], pl[4];
 #pragma unroll
