@@ -23,8 +23,8 @@ constexpr int ATT_MAX_SPLITS = 16;
 // W[nt*16 + (l & 15)][kt*32 + (l >> 4)*8 .. +7]  (1 KB per tile).
 //
 // The N axis is cut into units of `tpu` n-tiles (1, or 2 for a gate/up pair);
-// workgroup g owns the units [U*g/nwg, U*(g+1)/nwg) for the whole of K, so every
-// output element is complete inside one workgroup.  A workgroup walks its tiles
+// workgroup g owns a contiguous range of units (unit_range below) for the whole of K, so
+// every output element is complete inside one workgroup.  A workgroup walks its tiles
 //   for group (GRP n-tiles) : for K-block kb : for n-tile in group : for k-tile in block
 // where K-block kb covers the k-tiles [KT*kb/nKB, KT*(kb+1)/nKB); inside one
 // (K-block, n-tile) run of klen tiles, wave w takes [klen*w/WAVES, klen*(w+1)/WAVES).

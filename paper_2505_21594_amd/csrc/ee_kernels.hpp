@@ -1,27 +1,27 @@
 // gfx950 kernels of the verification pass.
 //
-// One persistent kernel runs a whole segment of the pass (embedding, a range of
-// layers, optionally an LM head with its accept step) as a list of stages with
-// a grid-wide barrier between consecutive stages.  Per layer (Eq. 3 of the
-// paper, f = Llama-2 block) there are five stages:
+// A segment of the pass (embedding, a range of layers, optionally an LM head with its
+// accept step) is a list of stages.  Per layer (Eq. 3 of the paper, f = Llama-2 block)
+// there are five:
 //   QKV   x_hat . [Wq;Wk;Wv]^T, * rstd, RoPE, q -> scratch, k/v -> paged bf16 cache
 //   ATT   causal attention of the new rows over the cache         -> attn
 //   O     h += attn . Wo^T
 //   GU    u = silu(rstd * x_hat.Wg^T) * (rstd * x_hat.Wu^T)
 //   DN    h += u . Wd^T
-// (plus a merge stage after ATT when the position range is split over
-// workgroups).  Head (z^(l) = LMHead(h^(l)); accept rule of Eq. 2 / Eq. 5):
-//   HEAD    x_hat . W_lm^T, * rstd, argmax candidate per workgroup
-//   ACCEPT  global argmax (lowest id wins ties), accept length, publication to
-//           pinned host memory, KV commit.
+// Head (z^(l) = LMHead(h^(l)); accept rule of Eq. 2 / Eq. 5; confidence of Eq. 4):
+//   HEAD    x_hat . W_lm^T, * rstd, argmax candidate and softmax denominator per workgroup
+//   ACCEPT  global argmax (lowest id wins ties), confidence, accept length, publication
+//           to pinned host memory, KV commit.
+// By default every stage is one launch (ee_gemm_chain_kernel for the five GEMM kinds,
+// ee_att_kernel, ee_misc_kernel for embedding and accept); optionally consecutive GEMM
+// stages share one launch of ee_gemm_chain_kernel with a grid-wide barrier between them,
+// each wave fetching the first weight tiles of its next stage before it enters the barrier.
 //
 // Every GEMM stage streams the weights once (HBM-bound).  A workgroup owns whole
 // n-tiles for the full K, so its outputs are complete after a cross-wave sum in
 // LDS and the element-wise epilogue runs in the same stage.  RMSNorm is split:
-// the GEMM input is g * h, the row factor rstd = 1/sqrt(mean(h^2)+eps) (computed
-// by every workgroup while it stages h) multiplies the fp32 result.
-// Each wave fetches the first weight tiles of its next GEMM stage before it
-// enters the barrier, so HBM stays busy while the grid synchronises.
+// the GEMM input is g * h (written by the stage that produces h), the row factor
+// rstd = 1/sqrt(mean(h^2)+eps), from per-workgroup partial sums, multiplies the fp32 result.
 #pragma once
 
 #include "ee_device.hpp"
@@ -91,13 +91,6 @@ __device__ __forceinline__ void store_dev32(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ uint4 load_dev128(const void *p)
-{
-    const EE_GLOBAL unsigned long long *q = as_global(reinterpret_cast<const unsigned long long *>(p));
-    unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_uint4((unsigned)a, (unsigned)(a >> 32), (unsigned)b, (unsigned)(b >> 32));
-}
 __device__ __forceinline__ float load_dev32(const float *p)
 {
     return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -162,18 +155,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f)
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
-}
-
-__device__ __forceinline__ void unpack8(const uint4 &v, float *f)
-{
-    f[0] = __uint_as_float(v.x << 16);
-    f[1] = __uint_as_float(v.x & 0xFFFF0000u);
-    f[2] = __uint_as_float(v.y << 16);
-    f[3] = __uint_as_float(v.y & 0xFFFF0000u);
-    f[4] = __uint_as_float(v.z << 16);
-    f[5] = __uint_as_float(v.z & 0xFFFF0000u);
-    f[6] = __uint_as_float(v.w << 16);
-    f[7] = __uint_as_float(v.w & 0xFFFF0000u);
 }
 
 // ------------------------------------------------------------------ grid barrier
@@ -843,15 +824,6 @@ __device__ __forceinline__ uint2 load_global8(const void *p)
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
     u32x2_t v = *as_global(reinterpret_cast<const u32x2_t *>(p));
     return make_uint2(v[0], v[1]);
-}
-
-// sum of the two bf16 terms of four consecutive cached values
-__device__ __forceinline__ void unpack4_sum(const uint2 &hi, const uint2 &lo, float *f)
-{
-    f[0] = __uint_as_float(hi.x << 16) + __uint_as_float(lo.x << 16);
-    f[1] = __uint_as_float(hi.x & 0xFFFF0000u) + __uint_as_float(lo.x & 0xFFFF0000u);
-    f[2] = __uint_as_float(hi.y << 16) + __uint_as_float(lo.y << 16);
-    f[3] = __uint_as_float(hi.y & 0xFFFF0000u) + __uint_as_float(lo.y & 0xFFFF0000u);
 }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
