@@ -358,7 +358,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
             lds_cap = std::max(lds_cap, (size_t)optin);
     }
-    const size_t slot_budget = std::max<size_t>(48 * 1024, (size_t)2 * WAVES * max_rows * 16 * sizeof(float));
+    const size_t slot_budget = std::max<size_t>(64 * 1024, (size_t)2 * WAVES * max_rows * 16 * sizeof(float));
     md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
     md.plan[G_O] = make_plan(c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
     md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg, max_rows, slot_budget);
