@@ -107,6 +107,7 @@ struct Scratch {
     float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
     float *att_part;     // [items][ATT_ROWS][hd+2] attention partials (only when the position range is split)
     int *att_count;      // [units] items of the unit that have delivered their partials; zero between launches
+    int *head_count;     // workgroups of a head launch that have delivered their candidates; zero between launches
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
     float *cand_sum;     // [nwg][rows_max]      sum over the workgroup's columns of exp(logit - candidate value)
@@ -134,6 +135,7 @@ struct PassArgs {
     int head_kind, head_idx;
     const float *head_gain;
     int commit, keep_logits;
+    int fuse_accept;                     // the head launch also runs the accept step (in the workgroup that finishes last)
     int att_splits;
     int H, d, Kpad_d;                    // copies of the model descriptor's fields for the attention kernel
     float att_scale;

@@ -615,8 +615,8 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     if (n_local == 0) {  // nothing to stream here (uniform over the workgroup)
         have_pre = prefetch_stage(next, a.nwg, buf);
         if (kind == G_HEAD && tid < rows) {
-            a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(-INFINITY), 0x7FFFFFFF);
-            a.sc.cand_sum[(size_t)blockIdx.x * md.rows_max + tid] = 0.f;
+            store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(-INFINITY), 0x7FFFFFFFu));
+            store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
         }
         if ((kind == G_O || kind == G_DN) && tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
         return;
@@ -774,9 +774,9 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     }
     if (kind == G_HEAD) {
         __syncthreads();
-        if (tid < rows) {
-            a.sc.cand[(size_t)blockIdx.x * md.rows_max + tid] = make_int2(__float_as_int(mi.bestv[tid]), mi.besti[tid]);
-            a.sc.cand_sum[(size_t)blockIdx.x * md.rows_max + tid] = mi.sume[tid];
+        if (tid < rows) {  // device-scope stores: the accept step may run in another workgroup of this launch
+            store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(mi.bestv[tid]), (unsigned)mi.besti[tid]));
+            store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, mi.sume[tid]);
         }
     }
 }
@@ -1101,10 +1101,16 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
 
 // ------------------------------------------------------------------ accept
 
-// Workgroup 0: global argmax per row, accept rule per session, publication.
+__device__ __forceinline__ int2 load_cand(const int2 *p)
+{
+    const unsigned long long v = __hip_atomic_load(as_global(reinterpret_cast<const unsigned long long *>(p)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_int2((int)(unsigned)v, (int)(unsigned)(v >> 32));
+}
+
+// One workgroup: global argmax per row, confidence, accept rule per session, publication.
+// Reads the candidates with device scope: they may have been written earlier in this launch.
 __device__ void accept_stage(const PassArgs &a, char *lds)
 {
-    if (blockIdx.x != 0) return;
     const ModelDev &md = a.mdv;
     const int rows = a.rows, M = a.M;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -1114,7 +1120,7 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
         for (int g = lane; g < a.nwg; g += 64) {
-            int2 c = a.sc.cand[(size_t)g * md.rows_max + m];
+            int2 c = load_cand(a.sc.cand + (size_t)g * md.rows_max + m);
             float v = __int_as_float(c.x);
             if (cand_better(v, c.y, bv, bi)) {
                 bv = v;
@@ -1134,8 +1140,8 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
         // workgroups' sums, each rescaled from its own maximum to the global one
         float se = 0.f;
         for (int g = lane; g < a.nwg; g += 64) {
-            const float vg = __int_as_float(a.sc.cand[(size_t)g * md.rows_max + m].x);
-            const float sg = a.sc.cand_sum[(size_t)g * md.rows_max + m];
+            const float vg = __int_as_float(load_cand(a.sc.cand + (size_t)g * md.rows_max + m).x);
+            const float sg = load_dev32(a.sc.cand_sum + (size_t)g * md.rows_max + m);
             if (sg > 0.f) se += sg * __expf(vg - bv);
         }
 #pragma unroll
@@ -1306,6 +1312,20 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a_by
                              in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
         trace_stamp(a, ph - a.ph_lo, 6);
     }
+    if (a.fuse_accept) {
+        // The launch ended with a head stage: the workgroup whose candidates arrive last also
+        // runs the accept step (one launch less per head); the counter is left at zero.
+        int *lastf = reinterpret_cast<int *>(lds + 8192);
+        wait_vmem();      // this workgroup's candidates are visible device-wide ...
+        __syncthreads();  // ... for every wave, before it is counted
+        if (threadIdx.x == 0) {
+            const int before = __hip_atomic_fetch_add(a.sc.head_count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *lastf = before == a.nwg - 1 ? 1 : 0;
+            if (*lastf) __hip_atomic_store(a.sc.head_count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (*lastf) accept_stage(a, lds);
+    }
     trace_stamp_wg(a, 1);
 }
 
@@ -1328,7 +1348,7 @@ __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a_by_value
     trace_stamp_wg(a, 0);
     if (st.type == ST_EMBED)
         embed_stage(a, lds);
-    else if (st.type == ST_ACCEPT)
+    else if (st.type == ST_ACCEPT && blockIdx.x == 0)
         accept_stage(a, lds);
     trace_stamp_wg(a, 1);
 }

@@ -641,6 +641,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
         const size_t max_items = max_units * forced + (size_t)m->nwg;
         S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
         S_TRY(dev_alloc(s->allocs, &sc.att_count, max_units));
+        S_TRY(dev_alloc(s->allocs, &sc.head_count, 1));
     }
     if (flags & EE_KEEP_LOGITS)
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
@@ -754,6 +755,8 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         int end = ph + 1;
         if (type == ST_GEMM && !single)
             while (end < n_phases && stage_type(a, end) == ST_GEMM) ++end;
+        // a head stage at the end of a GEMM launch takes the accept step along
+        a.fuse_accept = (type == ST_GEMM && end < n_phases && stage_type(a, end) == ST_ACCEPT) ? 1 : 0;
         a.ph_lo = ph;
         a.ph_hi = end;
         a.epoch_base = lead->epoch;
@@ -782,7 +785,7 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         HIP_TRY(hipGetLastError());
         if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->stream));
         lead->epoch += (unsigned)(end - ph - 1);
-        ph = end;
+        ph = end + a.fuse_accept;
     }
     return EE_OK;
 }
