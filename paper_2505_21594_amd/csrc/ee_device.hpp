@@ -41,6 +41,9 @@ struct GemmPlan {
     int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
     int xs_stride;   // bf16 elements per staged row of x_hat
     int steps;       // tile slots per wave (longest wave sequence)
+    int shared_acc;  // 1: the waves add their partial tiles into one accumulator per n-tile in LDS (atomic
+                     // adds) instead of keeping one partial per wave: with many rows only that leaves room
+                     // for all of a workgroup's n-tiles, so that the input is staged once per K-block
 };
 
 // Units [u0, u1) of workgroup g.  Workgroups are dealt to the chip's 8 XCDs round-robin (XCD =

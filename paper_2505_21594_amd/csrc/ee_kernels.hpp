@@ -427,6 +427,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     const float *slots = reinterpret_cast<const float *>(lds + md.lds_slots_off);
     const int tid = opaque(threadIdx.x);
     const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
+    const int n_part = pl.shared_acc ? 1 : WAVES;        // partial tiles to sum per output tile
     if (kind == G_GU) {
         const int items = (gn >> 1) * rows * 4;
         for (int idx = tid; idx < items; idx += WG_THREADS) {
@@ -436,7 +437,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const float *su = sg + (size_t)rows * 16;
             float4 G = make_float4(0.f, 0.f, 0.f, 0.f), U = G;
 #pragma unroll 2
-            for (int w = 0; w < WAVES; ++w) {
+            for (int w = 0; w < n_part; ++w) {
                 float4 x = *reinterpret_cast<const float4 *>(sg + w * wstride);
                 float4 y = *reinterpret_cast<const float4 *>(su + w * wstride);
                 G.x += x.x; G.y += x.y; G.z += x.z; G.w += x.w;
@@ -460,7 +461,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
-        for (int w = 0; w < WAVES; ++w) {
+        for (int w = 0; w < n_part; ++w) {
             float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
@@ -622,6 +623,11 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
         return;
     }
     if ((kind == G_O || kind == G_DN) && tid < rows) mi.rowss[tid] = 0.f;
+    if (pl.shared_acc) {  // the accumulators start at zero (one workgroup barrier before the first add)
+        float *acc0 = reinterpret_cast<float *>(lds + md.lds_slots_off);
+        for (int i = tid; i < n_local * rows * 16; i += WG_THREADS) acc0[i] = 0.f;
+        __syncthreads();
+    }
     trace_stamp(a, tsi, 0);
     // start the weight stream before anything else (unless the previous stage already did)
     if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
@@ -682,7 +688,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             f32x4_t acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-            if (s.slen == 0 && kb == 0) {  // no tiles in this block: contribute zeros
+            if (s.slen == 0 && kb == 0 && !pl.shared_acc) {  // no tiles in this block: contribute zeros
                 for (int ntg = 0; ntg < gn; ++ntg)
 #pragma unroll
                     for (int mt = 0; mt < MT; ++mt) {
@@ -716,14 +722,21 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                     for (int mt = 0; mt < MT; ++mt) {
                         int m = mt * 16 + (lane & 15);
                         if (m < rows) {
-                            float4 *dst = reinterpret_cast<float4 *>(
-                                slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
-                            float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
-                            if (kb > 0) {
-                                float4 o = *dst;
-                                v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                            if (pl.shared_acc) {
+                                EE_LDS float *dst = (EE_LDS float *)(slots + ((size_t)ntg * rows + m) * 16 + (lane >> 4) * 4);
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    __hip_atomic_fetch_add(dst + r, acc[mt][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            } else {
+                                float4 *dst = reinterpret_cast<float4 *>(
+                                    slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
+                                float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
+                                if (kb > 0) {
+                                    float4 o = *dst;
+                                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+                                }
+                                *dst = v;
                             }
-                            *dst = v;
                         }
                         acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
                     }

@@ -131,7 +131,12 @@ static GemmPlan make_plan(int N, int K, int tpu, int nwg, int rows_max, size_t s
     const size_t per_tile = (size_t)WAVES * rows_max * 16 * sizeof(float);
     int grp = (int)(slot_budget / per_tile) / tpu * tpu;
     grp = std::max(grp, tpu);
-    p.GRP = std::min(grp, std::max(plan_max_local(p.U, tpu, nwg), tpu));
+    const int max_local = std::max(plan_max_local(p.U, tpu, nwg), tpu);
+    p.GRP = std::min(grp, max_local);
+    if (p.GRP < max_local) {  // per-wave partials of all n-tiles do not fit: one shared accumulator each
+        p.shared_acc = 1;
+        p.GRP = max_local;
+    }
     p.nKB = 1;
     return p;
 }
@@ -156,7 +161,10 @@ static int plan_steps(const GemmPlan &p, int nwg)
     return mx;
 }
 
-static size_t plan_slot_bytes(const GemmPlan &p, int rows_max) { return (size_t)WAVES * p.GRP * rows_max * 16 * sizeof(float); }
+static size_t plan_slot_bytes(const GemmPlan &p, int rows_max)
+{
+    return (size_t)(p.shared_acc ? 1 : WAVES) * p.GRP * rows_max * 16 * sizeof(float);
+}
 
 // K-blocks so that one block of x_hat (hi and lo bf16 terms, all rows) fits `budget` bytes
 static bool plan_set_blocks(GemmPlan &p, int rows_max, size_t budget)
