@@ -39,7 +39,6 @@ struct GemmPlan {
     int U;           // units = NT / tpu
     int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
     int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
-    int xs_stride;   // bf16 elements per staged row of x_hat
     int steps;       // tile slots per wave (longest wave sequence)
     int shared_acc;  // 1: the waves add their partial tiles into one accumulator per n-tile in LDS (atomic
                      // adds) instead of keeping one partial per wave: with many rows only that leaves room
@@ -101,11 +100,11 @@ struct Scratch {
     float *h;            // [rows_max][d]        residual stream
     float *q;            // [rows_max][d]        queries after RoPE (pair-interleaved inside each head)
     // GEMM inputs as two bf16 terms each (x = hi + lo up to ~16 mantissa bits), written by the
-    // stage that produces them: hi at [0], lo at [1]
-    uint16_t *xn[2];     // [rows_max][Kpad_d]   gain * h for the next QKV or gate/up GEMM
-    uint16_t *xh[2];     // [rows_max][Kpad_d]   head_gain * h for the LM head
-    uint16_t *attn[2];   // [rows_max][Kpad_d]   attention output
-    uint16_t *u[2];      // [rows_max][Kpad_F]   silu(gate)*up
+    // stage that produces them, k-tile-major: [k-tile][term][row of the pass][32]
+    uint16_t *xn;        // [Kpad_d/32][2][rows][32]  gain * h for the next QKV or gate/up GEMM
+    uint16_t *xh;        // [Kpad_d/32][2][rows][32]  head_gain * h for the LM head
+    uint16_t *attn;      // [Kpad_d/32][2][rows][32]  attention output
+    uint16_t *u;         // [Kpad_F/32][2][rows][32]  silu(gate)*up
     float *ss_a;         // [nwg][rows_max]      partial sums of h^2 after the FFN block / embedding
     float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
     float *att_part;     // [items][ATT_ROWS][hd+2] attention partials (only when the position range is split)

@@ -341,10 +341,18 @@ __device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint
 
 
 struct GemmIn {
-    const uint16_t *hi, *lo;  // [rows][ldx] bf16 terms of the input (already scaled by the norm gain)
-    int ldx;
-    const float *ss;          // [nwg][rows_max] partial sums of squares for rstd, or nullptr
+    const uint16_t *x;  // the input (already scaled by the norm gain) as two bf16 terms, k-tile-major (x_index)
+    const float *ss;    // [nwg][rows_max] partial sums of squares for rstd, or nullptr
 };
+
+// GEMM inputs are stored the way the stages consume them: [k-tile][term][row][32] bf16 with
+// `rows` = the rows of this pass, term 0 = hi, 1 = lo.  The k-slice one wave multiplies with
+// (all rows, both terms) is then one contiguous range, which a few 1 KB loads copy into LDS,
+// and the 16 rows x 4 quads of one MFMA operand read one contiguous kilobyte of LDS.
+__device__ __forceinline__ size_t x_index(int rows, int m, int k, int term)
+{
+    return ((size_t)((k >> 5) * 2 + term) * rows + m) * 32 + (k & 31);
+}
 
 // split x into two bf16 terms: hi = bf16(x), lo = bf16(x - hi).  The MFMA takes bf16 operands;
 // feeding both terms keeps about 16 mantissa bits of the activations (weights are exact
@@ -356,37 +364,35 @@ __device__ __forceinline__ void split_bf16(float x, uint32_t &hi, uint32_t &lo)
     lo = f32_to_bf16(x - __uint_as_float(hi << 16));
 }
 
-__device__ __forceinline__ void store_split4(uint16_t *hi_p, uint16_t *lo_p, size_t idx, const float *v)
+// four consecutive columns k .. k+3 (k a multiple of 4) of row m
+__device__ __forceinline__ void store_split4(uint16_t *x, int rows, int m, int k, const float *v)
 {
     uint32_t h[4], l[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) split_bf16(v[e], h[e], l[e]);
-    store_dev64(hi_p + idx, make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16)));
-    store_dev64(lo_p + idx, make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16)));
+    store_dev64(x + x_index(rows, m, k, 0), make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16)));
+    store_dev64(x + x_index(rows, m, k, 1), make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16)));
 }
 
 // Wave-private staging of the GEMM input: the wave copies the k-slice it multiplies with,
-// [kst + s0, kst + s0 + slen) k-tiles of every row and of both bf16 terms, from memory
-// straight into LDS (layout xs_hi | xs_lo, each [rows][xs_stride]).  No registers hold the
-// data and no other wave reads this slice, so no workgroup barrier is needed: the wave waits
-// for its own loads (wait_vmem) and goes on.  One load instruction moves up to 64 x 16 bytes
-// of one row to consecutive LDS addresses.  DEV = true reads with device scope (the input was
-// written earlier in the same launch by other workgroups).
+// k-tiles [kst + s0, kst + s0 + slen) of every row and of both bf16 terms: one contiguous range
+// in memory, copied straight into LDS at the same offset relative to the K-block's start.  No
+// registers hold the data and no other wave reads this slice, so no workgroup barrier is
+// needed: the wave waits for its own loads (wait_vmem) and goes on.  One load instruction
+// moves 64 x 16 bytes.  DEV = true reads with device scope (the input was written earlier in
+// the same launch by other workgroups).
 #define EE_LDS __attribute__((address_space(3)))
 template <bool DEV>
-__device__ __forceinline__ void stage_x_wave(const GemmPlan &pl, const GemmIn &in, int rows, int kst, int s0, int slen,
-                                             char *lds, int lane)
+__device__ __forceinline__ void stage_x_wave(const GemmIn &in, int rows, int kst, int s0, int slen, char *lds, int lane)
 {
-    const int nchunk = slen * 4;  // 16-byte chunks of the slice in one row
-    for (int tr = 0; tr < 2 * rows; ++tr) {
-        const int term = tr >= rows ? 1 : 0, row = tr - term * rows;
-        const uint16_t *src = (term ? in.lo : in.hi) + (size_t)row * in.ldx + (size_t)(kst + s0) * 32;
-        char *dst = lds + ((size_t)tr * pl.xs_stride + (size_t)s0 * 32) * 2;
-        for (int c0 = 0; c0 < nchunk; c0 += 64)
-            if (c0 + lane < nchunk)
-                __builtin_amdgcn_global_load_lds((const EE_GLOBAL void *)(src + (size_t)(c0 + lane) * 8),
-                                                 (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, DEV ? 16 : 0);
-    }
+    const size_t tile_elems = (size_t)2 * rows * 32;          // one k-tile: both terms, all rows
+    const uint16_t *src = in.x + (size_t)(kst + s0) * tile_elems;
+    char *dst = lds + (size_t)s0 * tile_elems * 2;
+    const int nchunk = slen * 2 * rows * 4;                     // 16-byte chunks of the slice
+    for (int c0 = 0; c0 < nchunk; c0 += 64)
+        if (c0 + lane < nchunk)
+            __builtin_amdgcn_global_load_lds((const EE_GLOBAL void *)(src + (size_t)(c0 + lane) * 8),
+                                             (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, DEV ? 16 : 0);
 }
 
 // rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order.  DEV: the partial
@@ -449,7 +455,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = g[e] / (1.0f + __expf(-g[e])) * u[e];
             const int f = ((nt_first >> 1) + p) * 16 + qd * 4;
-            store_split4(a.sc.u[0], a.sc.u[1], (size_t)m * md.Kpad_F + f, o);
+            store_split4(a.sc.u, rows, m, f, o);
         }
         return;
     }
@@ -477,12 +483,12 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                 if (ep.gain_xn) {
                     float4 g = *reinterpret_cast<const float4 *>(ep.gain_xn + n);
                     float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
-                    store_split4(a.sc.xn[0], a.sc.xn[1], (size_t)m * md.Kpad_d + n, x);
+                    store_split4(a.sc.xn, rows, m, n, x);
                 }
                 if (ep.gain_xh) {
                     float4 g = *reinterpret_cast<const float4 *>(ep.gain_xh + n);
                     float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
-                    store_split4(a.sc.xh[0], a.sc.xh[1], (size_t)m * md.Kpad_d + n, x);
+                    store_split4(a.sc.xh, rows, m, n, x);
                 }
             }
             zbuf[idx] = sq;  // (ntg, m, quad) order
@@ -631,12 +637,11 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     trace_stamp(a, tsi, 0);
     // start the weight stream before anything else (unless the previous stage already did)
     if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
-    const uint16_t *xs_hi = reinterpret_cast<const uint16_t *>(lds);
-    const uint16_t *xs_lo = xs_hi + (size_t)rows * pl.xs_stride;
+    const uint16_t *xs = reinterpret_cast<const uint16_t *>(lds);  // the K-block's input, [k-tile][term][row][32]
     float *slots = reinterpret_cast<float *>(lds + md.lds_slots_off);
     int brow[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * pl.xs_stride;
+    for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * 32;
     const int bk = (lane >> 4) * 8;
     const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
 
@@ -651,9 +656,9 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
                 // blocks and the other waves must be done with theirs first.
                 if ((gi > 0 || kb > 0) && pl.KT % pl.nKB != 0) __syncthreads();
                 if (a.ph_hi - a.ph_lo > 1)
-                    stage_x_wave<true>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
+                    stage_x_wave<true>(in, rows, s.kst, s.s0, s.slen, lds, lane);
                 else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
-                    stage_x_wave<false>(pl, in, rows, s.kst, s.s0, s.slen, lds, lane);
+                    stage_x_wave<false>(in, rows, s.kst, s.s0, s.slen, lds, lane);
                 if (in.ss && gi == 0 && kb == 0) {
                     if (a.ph_hi - a.ph_lo > 1)
                         load_rstd<true>(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
@@ -708,11 +713,11 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             // the partial tile goes to the wave's slot in LDS
             auto tile_step = [&](const uint4 &av) __attribute__((always_inline)) {
                 bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
-                const int xo = (s.s0 + kk) * 32 + bk;
+                const int xo = (s.s0 + kk) * 2 * rows * 32 + bk;  // this k-tile's hi rows; the lo rows follow them
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
-                    uint4 bh = *reinterpret_cast<const uint4 *>(xs_hi + brow[mt] + xo);
-                    uint4 bl = *reinterpret_cast<const uint4 *>(xs_lo + brow[mt] + xo);
+                    uint4 bh = *reinterpret_cast<const uint4 *>(xs + brow[mt] + xo);
+                    uint4 bl = *reinterpret_cast<const uint4 *>(xs + brow[mt] + xo + rows * 32);
                     acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
                     acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
                 }
@@ -818,7 +823,7 @@ __device__ void embed_stage(const PassArgs &a, char *lds)
         sq[it] = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
         float4 g = *reinterpret_cast<const float4 *>(gain + c);
         float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
-        store_split4(a.sc.xn[0], a.sc.xn[1], (size_t)m * md.Kpad_d + c, x);
+        store_split4(a.sc.xn, rows, m, c, x);
     }
     __syncthreads();
     if (tid < rows) {
@@ -1040,9 +1045,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 }
                 uint32_t vh, vl;
                 split_bf16(num / den, vh, vl);
-                const size_t oi = (size_t)(s * M + r0 + i) * Kpad_d + hh * HD + e;
-                a.sc.attn[0][oi] = (uint16_t)vh;
-                a.sc.attn[1][oi] = (uint16_t)vl;
+                a.sc.attn[x_index(a.rows, s * M + r0 + i, hh * HD + e, 0)] = (uint16_t)vh;
+                a.sc.attn[x_index(a.rows, s * M + r0 + i, hh * HD + e, 1)] = (uint16_t)vl;
             }
         } else {
             float *out = a.sc.att_part + (size_t)item * ATT_ROWS * REC;
@@ -1100,9 +1104,8 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                         }
                     uint32_t vh, vl;
                     split_bf16(num / den, vh, vl);
-                    const size_t oi = (size_t)(s * M + r0 + i) * Kpad_d + hh * HD + e;
-                    a.sc.attn[0][oi] = (uint16_t)vh;
-                    a.sc.attn[1][oi] = (uint16_t)vl;
+                    a.sc.attn[x_index(a.rows, s * M + r0 + i, hh * HD + e, 0)] = (uint16_t)vh;
+                    a.sc.attn[x_index(a.rows, s * M + r0 + i, hh * HD + e, 1)] = (uint16_t)vl;
                 }
                 if (tid == 0) __hip_atomic_store(a.sc.att_count + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -1260,11 +1263,11 @@ __device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
 {
     const ModelDev &md = a.mdv;
     switch (kind) {
-    case G_QKV: return GemmIn{a.sc.xn[0], a.sc.xn[1], md.Kpad_d, a.sc.ss_a};
-    case G_O: return GemmIn{a.sc.attn[0], a.sc.attn[1], md.Kpad_d, nullptr};
-    case G_GU: return GemmIn{a.sc.xn[0], a.sc.xn[1], md.Kpad_d, a.sc.ss_f};
-    case G_DN: return GemmIn{a.sc.u[0], a.sc.u[1], md.Kpad_F, nullptr};
-    default: return GemmIn{a.sc.xh[0], a.sc.xh[1], md.Kpad_d, a.sc.ss_a};
+    case G_QKV: return GemmIn{a.sc.xn, a.sc.ss_a};
+    case G_O: return GemmIn{a.sc.attn, nullptr};
+    case G_GU: return GemmIn{a.sc.xn, a.sc.ss_f};
+    case G_DN: return GemmIn{a.sc.u, nullptr};
+    default: return GemmIn{a.sc.xh, a.sc.ss_a};
     }
 }
 

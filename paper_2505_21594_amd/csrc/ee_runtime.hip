@@ -171,10 +171,8 @@ static bool plan_set_blocks(GemmPlan &p, int rows_max, size_t budget)
 {
     for (int nkb = 1; nkb <= p.KT; ++nkb) {
         int klen = (p.KT + nkb - 1) / nkb;
-        size_t stride = (size_t)klen * 32 + 8;
-        if ((size_t)2 * rows_max * stride * 2 <= budget) {
+        if ((size_t)klen * 2 * rows_max * 32 * 2 <= budget) {  // [k-tile][term][row][32] bf16
             p.nKB = nkb;
-            p.xs_stride = (int)stride;
             return true;
         }
     }
@@ -391,7 +389,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
             ee_model_free(m);
             return fail(EE_EDEVICE, "ee_model_load: cannot fit one K-block of %d rows into %zu bytes of LDS", max_rows, x_budget);
         }
-        x_bytes = std::max(x_bytes, (size_t)2 * max_rows * p->xs_stride * 2);
+        x_bytes = std::max(x_bytes, (size_t)((p->KT + p->nKB - 1) / p->nKB) * 2 * max_rows * 32 * 2);
         p->steps = plan_steps(*p, m->nwg);
     }
     x_bytes = std::max(x_bytes, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
@@ -634,12 +632,10 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     const ModelDev &md = m->host_md;
     S_TRY(dev_alloc(s->allocs, &sc.h, (size_t)rows_max * d));
     S_TRY(dev_alloc(s->allocs, &sc.q, (size_t)rows_max * d));
-    for (int t = 0; t < 2; ++t) {
-        S_TRY(dev_alloc(s->allocs, &sc.xn[t], (size_t)rows_max * md.Kpad_d));
-        S_TRY(dev_alloc(s->allocs, &sc.xh[t], (size_t)rows_max * md.Kpad_d));
-        S_TRY(dev_alloc(s->allocs, &sc.attn[t], (size_t)rows_max * md.Kpad_d));
-        S_TRY(dev_alloc(s->allocs, &sc.u[t], (size_t)rows_max * md.Kpad_F));
-    }
+    S_TRY(dev_alloc(s->allocs, &sc.xn, (size_t)2 * rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.xh, (size_t)2 * rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.attn, (size_t)2 * rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.u, (size_t)2 * rows_max * md.Kpad_F));
     S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
