@@ -46,6 +46,7 @@ struct ee_model {
     int device;
     int nwg;
     size_t lds_budget;           // dynamic LDS bytes each launch asks for
+    int rows_api;                // max_rows as requested at load (c.max_rows is capped at LAUNCH_ROWS)
     ModelDev host_md;            // host copy of the device descriptor
     ModelDev *dev_md;
     std::vector<void *> allocs;  // every device allocation of the model
@@ -99,7 +100,7 @@ typedef void (*pass_kernel_t)(PassArgs);
 
 static pass_kernel_t chain_kernel(int rows)
 {
-    return rows <= 16 ? ee_gemm_chain_kernel<1> : (rows <= 32 ? ee_gemm_chain_kernel<2> : ee_gemm_chain_kernel<3>);
+    return rows <= 16 ? ee_gemm_chain_kernel<1> : ee_gemm_chain_kernel<2>;
 }
 
 static pass_kernel_t att_kernel(int hd) { return hd == 128 ? ee_att_kernel<128> : ee_att_kernel<64>; }
@@ -336,6 +337,8 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         int v = atoi(e);
         if (v >= 1 && v <= prop.multiProcessorCount) m->nwg = v;
     }
+    m->rows_api = max_rows;                         // rows one ee_verify_batch call may bring
+    max_rows = std::min(max_rows, LAUNCH_ROWS);     // rows of one launch (a larger batch runs as groups)
     c.max_rows = max_rows;
     c.n_workgroups = m->nwg;
     m->cfg = c;
@@ -503,6 +506,7 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 {
     if (!m || !out) return fail(EE_EINVAL, "ee_model_info: null argument");
     *out = m->cfg;
+    out->max_rows = m->rows_api;  // as requested at load; one launch handles up to LAUNCH_ROWS of them
     return EE_OK;
 }
 
@@ -937,8 +941,58 @@ static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exit
     return EE_OK;
 }
 
+static int verify_group(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                        const int32_t *exit_layers, int n_exits, const ee_verify_result **outs);
+
+// A batch of more rows than one launch handles runs as several groups of sessions, one after
+// the other; each group is a pass of its own (own leader, stream and events), so a session's
+// exit results are still published as soon as its group has them.
 extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
                                const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
+{
+    if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
+        return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
+    for (int i = 0; i < n_sessions; ++i)
+        if (!sessions[i] || !drafts[i]) return fail(EE_EINVAL, "ee_verify: null session or drafts");
+    const ee_model *m = sessions[0]->m;
+    const int M = gamma + 1;
+    if (gamma < 1) return fail(EE_EINVAL, "ee_verify: gamma %d < 1", gamma);
+    if (n_sessions * M > m->rows_api)
+        return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, m->rows_api);
+    for (int i = 0; i < n_sessions; ++i)
+        for (int j = 0; j < i; ++j)
+            if (sessions[j] == sessions[i]) return fail(EE_EINVAL, "ee_verify_batch: session listed twice");
+    // every check that can fail comes before the first group is enqueued
+    const float *gains[EE_MAX_EXITS];
+    int rc0 = check_exits(m, exit_layers, n_exits, gains);
+    if (rc0 != EE_OK) return rc0;
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        if (s->m != m) return fail(EE_EINVAL, "ee_verify_batch: sessions of different models");
+        if (gamma > s->max_gamma) return fail(EE_EINVAL, "ee_verify: gamma %d exceeds the session's max_gamma %d", gamma, s->max_gamma);
+        for (int j = 0; j < gamma; ++j)
+            if (drafts[i][j] < 0 || drafts[i][j] >= m->cfg.vocab)
+                return fail(EE_EINVAL, "ee_verify: draft token %d outside [0,%d)", drafts[i][j], m->cfg.vocab);
+    }
+    HIP_TRY(hipSetDevice(m->device));
+    for (int i = 0; i < n_sessions; ++i) {
+        ee_session *s = sessions[i];
+        if ((rc0 = finish_flight(s)) != EE_OK) return rc0;
+        if (!s->has_pending) return fail(EE_ESTATE, "ee_verify: session has no pending token (call ee_prefill first)");
+        if (s->kv_len + M > s->max_ctx) return fail(EE_ECAPACITY, "ee_verify: kv_len %d + %d rows exceed max_ctx %d", s->kv_len, M, s->max_ctx);
+    }
+    const int per_group = std::max(1, m->cfg.max_rows / M);
+    const int n_groups = (n_sessions + per_group - 1) / per_group;
+    for (int g = 0; g < n_groups; ++g) {  // groups of nearly equal size
+        const int lo = n_sessions * g / n_groups, hi = n_sessions * (g + 1) / n_groups;
+        int rc = verify_group(sessions + lo, hi - lo, drafts + lo, gamma, exit_layers, n_exits, outs ? outs + lo : nullptr);
+        if (rc != EE_OK) return rc;
+    }
+    return EE_OK;
+}
+
+static int verify_group(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                        const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
 {
     if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
         return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
