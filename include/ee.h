@@ -148,7 +148,7 @@ int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, const int32
               int n_exits, const ee_verify_result **out);
 /* One pass for several sessions of one model (multi-client serving): every
    weight byte is streamed once for all sessions of a group; attention, accept and
-   rollback are per session.  One launch handles up to 32 rows, so a batch of more
+   rollback are per session.  One launch handles up to 16 rows, so a batch of more
    rows runs as several groups of sessions one after the other, each group a pass
    of its own with its own events (results of an early group are published before a
    later group has run).  drafts[i] has gamma ids; n_sessions * (gamma+1) must not

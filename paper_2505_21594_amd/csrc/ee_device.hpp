@@ -11,7 +11,8 @@ namespace ee {
 constexpr int WAVES = 12;                // waves per workgroup: three per SIMD, 168 VGPRs each
 constexpr int WG_THREADS = WAVES * 64;
 constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
-constexpr int LAUNCH_ROWS = 32;           // rows one launch handles (two 16-row MFMA tiles); a larger batch runs as several groups
+constexpr int LAUNCH_ROWS = 16;           // rows one launch handles (one 16-row MFMA tile); a larger batch runs as several groups
+                                         // of sessions (measured: 8 x 5 rows as 3 groups 20 ms, as 2 groups of 20 rows 37 ms)
 constexpr int KV_PAGE = 16;              // positions per KV page
 constexpr int ATT_ROWS = 16;             // query rows of one attention item (one MFMA tile)
 constexpr int ATT_TILES = 8;             // KV pages (score tiles) a wave keeps in registers per item

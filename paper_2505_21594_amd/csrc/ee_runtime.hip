@@ -58,6 +58,8 @@ struct ee_session {
     unsigned flags;
     int max_ctx, max_gamma;
     hipStream_t stream;
+    hipStream_t run_stream;          // stream the pass this session leads is enqueued on (its own, or the first
+                                     // group leader's when a batch runs as several groups)
     hipEvent_t ev_start, ev_final, ev_exit[EE_MAX_EXITS];
     // KV cache
     int n_pages;
@@ -100,7 +102,8 @@ typedef void (*pass_kernel_t)(PassArgs);
 
 static pass_kernel_t chain_kernel(int rows)
 {
-    return rows <= 16 ? ee_gemm_chain_kernel<1> : ee_gemm_chain_kernel<2>;
+    (void)rows;  // one launch never has more than LAUNCH_ROWS = 16 rows
+    return ee_gemm_chain_kernel<1>;
 }
 
 static pass_kernel_t att_kernel(int hd) { return hd == 128 ? ee_att_kernel<128> : ee_att_kernel<64>; }
@@ -587,6 +590,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     } while (0)
 
     S_HIP(hipStreamCreate(&s->stream));
+    s->run_stream = s->stream;
     S_HIP(hipEventCreate(&s->ev_start));
     S_HIP(hipEventCreate(&s->ev_final));
     for (int i = 0; i < EE_MAX_EXITS; ++i) S_HIP(hipEventCreate(&s->ev_exit[i]));
@@ -787,11 +791,11 @@ static int launch_segment(ee_session *lead, PassArgs &a)
                 lead->lt_events.push_back(ev);
             }
             lead->lt_codes.push_back(launch_code(a, ph, end));
-            HIP_TRY(hipEventRecord(lead->lt_events[2 * i], lead->stream));
+            HIP_TRY(hipEventRecord(lead->lt_events[2 * i], lead->run_stream));
         }
-        hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->stream, a);
+        hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->run_stream, a);
         HIP_TRY(hipGetLastError());
-        if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->stream));
+        if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->run_stream));
         lead->epoch += (unsigned)(end - ph - 1);
         ph = end + a.fuse_accept;
     }
@@ -857,6 +861,7 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
     if (rc != EE_OK && rc != EE_EDEVICE) return rc;
     HIP_TRY(hipStreamSynchronize(s->stream));
     // reset
+    s->run_stream = s->stream;
     release_pages(s, 0);
     s->kv_len = 0;
     s->has_pending = false;
@@ -985,6 +990,7 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     const int n_groups = (n_sessions + per_group - 1) / per_group;
     for (int g = 0; g < n_groups; ++g) {  // groups of nearly equal size
         const int lo = n_sessions * g / n_groups, hi = n_sessions * (g + 1) / n_groups;
+        sessions[lo]->run_stream = sessions[0]->stream;  // the groups run one after the other on one stream
         int rc = verify_group(sessions + lo, hi - lo, drafts + lo, gamma, exit_layers, n_exits, outs ? outs + lo : nullptr);
         if (rc != EE_OK) return rc;
     }
@@ -1029,9 +1035,9 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
     for (int i = 0; i < n_sessions; ++i) {
         ee_session *s = sessions[i];
         if (s != lead) HIP_TRY(hipStreamSynchronize(s->stream));
-        if ((rc = ensure_pages(s, s->kv_len + M, lead->stream)) != EE_OK) return rc;
+        if ((rc = ensure_pages(s, s->kv_len + M, lead->run_stream)) != EE_OK) return rc;
         memcpy(s->host_drafts, drafts[i], (size_t)gamma * sizeof(int));
-        HIP_TRY(hipMemcpyAsync(s->dev_drafts, s->host_drafts, (size_t)gamma * sizeof(int), hipMemcpyHostToDevice, lead->stream));
+        HIP_TRY(hipMemcpyAsync(s->dev_drafts, s->host_drafts, (size_t)gamma * sizeof(int), hipMemcpyHostToDevice, lead->run_stream));
         s->result->gamma = gamma;
         s->result->n_exits = n_exits;
         s->result->device_status = 0;
@@ -1056,11 +1062,11 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
         if (((sessions[i]->flags & EE_NO_AUTOCOMMIT) != 0) != (a.commit == 0))
             return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
     HIP_TRY(hipMemcpyAsync(lead->dev_sessdev, lead->host_sessdev, (size_t)n_sessions * sizeof(SessDev),
-                           hipMemcpyHostToDevice, lead->stream));
+                           hipMemcpyHostToDevice, lead->run_stream));
     a.sess = lead->dev_sessdev;
     a.sess0 = lead->host_sessdev[0];
 
-    HIP_TRY(hipEventRecord(lead->ev_start, lead->stream));
+    HIP_TRY(hipEventRecord(lead->ev_start, lead->run_stream));
     lead->trace_n = 0;
     lead->lt_codes.clear();
     int layer = 0;
@@ -1073,7 +1079,7 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
         a.head_idx = e;
         a.head_gain = fin ? m->host_md.g_final : gains[e];
         if ((rc = launch_segment(lead, a)) != EE_OK) return rc;
-        HIP_TRY(hipEventRecord(fin ? lead->ev_final : lead->ev_exit[e], lead->stream));
+        HIP_TRY(hipEventRecord(fin ? lead->ev_final : lead->ev_exit[e], lead->run_stream));
         layer = a.layer_end;
     }
     for (int i = 0; i < n_sessions; ++i) {
