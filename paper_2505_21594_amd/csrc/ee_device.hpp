@@ -42,6 +42,7 @@ struct GemmPlan {
     int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
     int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
     int steps;       // tile slots per wave (longest wave sequence)
+    int lds_slots_off, lds_zbuf_off, lds_misc_off;  // this stage kind's layout of the LDS block after the input block
     int shared_acc;  // 1: the waves add their partial tiles into one accumulator per n-tile in LDS (atomic
                      // adds) instead of keeping one partial per wave: with many rows only that leaves room
                      // for all of a workgroup's n-tiles, so that the input is staged once per K-block
@@ -74,7 +75,6 @@ struct ModelDev {
     float eps, att_scale;
     int Kpad_d, Kpad_F;                  // K rounded up to 32
     int rows_max;
-    int lds_slots_off, lds_zbuf_off, lds_misc_off;  // byte offsets inside the dynamic LDS block
     GemmPlan plan[5];                    // indexed by GemmKind: QKV, O, GU, DN, HEAD
     // tiled weights: one allocation per GEMM kind, layer l at w[kind] + l * wstride[kind] (uint4 units)
     const uint4 *w[5];

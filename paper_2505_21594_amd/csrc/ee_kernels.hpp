@@ -234,10 +234,10 @@ struct Misc {  // views into the misc region of the LDS block
     float *sume;       // [rows_max]  sum of exp(logit - bestv) over the columns seen so far
 };
 
-__device__ __forceinline__ Misc misc_views(const ModelDev &md, char *lds)
+__device__ __forceinline__ Misc misc_views(const ModelDev &md, const GemmPlan &pl, char *lds)
 {
     Misc m;
-    char *p = lds + md.lds_misc_off;
+    char *p = lds + pl.lds_misc_off;
     const int R = md.rows_max;
     m.kvoff = reinterpret_cast<long long *>(p);
     p += (size_t)R * 8;
@@ -430,7 +430,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                                               int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds)
 {
     const ModelDev &md = a.mdv;
-    const float *slots = reinterpret_cast<const float *>(lds + md.lds_slots_off);
+    const float *slots = reinterpret_cast<const float *>(lds + pl.lds_slots_off);
     const int tid = opaque(threadIdx.x);
     const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
     const int n_part = pl.shared_acc ? 1 : WAVES;        // partial tiles to sum per output tile
@@ -459,7 +459,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         }
         return;
     }
-    float *zbuf = reinterpret_cast<float *>(lds + md.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group; O/DN: squares
+    float *zbuf = reinterpret_cast<float *>(lds + pl.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group; O/DN: squares
     const int items = gn * rows * 4;
     for (int idx = tid; idx < items; idx += WG_THREADS) {
         int ntg = idx / (rows * 4), rem = idx - ntg * rows * 4;
@@ -608,7 +608,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     const ModelDev &md = a.mdv;
     const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rows = a.rows;
-    const Misc mi = misc_views(md, lds);
+    const Misc mi = misc_views(md, pl, lds);
     int nt0, n_local;
     wg_units(pl, a.nwg, blockIdx.x, nt0, n_local);
 
@@ -630,7 +630,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     }
     if ((kind == G_O || kind == G_DN) && tid < rows) mi.rowss[tid] = 0.f;
     if (pl.shared_acc) {  // the accumulators start at zero (one workgroup barrier before the first add)
-        float *acc0 = reinterpret_cast<float *>(lds + md.lds_slots_off);
+        float *acc0 = reinterpret_cast<float *>(lds + pl.lds_slots_off);
         for (int i = tid; i < n_local * rows * 16; i += WG_THREADS) acc0[i] = 0.f;
         __syncthreads();
     }
@@ -638,7 +638,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     // start the weight stream before anything else (unless the previous stage already did)
     if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
     const uint16_t *xs = reinterpret_cast<const uint16_t *>(lds);  // the K-block's input, [k-tile][term][row][32]
-    float *slots = reinterpret_cast<float *>(lds + md.lds_slots_off);
+    float *slots = reinterpret_cast<float *>(lds + pl.lds_slots_off);
     int brow[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * 32;

@@ -10,6 +10,7 @@
 #include <unistd.h>
 
 #include <algorithm>
+#include <climits>
 #include <new>
 #include <vector>
 
@@ -120,7 +121,7 @@ static int plan_max_local(int U, int tpu, int nwg)
     return mx;
 }
 
-static GemmPlan make_plan(int N, int K, int tpu, int nwg, int rows_max, size_t slot_budget)
+static GemmPlan make_plan(int N, int K, int tpu)
 {
     GemmPlan p;
     memset(&p, 0, sizeof p);
@@ -131,16 +132,7 @@ static GemmPlan make_plan(int N, int K, int tpu, int nwg, int rows_max, size_t s
     p.KT = (K + 31) / 32;
     p.tpu = tpu;
     p.U = p.NT / tpu;
-    // group: as many n-tiles as the cross-wave reduction buffer holds
-    const size_t per_tile = (size_t)WAVES * rows_max * 16 * sizeof(float);
-    int grp = (int)(slot_budget / per_tile) / tpu * tpu;
-    grp = std::max(grp, tpu);
-    const int max_local = std::max(plan_max_local(p.U, tpu, nwg), tpu);
-    p.GRP = std::min(grp, max_local);
-    if (p.GRP < max_local) {  // per-wave partials of all n-tiles do not fit: one shared accumulator each
-        p.shared_acc = 1;
-        p.GRP = max_local;
-    }
+    p.GRP = tpu;
     p.nKB = 1;
     return p;
 }
@@ -370,46 +362,64 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
             lds_cap = std::max(lds_cap, (size_t)optin);
     }
-    const size_t slot_budget = std::max<size_t>(64 * 1024, (size_t)2 * WAVES * max_rows * 16 * sizeof(float));
-    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
-    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1, m->nwg, max_rows, slot_budget);
-    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg, max_rows, slot_budget);
-    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1, m->nwg, max_rows, slot_budget);
-    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1, m->nwg, max_rows, slot_budget);
+    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1);
+    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1);
+    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2);
+    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1);
+    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1);
     GemmPlan *plans[5] = {&md.plan[0], &md.plan[1], &md.plan[2], &md.plan[3], &md.plan[4]};
-    size_t slots = 0;
-    for (GemmPlan *p : plans) slots = std::max(slots, plan_slot_bytes(*p, max_rows));
-    int max_grp = 1;
-    for (GemmPlan *p : plans) max_grp = std::max(max_grp, p->GRP);
-    const size_t zbuf = align_up((size_t)max_rows * max_grp * 16 * sizeof(float), 256);
     const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4 + 4), 256);
     const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
-    if (slots + zbuf + misc + 4096 > lds_cap) {
-        ee_model_free(m);
-        return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
-    }
-    const size_t x_budget = (lds_cap - slots - zbuf - misc) / 256 * 256;
-    size_t x_bytes = 0;
+    // Every stage kind lays the block out for itself: [input K-block][partial tiles][zbuf][misc].
+    // More n-tiles per group need more room for partial tiles and leave less for the input, i.e.
+    // more K-blocks; a stage runs groups x K-blocks segments, each with a restaging of the input,
+    // so the pair with the fewest segments is taken (ties: fewer K-blocks).
+    size_t lds = 0;
     for (GemmPlan *p : plans) {
-        if (!plan_set_blocks(*p, max_rows, x_budget)) {
+        const int max_local = std::max(plan_max_local(p->U, p->tpu, m->nwg), p->tpu);
+        int best_cost = INT_MAX, best_grp = 0, best_nkb = 0, best_shared = 0;
+        for (int shared = 0; shared <= 1 && best_grp == 0; ++shared)  // shared accumulators only if nothing else fits
+            for (int grp = p->tpu; grp <= max_local; grp += p->tpu) {
+                if (shared && grp != max_local) continue;
+                const size_t slots = align_up((size_t)(shared ? 1 : WAVES) * grp * max_rows * 16 * sizeof(float), 256);
+                const size_t zbuf = align_up((size_t)max_rows * grp * 16 * sizeof(float), 256);
+                if (slots + zbuf + misc + 4096 > lds_cap) continue;
+                const size_t x_budget = (lds_cap - slots - zbuf - misc) / 256 * 256;
+                GemmPlan t = *p;
+                if (!plan_set_blocks(t, max_rows, x_budget)) continue;
+                const int cost = ((max_local + grp - 1) / grp) * t.nKB;
+                if (cost < best_cost || (cost == best_cost && t.nKB < best_nkb)) {
+                    best_cost = cost;
+                    best_grp = grp;
+                    best_nkb = t.nKB;
+                    best_shared = shared;
+                }
+            }
+        if (best_grp == 0) {
             ee_model_free(m);
-            return fail(EE_EDEVICE, "ee_model_load: cannot fit one K-block of %d rows into %zu bytes of LDS", max_rows, x_budget);
+            return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
         }
-        x_bytes = std::max(x_bytes, (size_t)((p->KT + p->nKB - 1) / p->nKB) * 2 * max_rows * 32 * 2);
+        p->GRP = best_grp;
+        p->nKB = best_nkb;
+        p->shared_acc = best_shared;
+        const size_t slots = align_up(plan_slot_bytes(*p, max_rows), 256);
+        const size_t zbuf = align_up((size_t)max_rows * p->GRP * 16 * sizeof(float), 256);
+        size_t x_bytes = (size_t)((p->KT + p->nKB - 1) / p->nKB) * 2 * max_rows * 32 * 2;
+        x_bytes = align_up(x_bytes, 256);
+        p->lds_slots_off = (int)x_bytes;
+        p->lds_zbuf_off = (int)(x_bytes + slots);
+        p->lds_misc_off = (int)(x_bytes + slots + zbuf);
+        lds = std::max(lds, x_bytes + slots + zbuf + misc);
         p->steps = plan_steps(*p, m->nwg);
     }
-    x_bytes = std::max(x_bytes, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
-    x_bytes = align_up(x_bytes, 256);
-    md.lds_slots_off = (int)x_bytes;
-    md.lds_zbuf_off = (int)(x_bytes + slots);
-    md.lds_misc_off = (int)(x_bytes + slots + zbuf);
-    size_t lds = std::max(x_bytes + slots + zbuf + misc, att);  // attention uses the block on its own
+    // the embedding stage keeps one float per (row, column quad) of its column range at the block's start
+    lds = std::max(lds, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
+    lds = std::max(lds, att);  // attention uses the block on its own
     // more than half of the CU's LDS keeps it to one workgroup per compute unit
     lds = std::max(lds, std::min((size_t)84 * 1024, lds_cap));
     m->lds_budget = lds;
     {
-        pass_kernel_t ks[6] = {chain_kernel(16), chain_kernel(32), chain_kernel(48), att_kernel(64), att_kernel(128),
-                               ee_misc_kernel};
+        pass_kernel_t ks[4] = {chain_kernel(16), att_kernel(64), att_kernel(128), ee_misc_kernel};
         for (pass_kernel_t k : ks) {
             hipError_t fe = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
