@@ -349,3 +349,33 @@ def test_scattered_pages_use_the_page_table(tiny_pair, mid_pair, monkeypatch):
         prompt = eegen.prompt_tokens(1200, 75, o.vocab)
         drafts = eegen.prompt_tokens(1201, 6, o.vocab)
         _one_round(g, o, prompt, drafts, exits, what="scattered pages")
+
+
+def test_empty_cache_and_exit_after_every_layer(model_dir):
+    """Degenerate cases: the first round of the paper's client (prompt of one token held back,
+    nothing cached: attention sees only the pass's own rows) and an exit after every layer."""
+    cfg = eegen.ModelConfig(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                            exit_layers=(1, 2, 3))
+    p = f"{model_dir}/gpu_tiny_all_exits.bin"
+    eegen.write_model(p, cfg, 31, gains="uniform")
+    g, o = ee.Model(p), eo.Model(p)
+    try:
+        for n_prompt in (1, 2):
+            prompt = eegen.prompt_tokens(40 + n_prompt, n_prompt, cfg.vocab)
+            drafts = eegen.prompt_tokens(50 + n_prompt, 4, cfg.vocab)
+            gs = g.session(64, max_gamma=8, flags=ee.KEEP_LOGITS)
+            os_ = o.session(64)
+            os_.prefill(prompt, flags=eo.HOLD_LAST)
+            gs.ee_prefill(prompt, flags=ee.HOLD_LAST)
+            assert gs.ee_kv_len() == os_.kv_len == n_prompt - 1
+            for rnd in range(3):
+                ro = os_.verify(drafts, [1, 2, 3], commit=True, want_logits=True)
+                rg = gs.verify_sync(drafts, [1, 2, 3])
+                exempt, _ = check_pass(ro, rg, gpu_logits(gs, 3), drafts, f"prompt {n_prompt} round {rnd}")
+                if exempt and (rg.accept_len != ro.accept_len or rg.next_token != ro.next_token):
+                    gs.ee_kv_truncate(os_.kv_len)
+                    gs.ee_set_pending(os_.pending)
+                assert gs.ee_kv_len() == os_.kv_len and gs.ee_pending() == os_.pending
+            gs.free()
+    finally:
+        g.free()
