@@ -42,6 +42,9 @@ struct GemmPlan {
     int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
     int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
     int steps;       // tile slots per wave (longest wave sequence)
+    int nwg;         // workgroups that take part in this stage kind: the fewest that keep the busiest one's
+                     // share unchanged, so that all of them get (nearly) the same share; the rest idle.
+                     // Half of the compute units already saturate HBM, uneven shares only lengthen the tail.
     int lds_slots_off, lds_zbuf_off, lds_misc_off;  // this stage kind's layout of the LDS block after the input block
     int shared_acc;  // 1: the waves add their partial tiles into one accumulator per n-tile in LDS (atomic
                      // adds) instead of keeping one partial per wave: with many rows only that leaves room

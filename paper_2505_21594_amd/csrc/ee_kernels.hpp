@@ -269,8 +269,8 @@ struct Seg {  // one (group, K-block) of a workgroup's tile sequence, seen from 
 
 __device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int &nt0, int &n_local)
 {
-    int u0, u1;
-    unit_range(pl.U, nwg, g, u0, u1);
+    int u0 = 0, u1 = 0;
+    if (g < nwg) unit_range(pl.U, nwg, g, u0, u1);  // workgroups past the stage's count own nothing
     nt0 = u0 * pl.tpu;
     n_local = (u1 - u0) * pl.tpu;
 }
@@ -329,11 +329,11 @@ __device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint
 {
     if (!nx.pl) return false;
     int nt0, n_local;
-    wg_units(*nx.pl, nwg, blockIdx.x, nt0, n_local);
+    wg_units(*nx.pl, nx.pl->nwg, blockIdx.x, nt0, n_local);
     if (n_local == 0) return true;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     Seg s = seg_setup(*nx.pl, nt0, n_local, wave, 0, 0);
-    seg_prefetch(nx.W, nwg, wave, s, pre);
+    seg_prefetch(nx.W, nx.pl->nwg, wave, s, pre);
     return true;
 }
 
@@ -610,7 +610,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     const int rows = a.rows;
     const Misc mi = misc_views(md, pl, lds);
     int nt0, n_local;
-    wg_units(pl, a.nwg, blockIdx.x, nt0, n_local);
+    wg_units(pl, pl.nwg, blockIdx.x, nt0, n_local);
 
     if (kind == G_HEAD) {
         if (tid < rows) {
@@ -636,7 +636,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
     }
     trace_stamp(a, tsi, 0);
     // start the weight stream before anything else (unless the previous stage already did)
-    if (!have_pre) seg_prefetch(W, a.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
+    if (!have_pre) seg_prefetch(W, pl.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
     const uint16_t *xs = reinterpret_cast<const uint16_t *>(lds);  // the K-block's input, [k-tile][term][row][32]
     float *slots = reinterpret_cast<float *>(lds + pl.lds_slots_off);
     int brow[MT];
@@ -706,8 +706,8 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             int ntg = 0, kk = 0;  // compute cursor
             const WRes wres = weight_resource(W);
             const int lane_off = lane * 16;
-            const int woff = tile_off(a.nwg, wave, s.step0);
-            const int wstep = a.nwg * WAVES * 1024;  // bytes from one tile of the wave's sequence to the next
+            const int woff = tile_off(pl.nwg, wave, s.step0);
+            const int wstep = pl.nwg * WAVES * 1024;  // bytes from one tile of the wave's sequence to the next
             const int woff_last = woff + (s.n - 1) * wstep;
             // one tile: two MFMAs (both bf16 terms of the input); at the end of an n-tile's run
             // the partial tile goes to the wave's slot in LDS
@@ -774,7 +774,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
             if (!last_seg) {
                 const int ngi = kb + 1 < pl.nKB ? gi : gi + 1, nkb = kb + 1 < pl.nKB ? kb + 1 : 0;
                 const Seg ns = seg_setup(pl, nt0, n_local, wave, ngi, nkb);
-                seg_prefetch(W, a.nwg, wave, ns, buf);
+                seg_prefetch(W, pl.nwg, wave, ns, buf);
             } else {
                 have_pre = prefetch_stage(next, a.nwg, buf);
             }

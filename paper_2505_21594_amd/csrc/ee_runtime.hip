@@ -208,7 +208,7 @@ static int upload_tiled(const ee_model *m, const GemmPlan &pl, int perm, const u
 {
     for (int i = 0; i < n_src; ++i)
         HIP_TRY(hipMemcpy(tmp + (size_t)i * elems_each, srcs[i], elems_each * 2, hipMemcpyHostToDevice));
-    hipLaunchKernelGGL(tile_weights_kernel, dim3(m->nwg), dim3(512), 0, 0, tmp, dst, pl, m->nwg, perm,
+    hipLaunchKernelGGL(tile_weights_kernel, dim3(pl.nwg), dim3(512), 0, 0, tmp, dst, pl, pl.nwg, perm,
                        m->cfg.d_model, m->cfg.head_dim, m->cfg.d_ffn);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipDeviceSynchronize());
@@ -368,6 +368,12 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1);
     md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1);
     GemmPlan *plans[5] = {&md.plan[0], &md.plan[1], &md.plan[2], &md.plan[3], &md.plan[4]};
+    for (GemmPlan *p : plans) {
+        // the fewest workgroups that do not raise the busiest one's share
+        const int most = (p->U + m->nwg - 1) / m->nwg;
+        p->nwg = std::min(m->nwg, (p->U + most - 1) / most);
+        if (const char *e = getenv("EE_FULL_GRID")) p->nwg = atoi(e) ? m->nwg : p->nwg;  // tuning aid
+    }
     const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4 + 4), 256);
     const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
     // Every stage kind lays the block out for itself: [input K-block][partial tiles][zbuf][misc].
@@ -376,7 +382,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     // so the pair with the fewest segments is taken (ties: fewer K-blocks).
     size_t lds = 0;
     for (GemmPlan *p : plans) {
-        const int max_local = std::max(plan_max_local(p->U, p->tpu, m->nwg), p->tpu);
+        const int max_local = std::max(plan_max_local(p->U, p->tpu, p->nwg), p->tpu);
         int best_cost = INT_MAX, best_grp = 0, best_nkb = 0, best_shared = 0;
         for (int shared = 0; shared <= 1 && best_grp == 0; ++shared)  // shared accumulators only if nothing else fits
             for (int grp = p->tpu; grp <= max_local; grp += p->tpu) {
@@ -410,7 +416,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         p->lds_zbuf_off = (int)(x_bytes + slots);
         p->lds_misc_off = (int)(x_bytes + slots + zbuf);
         lds = std::max(lds, x_bytes + slots + zbuf + misc);
-        p->steps = plan_steps(*p, m->nwg);
+        p->steps = plan_steps(*p, p->nwg);
     }
     // the embedding stage keeps one float per (row, column quad) of its column range at the block's start
     lds = std::max(lds, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
@@ -453,7 +459,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.emb = dev_emb;
 
     // tiled weights: one allocation per GEMM kind, layers at a fixed stride
-    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * m->nwg * WAVES * 64;
+    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * WAVES * 64;
     const long long s_head = md.wstride[G_HEAD];
     md.wstride[G_HEAD] = 0;
     (void)s_head;
@@ -465,7 +471,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * m->nwg * WAVES * 64, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * WAVES * 64, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
