@@ -379,3 +379,46 @@ def test_empty_cache_and_exit_after_every_layer(model_dir):
             gs.free()
     finally:
         g.free()
+
+
+@pytest.mark.parametrize("B,gamma,max_rows,chain", [(5, 2, 15, False), (7, 1, 14, False), (3, 7, 24, False), (6, 4, 30, True)])
+def test_batch_group_shapes(model_dir, B, gamma, max_rows, chain):
+    """Batches that fit one launch (<= 16 rows), that split into uneven groups, and one with
+    chained GEMM launches; also: more rows than the model was loaded for is refused."""
+    p = f"{model_dir}/gpu_tiny_groups.bin"
+    eegen.write_model(p, eegen.TINY, 77, gains="uniform")
+    g = ee.Model(p, max_rows=max_rows)
+    o = eo.Model(p)
+    sess, osess = [], []
+    try:
+        for b in range(B):
+            toks = eegen.prompt_tokens(400, 9 + 2 * b, o.vocab, session=b)
+            gs = g.session(96, max_gamma=gamma, flags=ee.CHAIN_LAUNCHES if chain else 0)
+            os_ = o.session(96)
+            if gs.ee_prefill(toks) != os_.prefill(toks):
+                gs.ee_set_pending(os_.pending)
+            sess.append(gs)
+            osess.append(os_)
+        for rnd in range(2):
+            drafts = [eegen.prompt_tokens(401 + rnd, gamma, o.vocab, session=b) for b in range(B)]
+            ee.ee_verify_batch(sess, drafts, TINY_EXITS)
+            for b in range(B):
+                sess[b].ee_wait_final()
+                ro = osess[b].verify(drafts[b], TINY_EXITS, want_logits=True)
+                rg = sess[b].final_result()
+                exempt, _ = check_pass(ro, rg, None, drafts[b], f"B={B} gamma={gamma} round {rnd} session {b}")
+                if exempt and (rg.accept_len != ro.accept_len or rg.next_token != ro.next_token):
+                    sess[b].ee_kv_truncate(osess[b].kv_len)
+                    sess[b].ee_set_pending(osess[b].pending)
+                assert sess[b].ee_kv_len() == osess[b].kv_len and sess[b].ee_pending() == osess[b].pending
+        if B * (gamma + 1) == max_rows and B < ee.EE_MAX_BATCH:
+            extra = g.session(96, max_gamma=gamma)
+            extra.ee_prefill(eegen.prompt_tokens(402, 8, o.vocab))
+            with pytest.raises(ee.EEError) as e:
+                ee.ee_verify_batch(sess + [extra], [d for d in drafts] + [drafts[0]], TINY_EXITS)
+            assert e.value.code == ee.EE_EINVAL
+            extra.free()
+    finally:
+        for s in sess:
+            s.free()
+        g.free()
