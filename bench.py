@@ -9,7 +9,9 @@ the greedy continuation with each position replaced by a random id with
 p = 0.3.  Weights, prompt and drafts are seeded synthetic data already resident
 in HBM when the timed region starts.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, steps, ms_per_step, config, device_ms_per_pass,
+verified_tokens_per_s, exit_lead_ms, roofline (dominant kernel against the HBM peak, with the
+measured HBM traffic per launch) and cpu_baseline (the CPU oracle timed on the host cores).
 """
 from __future__ import annotations
 
