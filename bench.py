@@ -216,8 +216,6 @@ def main():
     ap.add_argument("--workload", default="llama7b_g4_ctx512", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=20250521)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--chain-launches", action="store_true",
-                    help="run consecutive GEMM stages in one persistent launch with grid barriers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run 20 plain copies of 1 GiB (reference reading for the HBM traffic counters)")
     args = ap.parse_args()
@@ -241,7 +239,7 @@ def main():
     model = ee.Model(path, device=0, max_rows=B * M)
     print(f"[bench] model on GPU in {time.time() - t:.1f}s, {model.n_workgroups} workgroups", file=sys.stderr, flush=True)
     rounds = W + K
-    flags = ee.CHAIN_LAUNCHES if args.chain_launches else 0
+    flags = 0
     run = Run(ee, model, cfg, args.seed, n_prompt, gamma, exits, p_corrupt, B, n_emb, flags)
     t = time.time()
     sessions = run.make_sessions(rounds=rounds)
@@ -265,13 +263,10 @@ def main():
     wall = time.perf_counter() - t0
 
     kinds = per_launch_roofline(ee, run, min(rounds, 9))
-    gemm = [k for k in ("qkv", "o", "gu", "dn", "head", "chain") if k in kinds]
+    gemm = [k for k in ("qkv", "o", "gu", "dn", "head") if k in kinds]
     g_n = sum(kinds[k]["launches_per_pass"] for k in gemm)
     g_ms = sum(kinds[k]["launches_per_pass"] * kinds[k]["avg_launch_us"] for k in gemm) * 1e-3
     g_bytes = sum(kinds[k]["launches_per_pass"] * kinds[k]["algorithmic_bytes_per_launch"] for k in gemm)
-    if "chain" in kinds:  # chained launches: every GEMM byte of the pass
-        g_bytes = sum(algorithmic_bytes(cfg, len(ex), P, M, B) - launch_bytes(cfg, "att", P, M, B) * cfg.n_layers
-                      - launch_bytes(cfg, "embed", P, M, B) for P in ctx_at) / len(ctx_at)
 
     mean_dev_ms = sum(dev_ms) / len(dev_ms)
     bytes_per_pass = [algorithmic_bytes(cfg, len(ex), P, M, B) for P in ctx_at]
@@ -279,7 +274,7 @@ def main():
     pass_gbps = mean_bytes / (mean_dev_ms * 1e-3) / 1e9
     achieved = g_bytes / (g_ms * 1e-3) / 1e9
     committed = sum(a + B for a in accepted)
-    kernel_name = "ee_gemm_chain_kernel<%d>" % ((B * M + 15) // 16)
+    kernel_name = "ee_gemm_kernel<%d>" % ((B * M + 15) // 16)
     out = {
         "metric": "verify passes/s (Llama2-7B-shape, gamma=4, ctx 512)" if args.workload == "llama7b_g4_ctx512"
         else f"verify passes/s ({args.workload})",
@@ -291,7 +286,7 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "gamma": gamma, "exit_layers": ex, "prompt": n_prompt,
                    "batch": B, "embedding_prefix_rows": n_emb, "context_first": ctx_at[0], "context_last": ctx_at[-1],
-                   "launch_mode": "chain" if args.chain_launches else "stage"},
+                   "launch_mode": "stage"},
         "device_ms_per_pass": {"mean": mean_dev_ms, "median": statistics.median(dev_ms),
                                "p10": float(np.percentile(dev_ms, 10)), "p90": float(np.percentile(dev_ms, 90))},
         "verified_tokens_per_s": committed / wall,
@@ -299,7 +294,7 @@ def main():
         "exit_lead_ms": [mean_dev_ms - sum(e[i] for e in exit_ms) / len(exit_ms) for i in range(len(ex))],
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if args.chain_launches else measured_traffic(kernel_name, args.workload),
+                     "traffic": measured_traffic(kernel_name, args.workload),
                      "kernel": kernel_name,
                      "launches_per_pass": g_n, "algorithmic_bytes_per_launch": g_bytes / g_n,
                      "avg_launch_us": g_ms / g_n * 1e3,

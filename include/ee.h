@@ -66,12 +66,8 @@ extern "C" {
 /* ee_session_create flags */
 #define EE_KEEP_LOGITS 1u     /* keep every head's logits of the last pass (debug)      */
 #define EE_NO_AUTOCOMMIT 2u   /* final accept does not move kv_len / pending            */
-#define EE_TRACE 8u           /* debug: record stage timestamps of the last pass          */
 #define EE_TIME_LAUNCHES 16u  /* measurement: an event pair around every launch of a verify
                                  pass (see ee_launch_times); perturbs the pass slightly    */
-#define EE_CHAIN_LAUNCHES 4u  /* consecutive GEMM stages share one persistent launch with
-                                 grid barriers (and fetch the next stage's weights across
-                                 them) instead of one launch per stage; same results      */
 
 typedef struct ee_model ee_model;     /* opaque; immutable after load                   */
 typedef struct ee_session ee_session; /* opaque; one KV cache, one stream               */
@@ -113,7 +109,8 @@ const char *ee_last_error(void);
 /* Reads a model file (header + row-major bf16 tensors, see the generator's
    format description), uploads it to GPU `device` and re-lays the weight
    matrices out in the tile order the kernels stream.  max_rows (1..EE_MAX_ROWS)
-   is the largest number of rows a pass will carry; ee_model_load uses 16.
+   is the largest number of rows a pass (or a prefill chunk) will carry; ee_model_load
+   uses 16.
    Cold path; synchronous. */
 int ee_model_load(const char *path, int device, ee_model **out);
 int ee_model_load_ex(const char *path, int device, int max_rows, ee_model **out);
@@ -146,13 +143,13 @@ int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_emb, const 
    block.  A pass still in flight on this session is waited for first. */
 int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
               int n_exits, const ee_verify_result **out);
-/* One pass for several sessions of one model (multi-client serving): every
-   weight byte is streamed once for all sessions of a group; attention, accept and
-   rollback are per session.  One launch handles up to 16 rows, so a batch of more
-   rows runs as several groups of sessions one after the other, each group a pass
-   of its own with its own events (results of an early group are published before a
-   later group has run).  drafts[i] has gamma ids; n_sessions * (gamma+1) must not
-   exceed the model's max_rows.  outs may be NULL. */
+/* One pass for several sessions of one model (multi-client serving, the paper's
+   batch-processing appendix): every weight byte is streamed once for all rows of all
+   sessions; attention, accept and rollback are per session.  The first session leads
+   the pass: its stream, events and scratch carry it (list the session with the largest
+   max_ctx first); every session's own result block is filled and every session can be
+   waited on.  drafts[i] has gamma ids; n_sessions * (gamma+1) must not exceed the
+   model's max_rows (at most EE_MAX_ROWS).  outs may be NULL. */
 int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts,
                     int gamma, const int32_t *exit_layers, int n_exits,
                     const ee_verify_result **outs);
@@ -174,8 +171,10 @@ int ee_set_pending(ee_session *s, int32_t token);
 int ee_kv_len(ee_session *s, int *out);
 int ee_pending(ee_session *s, int32_t *out);
 
-/* Debug (needs EE_KEEP_LOGITS): logits of head head_idx of the last verify pass
-   (0..n_exits-1 = exit heads in order, n_exits = final head) as float[gamma+1][vocab]. */
+/* Debug: logits of head head_idx of the last verify pass (0..n_exits-1 = exit heads in
+   order, n_exits = final head) for this session's rows as float[gamma+1][vocab].  The
+   session that led the pass (the session itself for ee_verify, the first one of an
+   ee_verify_batch call) must have been created with EE_KEEP_LOGITS. */
 int ee_debug_logits(ee_session *s, int head_idx, float *out);
 
 /* Measurement aid: `reps` launches of a plain copy kernel (ee_copy_kernel) that moves `bytes`
@@ -186,9 +185,17 @@ int ee_debug_copy(int device, size_t bytes, int reps);
 /* hipDeviceSynchronize on `device`: every pass enqueued so far has finished. */
 int ee_device_synchronize(int device);
 
-/* Measurement aid: `launches` launches of the pass kernel that execute `barriers`
-   grid-wide barriers each and nothing else; mean microseconds per launch. */
-int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch);
+/* Per-session options; the session must have no pass in flight.
+   EE_OPT_ATT_SPLITS: parts the cached positions of a head are split into for attention
+     (1..16), 0 = chosen per pass from the context length and the number of compute units
+     (the default).  A value the context or the scratch cannot take is raised / lowered to
+     the nearest that works.
+   EE_OPT_SCATTER_PAGES: 1 = hand KV pages out in descending order from the next ee_prefill
+     on, so that a session's pages are not consecutive and every lookup goes through the page
+     table (a fresh session's pages are consecutive and the kernels then skip the lookup). */
+#define EE_OPT_ATT_SPLITS 1
+#define EE_OPT_SCATTER_PAGES 2
+int ee_session_option(ee_session *s, int option, int value);
 
 /* Measurement (EE_TIME_LAUNCHES sessions, pass led by `s`): for every kernel launch of the
    last verify pass, in launch order, what it ran (EE_LAUNCH_* code) and the milliseconds
@@ -198,22 +205,11 @@ int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_pe
 #define EE_LAUNCH_O 1       /* attention output projection + residual + FFN norm input   */
 #define EE_LAUNCH_GU 2      /* gate/up projections + SiLU * up                           */
 #define EE_LAUNCH_DN 3      /* down projection + residual + next norm inputs             */
-#define EE_LAUNCH_HEAD 4    /* exit or final head: norm + LM head + per-workgroup argmax */
+#define EE_LAUNCH_HEAD 4    /* exit or final head: norm + LM head + argmax, accept rule,
+                               publication, KV commit                                    */
 #define EE_LAUNCH_ATT 5     /* attention over the paged KV cache                         */
 #define EE_LAUNCH_EMBED 6   /* embedding gather                                          */
-#define EE_LAUNCH_ACCEPT 7  /* global argmax, accept rule, publication, KV commit        */
-#define EE_LAUNCH_CHAIN 8   /* several GEMM stages in one launch (EE_CHAIN_LAUNCHES)     */
 int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, int *n_launches);
-
-/* Debug (EE_TRACE sessions): wall-clock stamps, in 10 ns ticks, that workgroup 0 took in every
-   GEMM stage of the last verify pass; 8 values per stage (stage start, inputs staged, later
-   K-block staged, weights streamed, cross-wave reduce reached, epilogue done, stage end, grid
-   barrier entered). */
-int ee_debug_trace(ee_session *s, unsigned long long *out, int max_values, int *n_values);
-
-/* Debug (EE_TRACE sessions): the same clock at the start and at the end of every workgroup of
-   every launch of the last verify pass, in launch order: launches x workgroups x 2 values. */
-int ee_debug_trace_workgroups(ee_session *s, unsigned long long *out, int max_values, int *n_values);
 
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
    kernels assume and compares with the plain 16x32 . 32x16 product. */

@@ -26,18 +26,17 @@ EE_EINVAL, EE_ESTATE, EE_ECAPACITY, EE_EIO, EE_EFORMAT, EE_EDEVICE = -1, -2, -3,
 HOLD_LAST = 1
 KEEP_LOGITS = 1
 NO_AUTOCOMMIT = 2
-CHAIN_LAUNCHES = 4
-TRACE = 8
 TIME_LAUNCHES = 16
-LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "att", "embed", "accept", "chain")
+OPT_ATT_SPLITS, OPT_SCATTER_PAGES = 1, 2
+LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "att", "embed")
 
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
     "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
-    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_debug_launch_cost", "ee_debug_trace",
-    "ee_launch_times", "ee_debug_trace_workgroups", "ee_debug_copy",
+    "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_session_option",
+    "ee_launch_times", "ee_debug_copy",
 ]
 
 
@@ -107,10 +106,8 @@ def load_library():
     lib.ee_debug_logits.argtypes = [vp, ci, vp]
     lib.ee_debug_mfma_layout.argtypes = [ci]
     lib.ee_device_synchronize.argtypes = [ci]
-    lib.ee_debug_launch_cost.argtypes = [vp, ci, ci, P(ctypes.c_float)]
-    lib.ee_debug_trace.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
+    lib.ee_session_option.argtypes = [vp, ci, ci]
     lib.ee_debug_copy.argtypes = [ci, ctypes.c_size_t, ci]
-    lib.ee_debug_trace_workgroups.argtypes = [vp, P(ctypes.c_ulonglong), ci, P(ci)]
     lib.ee_launch_times.argtypes = [vp, i32p, P(ctypes.c_float), ci, P(ci)]
     for name in EXPORTS:
         if name != "ee_last_error":
@@ -251,23 +248,8 @@ class Session:
         _check(self._l.ee_debug_logits(self._h, head_idx, out.ctypes.data))
         return out
 
-    def ee_debug_launch_cost(self, launches: int, barriers: int) -> float:
-        us = ctypes.c_float()
-        _check(self._l.ee_debug_launch_cost(self._h, launches, barriers, ctypes.byref(us)))
-        return float(us.value)
-
-    def ee_debug_trace(self) -> np.ndarray:
-        buf = (ctypes.c_ulonglong * (1 << 14))()
-        n = ctypes.c_int()
-        _check(self._l.ee_debug_trace(self._h, buf, 1 << 14, ctypes.byref(n)))
-        return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, 8).copy()
-
-    def ee_debug_trace_workgroups(self) -> np.ndarray:
-        cap = 2048 * self.model.n_workgroups * 2
-        buf = (ctypes.c_ulonglong * cap)()
-        n = ctypes.c_int()
-        _check(self._l.ee_debug_trace_workgroups(self._h, buf, cap, ctypes.byref(n)))
-        return np.frombuffer(buf, dtype=np.uint64, count=n.value).reshape(-1, self.model.n_workgroups, 2).copy()
+    def ee_session_option(self, option: int, value: int) -> None:
+        _check(self._l.ee_session_option(self._h, option, value))
 
     def ee_launch_times(self):
         """[(launch code, milliseconds)] of every launch of the last verify pass."""

@@ -8,11 +8,11 @@
 
 namespace ee {
 
-constexpr int WAVES = 12;                // waves per workgroup: three per SIMD, 168 VGPRs each
+constexpr int SWAVES = 8;                // streaming waves: weight tiles -> MFMA
+constexpr int HWAVES = 4;                // helper waves: stage the input blocks while the others stream
+constexpr int WAVES = SWAVES + HWAVES;   // three per SIMD, 168 VGPRs each
 constexpr int WG_THREADS = WAVES * 64;
-constexpr int PF_DEPTH = 8;              // weight tiles (1 KB each) in flight per wave
-constexpr int LAUNCH_ROWS = 16;           // rows one launch handles (one 16-row MFMA tile); a larger batch runs as several groups
-                                         // of sessions (measured: 8 x 5 rows as 3 groups 20 ms, as 2 groups of 20 rows 37 ms)
+constexpr int GROUP_TILES = 8;           // n-tiles whose accumulators a streaming wave keeps in registers at once
 constexpr int KV_PAGE = 16;              // positions per KV page
 constexpr int ATT_ROWS = 16;             // query rows of one attention item (one MFMA tile)
 constexpr int ATT_TILES = 8;             // KV pages (score tiles) a wave keeps in registers per item
@@ -26,12 +26,15 @@ constexpr int ATT_MAX_SPLITS = 16;
 //
 // The N axis is cut into units of `tpu` n-tiles (1, or 2 for a gate/up pair);
 // workgroup g owns a contiguous range of units (unit_range below) for the whole of K, so
-// every output element is complete inside one workgroup.  A workgroup walks its tiles
-//   for group (GRP n-tiles) : for K-block kb : for n-tile in group : for k-tile in block
-// where K-block kb covers the k-tiles [KT*kb/nKB, KT*(kb+1)/nKB); inside one
-// (K-block, n-tile) run of klen tiles, wave w takes [klen*w/WAVES, klen*(w+1)/WAVES).
+// every output element is complete inside one workgroup.  Its n-tiles are taken in groups
+// of up to GROUP_TILES; streaming wave w owns the k-tiles w, w + SWAVES, w + 2 SWAVES, ...
+// ("k-steps" s = 0, 1, ...) and walks
+//   for group : for k-step s : for n-tile of the group : tile(n-tile, k-tile w + SWAVES*s)
+// keeping one accumulator per n-tile of the group in registers for the whole of K.  The order
+// does not depend on the number of rows; how many k-tiles of the input sit in LDS at a time
+// (StageLds) is chosen per launch.
 // In memory the tiles are interleaved over the whole chip: the i-th tile of the
-// sequence of wave w of workgroup g sits at tile slot (i*nwg + g)*WAVES + w, so at any
+// sequence of wave w of workgroup g sits at tile slot (i*nwg + g)*SWAVES + w, so at any
 // moment all waves together read one contiguous window (measured: up to 15 % more
 // HBM bandwidth than one contiguous range per wave).  `steps` is the longest sequence.
 struct GemmPlan {
@@ -39,16 +42,27 @@ struct GemmPlan {
     int NT, KT;      // tiles along N and K (K zero-padded to 32)
     int tpu;         // n-tiles per unit
     int U;           // units = NT / tpu
-    int nKB;         // K-blocks (x_hat is staged in LDS one K-block at a time)
-    int GRP;         // n-tiles per group (cross-wave reduction buffer holds one group)
     int steps;       // tile slots per wave (longest wave sequence)
     int nwg;         // workgroups that take part in this stage kind: the fewest that keep the busiest one's
                      // share unchanged, so that all of them get (nearly) the same share; the rest idle.
                      // Half of the compute units already saturate HBM, uneven shares only lengthen the tail.
-    int lds_slots_off, lds_zbuf_off, lds_misc_off;  // this stage kind's layout of the LDS block after the input block
-    int shared_acc;  // 1: the waves add their partial tiles into one accumulator per n-tile in LDS (atomic
-                     // adds) instead of keeping one partial per wave: with many rows only that leaves room
-                     // for all of a workgroup's n-tiles, so that the input is staged once per K-block
+};
+
+// LDS map of one GEMM launch, chosen on the host from the rows of the launch:
+//   [input block 0][input block 1] ... [misc]
+// An input block holds kbt k-tiles of the input as [k-tile][term][row][32] bf16 (both bf16
+// terms, all rows); with nkb > 1 blocks the helper waves fill one buffer while the streaming
+// waves read the other.  After a group's last block the same space holds the waves'
+// partial tiles for the cross-wave sum ([wave][n-tile of the chunk][row][16] floats, `chunk`
+// n-tiles at a time) and, behind them at zbuf_off, one [row][chunk*16] float tile for the
+// head's logits / the squares of the residual stream.
+struct StageLds {
+    int kbt;         // k-tiles per input block (a multiple of SWAVES)
+    int nkb;         // input blocks along K
+    int xbuf_bytes;  // bytes of one input buffer
+    int chunk;       // n-tiles reduced at a time
+    int zbuf_off;
+    int misc_off;
 };
 
 // Units [u0, u1) of workgroup g.  Workgroups are dealt to the chip's 8 XCDs round-robin (XCD =
@@ -78,7 +92,7 @@ struct ModelDev {
     float eps, att_scale;
     int Kpad_d, Kpad_F;                  // K rounded up to 32
     int rows_max;
-    GemmPlan plan[5];                    // indexed by GemmKind: QKV, O, GU, DN, HEAD
+    GemmPlan plan[5];                    // indexed by GemmKind: QKV, O, GU, DN, HEAD (host side; a launch gets its own by value)
     // tiled weights: one allocation per GEMM kind, layer l at w[kind] + l * wstride[kind] (uint4 units)
     const uint4 *w[5];
     long long wstride[5];
@@ -118,22 +132,19 @@ struct Scratch {
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
     float *cand_sum;     // [nwg][rows_max]      sum over the workgroup's columns of exp(logit - candidate value)
-    unsigned *bar_flags; // [nwg]                grid barrier: last epoch each workgroup arrived at
-    int *err;            // set to 1 when a bounded wait gave up
-    unsigned long long *trace;  // debug: wall-clock stamps of workgroup 0 (EE_TRACE sessions), else nullptr
 };
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
 struct PassArgs {
-    const ModelDev *md;                  // device copy of the model descriptor (tables indexed by stage kind)
-    ModelDev mdv;                        // the descriptor by value (fields with constant names only)
-    GemmPlan plan0;                      // plan and weights of the launch's first GEMM stage
+    ModelDev mdv;                        // the model descriptor by value
+    GemmPlan plan0;                      // plan, LDS map and weights of the launch's GEMM stage
+    StageLds lay;
     const uint4 *W0;
     Scratch sc;
     int nwg;
     int n_sess, M, rows;                 // rows = n_sess * M
-    int mode;                            // 0 verify, 1 prefill chunk, 2 barrier measurement
+    int mode;                            // 0 verify, 1 prefill chunk
     const int *pf_tokens;                // prefill: [rows] token ids, < 0 => embedding row
     const uint16_t *pf_emb;              // prefill: [rows][d] bf16
     int pf_pos0;                         // prefill: position of row 0
@@ -146,12 +157,10 @@ struct PassArgs {
     int att_splits;
     int H, d, Kpad_d;                    // copies of the model descriptor's fields for the attention kernel
     float att_scale;
-    int ph_lo, ph_hi;                    // stages [ph_lo, ph_hi) of the segment's stage list run in this launch
-    unsigned spin_limit;
-    unsigned epoch_base;                 // barrier epoch before this launch
-    int trace_base;                      // debug: first stamp slot of this launch
+    int stage;                           // index of this launch's stage in the segment's stage list
     const SessDev *sess;                 // device array [n_sess]
     SessDev sess0;                       // copy of sess[0]
 };
+
 
 }  // namespace ee

@@ -1,8 +1,8 @@
 // gfx950 kernels of the verification pass.
 //
 // A segment of the pass (embedding, a range of layers, optionally an LM head with its
-// accept step) is a list of stages.  Per layer (Eq. 3 of the paper, f = Llama-2 block)
-// there are five:
+// accept step) is a list of stages, one launch each.  Per layer (Eq. 3 of the paper,
+// f = Llama-2 block) there are five:
 //   QKV   x_hat . [Wq;Wk;Wv]^T, * rstd, RoPE, q -> scratch, k/v -> paged bf16 cache
 //   ATT   causal attention of the new rows over the cache         -> attn
 //   O     h += attn . Wo^T
@@ -11,11 +11,9 @@
 // Head (z^(l) = LMHead(h^(l)); accept rule of Eq. 2 / Eq. 5; confidence of Eq. 4):
 //   HEAD    x_hat . W_lm^T, * rstd, argmax candidate and softmax denominator per workgroup
 //   ACCEPT  global argmax (lowest id wins ties), confidence, accept length, publication
-//           to pinned host memory, KV commit.
-// By default every stage is one launch (ee_gemm_chain_kernel for the five GEMM kinds,
-// ee_att_kernel, ee_misc_kernel for embedding and accept); optionally consecutive GEMM
-// stages share one launch of ee_gemm_chain_kernel with a grid-wide barrier between them,
-// each wave fetching the first weight tiles of its next stage before it enters the barrier.
+//           to pinned host memory, KV commit (run by the head launch's last workgroup).
+// Kernels: ee_gemm_kernel<MT> for the five GEMM kinds (MT = 16-row tiles of the pass, rows <= 48),
+// ee_att_kernel, ee_misc_kernel (embedding).
 //
 // Every GEMM stage streams the weights once (HBM-bound).  A workgroup owns whole
 // n-tiles for the full K, so its outputs are complete after a cross-wave sum in
@@ -32,13 +30,12 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
-constexpr int D = PF_DEPTH;
-
 // Pointers read from descriptors in memory are generic to the compiler, and generic loads go
 // through the flat path, whose completion also counts against the LDS counter: a wait for an
 // LDS read would then drain every weight load in flight.  These helpers state that the
 // address is global memory.
 #define EE_GLOBAL __attribute__((address_space(1)))
+#define EE_LDS __attribute__((address_space(3)))
 template <typename T>
 __device__ __forceinline__ const EE_GLOBAL T *as_global(const T *p)
 {
@@ -77,11 +74,10 @@ __device__ __forceinline__ uint4 load_global16(const void *p)
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// Device-scope accesses for the small buffers that cross a grid barrier inside one launch
-// (GEMM inputs written by one stage's epilogue and read by the next stage's staging, partial
-// sums of squares).  Stores write through to memory and loads bypass the per-XCD L2, so the
-// barrier itself needs no cache write-back or invalidate; everything else is read-only in
-// the launch or crosses a kernel boundary.
+// Device-scope accesses for the small buffers that one launch's workgroups exchange among
+// themselves (attention partials of a split position range, argmax candidates of a head):
+// stores write through to memory and loads bypass the per-XCD L2.  Everything else is read-only
+// in a launch or crosses a kernel boundary.
 __device__ __forceinline__ void store_dev64(void *p, uint2 v)
 {
     __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), ((unsigned long long)v.y << 32) | v.x,
@@ -96,25 +92,11 @@ __device__ __forceinline__ float load_dev32(const float *p)
     return __hip_atomic_load(as_global(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 // The value itself, but opaque to the optimiser: keeps per-thread index arithmetic of a stage
-// from being hoisted out of the stage loop, where it would occupy registers for the whole kernel.
+// from being hoisted to the kernel's start, where it would occupy registers throughout.
 __device__ __forceinline__ int opaque(int x)
 {
     asm volatile("" : "+v"(x));
     return x;
-}
-// debug: stamp slot (stage-in-launch, k) with the 100 MHz wall clock, workgroup 0 only
-#define EE_TRACE_SLOTS 8
-#define EE_TRACE_WG_BASE (1 << 14)  // per-workgroup stamps follow workgroup 0's slots
-__device__ __forceinline__ void trace_stamp(const PassArgs &a, int stage_in_launch, int k)
-{
-    if (a.sc.trace && blockIdx.x == 0 && threadIdx.x == 0)
-        a.sc.trace[a.trace_base + stage_in_launch * EE_TRACE_SLOTS + k] = wall_clock64();
-}
-// debug: every workgroup stamps the start (k = 0) and the end (k = 1) of the launch
-__device__ __forceinline__ void trace_stamp_wg(const PassArgs &a, int k)
-{
-    if (a.sc.trace && threadIdx.x == 0)
-        a.sc.trace[EE_TRACE_WG_BASE + ((size_t)(a.trace_base / EE_TRACE_SLOTS) * a.nwg + blockIdx.x) * 2 + k] = wall_clock64();
 }
 // The launch arguments are several hundred bytes; the compiler fetches their fields where it
 // needs them, and every first touch of another 64-byte line is a miss of the scalar cache that
@@ -146,6 +128,15 @@ __device__ __forceinline__ void wait_vmem()
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
     asm volatile("" ::: "memory");
 }
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every
+// vector memory operation of the wave, i.e. for all weight tiles a streaming wave has in
+// flight; nothing that crosses these barriers goes through global memory.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
@@ -155,42 +146,6 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f)
     uint32_t u = __float_as_uint(f);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
-}
-
-// ------------------------------------------------------------------ grid barrier
-
-// Every workgroup publishes the epoch it has reached in its own flag and waits until all
-// flags have reached it.  Callers make their cross-workgroup data visible themselves:
-// device-scope stores followed by wait_vmem() in every wave before the barrier, device-scope
-// loads after it.  The wait is bounded: after spin_limit polls the workgroup raises *err and
-// goes on, and later barriers fall through at once, so the grid always drains.
-__device__ __forceinline__ void grid_barrier(unsigned *flags, unsigned nwg, unsigned epoch, int *err,
-                                             unsigned spin_limit)
-{
-    wait_vmem();
-    __syncthreads();
-    if (threadIdx.x < 64) {
-        if (threadIdx.x == 0)
-            __hip_atomic_store(&flags[blockIdx.x], epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        unsigned spins = 0;
-        while (true) {
-            bool ok = true;
-            for (unsigned i = threadIdx.x; i < nwg; i += 64) {
-                unsigned f = __hip_atomic_load(&flags[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ok = ok && ((int)(f - epoch) >= 0);
-            }
-            if (__all(ok)) break;
-            ++spins;
-            if ((spins & 63u) == 0 &&
-                __hip_atomic_load(err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
-                break;
-            if (spins > spin_limit) {
-                __hip_atomic_store(err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                break;
-            }
-        }
-    }
-    __syncthreads();
 }
 
 // ------------------------------------------------------------------ rows
@@ -224,25 +179,25 @@ __device__ __forceinline__ int row_token(const PassArgs &a, int r)
 // ------------------------------------------------------------------ LDS map
 
 struct Misc {  // views into the misc region of the LDS block
-    float *rstd;       // [rows_max]
-    float *rowss;      // [rows_max]  this workgroup's sum of h^2 per row (O / DN stages)
-    int *pos;          // [rows_max]
-    long long *kvoff;  // [rows_max]  element offset of the row's (layer, page, head 0) record in the KV pools
-    float2 *rope;      // [rows_max][hd/2]
-    float *bestv;      // [rows_max]
-    int *besti;        // [rows_max]
-    float *sume;       // [rows_max]  sum of exp(logit - bestv) over the columns seen so far
+    float *rstd;       // [rows]
+    float *rowss;      // [rows]  this workgroup's sum of h^2 per row (O / DN stages)
+    int *pos;          // [rows]
+    long long *kvoff;  // [rows]  element offset of the row's (layer, page, head 0) record in the KV pools
+    float *bestv;      // [rows]
+    int *besti;        // [rows]
+    float *sume;       // [rows]  sum of exp(logit - bestv) over the columns seen so far
+    int *lastf;        // "this workgroup finished the head launch last"
 };
 
-__device__ __forceinline__ Misc misc_views(const ModelDev &md, const GemmPlan &pl, char *lds)
+constexpr int MISC_BYTES = EE_MAX_ROWS * (8 + 6 * 4) + 64;
+
+__device__ __forceinline__ Misc misc_views(const StageLds &ly, char *lds)
 {
     Misc m;
-    char *p = lds + pl.lds_misc_off;
-    const int R = md.rows_max;
+    char *p = lds + ly.misc_off;
+    const int R = EE_MAX_ROWS;
     m.kvoff = reinterpret_cast<long long *>(p);
     p += (size_t)R * 8;
-    m.rope = reinterpret_cast<float2 *>(p);
-    p += (size_t)R * (md.hd / 2) * 8;
     m.rstd = reinterpret_cast<float *>(p);
     p += (size_t)R * 4;
     m.rowss = reinterpret_cast<float *>(p);
@@ -254,91 +209,25 @@ __device__ __forceinline__ Misc misc_views(const ModelDev &md, const GemmPlan &p
     m.besti = reinterpret_cast<int *>(p);
     p += (size_t)R * 4;
     m.sume = reinterpret_cast<float *>(p);
+    p += (size_t)R * 4;
+    m.lastf = reinterpret_cast<int *>(p);
     return m;
 }
 
 // ------------------------------------------------------------------ weight-stream geometry
 
-struct Seg {  // one (group, K-block) of a workgroup's tile sequence, seen from one wave
-    int gn;           // n-tiles in the group
-    int klen, kst;    // k-tiles of the block, first k-tile
-    int s0, slen;     // this wave's slice of every run: [s0, s0 + slen)
-    int n;            // tiles of this wave in the segment = gn * slen
-    int step0;        // position of the segment's first tile in this wave's sequence
-};
-
-__device__ __forceinline__ void wg_units(const GemmPlan &pl, int nwg, int g, int &nt0, int &n_local)
+__device__ __host__ inline void wg_units(const GemmPlan &pl, int g, int &nt0, int &n_local)
 {
     int u0 = 0, u1 = 0;
-    if (g < nwg) unit_range(pl.U, nwg, g, u0, u1);  // workgroups past the stage's count own nothing
+    if (g < pl.nwg) unit_range(pl.U, pl.nwg, g, u0, u1);  // workgroups past the stage's count own nothing
     nt0 = u0 * pl.tpu;
     n_local = (u1 - u0) * pl.tpu;
 }
 
-// tiles this wave streams in the groups/blocks before (gi, kb)
-__device__ __forceinline__ int seg_steps_before(const GemmPlan &pl, int n_local, int wave, int gi, int kb)
-{
-    // every full pass over K gives the wave  sum_kb slen(kb)  tiles per n-tile
-    int per_tile = 0, before_kb = 0;
-    for (int b = 0; b < pl.nKB; ++b) {
-        int kst = pl.KT * b / pl.nKB, klen = pl.KT * (b + 1) / pl.nKB - kst;
-        int sl = klen * (wave + 1) / WAVES - klen * wave / WAVES;
-        per_tile += sl;
-        if (b < kb) before_kb += sl;
-    }
-    const int gn = min(pl.GRP, n_local - gi * pl.GRP);
-    return gi * pl.GRP * per_tile + gn * before_kb;
-}
-
-__device__ __forceinline__ Seg seg_setup(const GemmPlan &pl, int nt0, int n_local, int wave, int gi, int kb)
-{
-    Seg s;
-    s.gn = min(pl.GRP, n_local - gi * pl.GRP);
-    s.kst = pl.KT * kb / pl.nKB;
-    s.klen = pl.KT * (kb + 1) / pl.nKB - s.kst;
-    s.s0 = s.klen * wave / WAVES;
-    s.slen = s.klen * (wave + 1) / WAVES - s.s0;
-    s.n = s.gn * s.slen;
-    s.step0 = seg_steps_before(pl, n_local, wave, gi, kb);
-    return s;
-}
-
-// byte offset of the wave's tile number `step` (see GemmPlan): slot (step*nwg + g)*WAVES + wave;
-// at most the stage's bytes, below 2^31
-__device__ __forceinline__ int tile_off(int nwg, int wave, int step)
-{
-    return ((step * nwg + (int)blockIdx.x) * WAVES + wave) * 1024;
-}
-
-// first min(D, s.n) tiles of the wave's sequence in segment s
-__device__ __forceinline__ void seg_prefetch(const uint4 *__restrict__ W, int nwg, int wave, const Seg &s, uint4 (&pre)[D])
-{
-    const WRes res = weight_resource(W);
-    const int lane_off = (threadIdx.x & 63) * 16;
-#pragma unroll
-    for (int j = 0; j < D; ++j)
-        if (j < s.n) pre[j] = load_tile16(res, lane_off, tile_off(nwg, wave, s.step0 + j));
-}
-
-struct NextGemm {  // the GEMM stage that follows in the same launch
-    const GemmPlan *pl;  // in device memory; nullptr: nothing to fetch
-    const uint4 *W;
-};
-
-__device__ __forceinline__ bool prefetch_stage(const NextGemm &nx, int nwg, uint4 (&pre)[D])
-{
-    if (!nx.pl) return false;
-    int nt0, n_local;
-    wg_units(*nx.pl, nx.pl->nwg, blockIdx.x, nt0, n_local);
-    if (n_local == 0) return true;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    Seg s = seg_setup(*nx.pl, nt0, n_local, wave, 0, 0);
-    seg_prefetch(nx.W, nx.pl->nwg, wave, s, pre);
-    return true;
-}
+// k-steps of streaming wave w: its k-tiles are w, w + SWAVES, ...
+__device__ __host__ inline int wave_ksteps(int KT, int w) { return KT > w ? (KT - w + SWAVES - 1) / SWAVES : 0; }
 
 // ------------------------------------------------------------------ GEMM stage
-
 
 struct GemmIn {
     const uint16_t *x;  // the input (already scaled by the norm gain) as two bf16 terms, k-tile-major (x_index)
@@ -346,9 +235,9 @@ struct GemmIn {
 };
 
 // GEMM inputs are stored the way the stages consume them: [k-tile][term][row][32] bf16 with
-// `rows` = the rows of this pass, term 0 = hi, 1 = lo.  The k-slice one wave multiplies with
-// (all rows, both terms) is then one contiguous range, which a few 1 KB loads copy into LDS,
-// and the 16 rows x 4 quads of one MFMA operand read one contiguous kilobyte of LDS.
+// `rows` = the rows of this pass, term 0 = hi, 1 = lo.  A range of k-tiles (all rows, both
+// terms) is then one contiguous range, which 1 KB loads copy straight into LDS, and the 16 rows x
+// 4 quads of one MFMA operand read one contiguous kilobyte of LDS.
 __device__ __forceinline__ size_t x_index(int rows, int m, int k, int term)
 {
     return ((size_t)((k >> 5) * 2 + term) * rows + m) * 32 + (k & 31);
@@ -370,44 +259,34 @@ __device__ __forceinline__ void store_split4(uint16_t *x, int rows, int m, int k
     uint32_t h[4], l[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) split_bf16(v[e], h[e], l[e]);
-    store_dev64(x + x_index(rows, m, k, 0), make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16)));
-    store_dev64(x + x_index(rows, m, k, 1), make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16)));
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
+    *reinterpret_cast<EE_GLOBAL u32x2_t *>(as_global_mut(x) + x_index(rows, m, k, 0)) = (u32x2_t){h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+    *reinterpret_cast<EE_GLOBAL u32x2_t *>(as_global_mut(x) + x_index(rows, m, k, 1)) = (u32x2_t){l[0] | (l[1] << 16), l[2] | (l[3] << 16)};
 }
 
-// Wave-private staging of the GEMM input: the wave copies the k-slice it multiplies with,
-// k-tiles [kst + s0, kst + s0 + slen) of every row and of both bf16 terms: one contiguous range
-// in memory, copied straight into LDS at the same offset relative to the K-block's start.  No
-// registers hold the data and no other wave reads this slice, so no workgroup barrier is
-// needed: the wave waits for its own loads (wait_vmem) and goes on.  One load instruction
-// moves 64 x 16 bytes.  DEV = true reads with device scope (the input was written earlier in
-// the same launch by other workgroups).
-#define EE_LDS __attribute__((address_space(3)))
-template <bool DEV>
-__device__ __forceinline__ void stage_x_wave(const GemmIn &in, int rows, int kst, int s0, int slen, char *lds, int lane)
+// Helper waves: copy k-tiles [kt0, kt0 + klen) of the input (all rows, both terms: one
+// contiguous range in memory) straight into LDS at dst.  One load instruction moves 64 x 16
+// bytes; no registers hold the data.  The caller waits (wait_vmem) before it tells the others.
+__device__ __forceinline__ void stage_block(const uint16_t *x, int rows, int kt0, int klen, char *dst, int hwave, int lane)
 {
     const size_t tile_elems = (size_t)2 * rows * 32;          // one k-tile: both terms, all rows
-    const uint16_t *src = in.x + (size_t)(kst + s0) * tile_elems;
-    char *dst = lds + (size_t)s0 * tile_elems * 2;
-    const int nchunk = slen * 2 * rows * 4;                     // 16-byte chunks of the slice
-    for (int c0 = 0; c0 < nchunk; c0 += 64)
+    const uint16_t *src = x + (size_t)kt0 * tile_elems;
+    const int nchunk = klen * 2 * rows * 4;                     // 16-byte chunks of the block
+    for (int c0 = hwave * 64; c0 < nchunk; c0 += HWAVES * 64)
         if (c0 + lane < nchunk)
             __builtin_amdgcn_global_load_lds((const EE_GLOBAL void *)(src + (size_t)(c0 + lane) * 8),
-                                             (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, DEV ? 16 : 0);
+                                             (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, 0);
 }
 
-// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order.  DEV: the partial
-// sums were written earlier in the same launch (device-scope loads); otherwise ordinary loads,
-// which the XCD's L2 serves to all but the first workgroup: every workgroup reads the same
-// few kilobytes, and past the L2 that is thousands of requests for the same lines.
-template <bool DEV>
+// rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order; helper waves only.
+// Ordinary loads, which the XCD's L2 serves to all but the first workgroup: every workgroup
+// reads the same few kilobytes.
 __device__ __forceinline__ void load_rstd(const float *ss, int nwg, int rows_max, int rows, int d, float eps,
-                                          float *rstd_lds)
+                                          float *rstd_lds, int hwave, int lane)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int m = wave; m < rows; m += WAVES) {
+    for (int m = hwave; m < rows; m += HWAVES) {
         float s = 0.f;
-        for (int g = lane; g < nwg; g += 64)
-            s += DEV ? load_dev32(ss + (size_t)g * rows_max + m) : *as_global(ss + (size_t)g * rows_max + m);
+        for (int g = lane; g < nwg; g += 64) s += *as_global(ss + (size_t)g * rows_max + m);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
         if (lane == 0) rstd_lds[m] = 1.0f / sqrtf(s / (float)d + eps);
@@ -419,21 +298,21 @@ __device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
     return v > bv || (v == bv && i < bi);
 }
 
-// Epilogue of one group: sum the waves' partial tiles, apply the stage's element-wise tail.
 struct GemmEpi {           // what the O / DN epilogue produces besides h
     const float *gain_xn;  // gain of the next GEMM input (xn), or nullptr
     const float *gain_xh;  // gain of the LM-head input (xh), or nullptr
     float *ss_out;         // [nwg][rows_max] partial sums of h^2
 };
 
-__device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const GemmPlan &pl, int nt_first,
+// Epilogue of one chunk of gn n-tiles starting at n-tile nt_first: sum the streaming waves'
+// partial tiles (fixed order), apply the stage's element-wise tail.  All threads.
+__device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const StageLds &ly, int nt_first,
                                               int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds)
 {
     const ModelDev &md = a.mdv;
-    const float *slots = reinterpret_cast<const float *>(lds + pl.lds_slots_off);
+    const float *slots = reinterpret_cast<const float *>(lds);
     const int tid = opaque(threadIdx.x);
-    const size_t wstride = (size_t)pl.GRP * rows * 16;  // floats per wave in the slot buffer
-    const int n_part = pl.shared_acc ? 1 : WAVES;        // partial tiles to sum per output tile
+    const size_t wstride = (size_t)ly.chunk * rows * 16;  // floats per wave in the slot buffer
     if (kind == G_GU) {
         const int items = (gn >> 1) * rows * 4;
         for (int idx = tid; idx < items; idx += WG_THREADS) {
@@ -443,7 +322,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const float *su = sg + (size_t)rows * 16;
             float4 G = make_float4(0.f, 0.f, 0.f, 0.f), U = G;
 #pragma unroll 2
-            for (int w = 0; w < n_part; ++w) {
+            for (int w = 0; w < SWAVES; ++w) {
                 float4 x = *reinterpret_cast<const float4 *>(sg + w * wstride);
                 float4 y = *reinterpret_cast<const float4 *>(su + w * wstride);
                 G.x += x.x; G.y += x.y; G.z += x.z; G.w += x.w;
@@ -459,7 +338,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         }
         return;
     }
-    float *zbuf = reinterpret_cast<float *>(lds + pl.lds_zbuf_off);  // head: [rows][GRP*16] logits of this group; O/DN: squares
+    float *zbuf = reinterpret_cast<float *>(lds + ly.zbuf_off);  // head: [rows][chunk*16] logits of this chunk; O/DN: squares
     const int items = gn * rows * 4;
     for (int idx = tid; idx < items; idx += WG_THREADS) {
         int ntg = idx / (rows * 4), rem = idx - ntg * rows * 4;
@@ -467,7 +346,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
-        for (int w = 0; w < n_part; ++w) {
+        for (int w = 0; w < SWAVES; ++w) {
             float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
@@ -475,19 +354,19 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         if (kind == G_O || kind == G_DN) {
             float sq = 0.f;
             if (n < md.d) {
-                float4 *hp = reinterpret_cast<float4 *>(a.sc.h + (size_t)m * md.d + n);
-                float4 hv = *hp;
-                float v[4] = {hv.x + S.x, hv.y + S.y, hv.z + S.z, hv.w + S.w};
-                *hp = make_float4(v[0], v[1], v[2], v[3]);
+                EE_GLOBAL f32x4_t *hp = reinterpret_cast<EE_GLOBAL f32x4_t *>(as_global_mut(a.sc.h) + (size_t)m * md.d + n);
+                const f32x4_t hv = *hp;
+                float v[4] = {hv[0] + S.x, hv[1] + S.y, hv[2] + S.z, hv[3] + S.w};
+                *hp = (f32x4_t){v[0], v[1], v[2], v[3]};
                 sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
                 if (ep.gain_xn) {
-                    float4 g = *reinterpret_cast<const float4 *>(ep.gain_xn + n);
-                    float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
+                    const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xn + n));
+                    float x[4] = {v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]};
                     store_split4(a.sc.xn, rows, m, n, x);
                 }
                 if (ep.gain_xh) {
-                    float4 g = *reinterpret_cast<const float4 *>(ep.gain_xh + n);
-                    float x[4] = {v[0] * g.x, v[1] * g.y, v[2] * g.z, v[3] * g.w};
+                    const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xh + n));
+                    float x[4] = {v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]};
                     store_split4(a.sc.xh, rows, m, n, x);
                 }
             }
@@ -498,19 +377,19 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             float v[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
             const int sect = n / d, c = n - sect * d;
             const int head = c / hd, e = c - head * hd;
+            const int ses = a.mode == 1 ? 0 : m / a.M;
             if (sect < 2) {
-                // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2
-                float2 c0 = mi.rope[m * (hd >> 1) + (e >> 1)], c1 = mi.rope[m * (hd >> 1) + (e >> 1) + 1];
-                float y0 = v[0] * c0.x - v[1] * c0.y, y1 = v[1] * c0.x + v[0] * c0.y;
-                float y2 = v[2] * c1.x - v[3] * c1.y, y3 = v[3] * c1.x + v[2] * c1.y;
+                // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2; (cos, sin) of the row's position
+                const f32x4_t cs = *as_global(reinterpret_cast<const f32x4_t *>(EE_SESS(a, ses, rope) + (size_t)mi.pos[m] * (hd >> 1) + (e >> 1)));
+                float y0 = v[0] * cs[0] - v[1] * cs[1], y1 = v[1] * cs[0] + v[0] * cs[1];
+                float y2 = v[2] * cs[2] - v[3] * cs[3], y3 = v[3] * cs[2] + v[2] * cs[3];
                 v[0] = y0; v[1] = y1; v[2] = y2; v[3] = y3;
             }
             if (sect == 0) {
-                *reinterpret_cast<float4 *>(a.sc.q + (size_t)m * d + c) = make_float4(v[0], v[1], v[2], v[3]);
+                *reinterpret_cast<EE_GLOBAL f32x4_t *>(as_global_mut(a.sc.q) + (size_t)m * d + c) = (f32x4_t){v[0], v[1], v[2], v[3]};
             } else {
                 // cached value = hi + lo, two bf16 terms.  K: [position][term][hd]; V transposed
                 // inside the page: [term][hd][position] (see the attention stage)
-                const int ses = a.mode == 1 ? 0 : m / a.M;
                 uint32_t vh[4], vl[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) split_bf16(v[t], vh[t], vl[t]);
@@ -533,14 +412,14 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         } else {  // G_HEAD
             const float rs = mi.rstd[m];
             float z[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
-            float *zr = zbuf + (size_t)m * pl.GRP * 16 + ntg * 16 + qd * 4;
+            float *zr = zbuf + (size_t)m * ly.chunk * 16 + ntg * 16 + qd * 4;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 if (n + e >= md.V) z[e] = -INFINITY;
                 zr[e] = z[e];
             }
             if (a.keep_logits) {
-                float *keep = a.sc.logits + ((size_t)a.head_idx * md.rows_max + m) * md.V;
+                EE_GLOBAL float *keep = as_global_mut(a.sc.logits) + ((size_t)a.head_idx * md.rows_max + m) * md.V;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if (n + e < md.V) keep[n + e] = z[e];
@@ -548,8 +427,8 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         }
     }
     if (kind == G_O || kind == G_DN) {
-        __syncthreads();
-        if (tid < rows) {  // this group's sum of squares per row, fixed order
+        lds_barrier();
+        if (tid < rows) {  // this chunk's sum of squares per row, fixed order
             float t = 0.f;
             for (int ntg = 0; ntg < gn; ++ntg)
                 for (int qd = 0; qd < 4; ++qd) t += zbuf[(ntg * rows + tid) * 4 + qd];
@@ -557,13 +436,13 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         }
     }
     if (kind == G_HEAD) {
-        __syncthreads();
+        lds_barrier();
         const int lane = tid & 63, wave = tid >> 6;
         for (int m = wave; m < rows; m += WAVES) {
             float bv = -INFINITY;
             int bi = 0x7FFFFFFF;
             for (int c = lane; c < gn * 16; c += 64) {
-                float z = zbuf[(size_t)m * pl.GRP * 16 + c];
+                float z = zbuf[(size_t)m * ly.chunk * 16 + c];
                 int n = nt_first * 16 + c;
                 if (cand_better(z, n, bv, bi)) {
                     bv = z;
@@ -579,14 +458,14 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                     bi = oi;
                 }
             }
-            // sum of exp(z - bv) over the group's columns (masked columns hold -inf and add 0):
+            // sum of exp(z - bv) over the chunk's columns (masked columns hold -inf and add 0):
             // the softmax denominator for the confidence score (paper Eq. 4), kept relative to the
             // running maximum like the argmax candidate
             float se = 0.f;
-            for (int c = lane; c < gn * 16; c += 64) se += __expf(zbuf[(size_t)m * pl.GRP * 16 + c] - bv);
+            for (int c = lane; c < gn * 16; c += 64) se += __expf(zbuf[(size_t)m * ly.chunk * 16 + c] - bv);
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) se += __shfl_xor(se, off, 64);
-            if (lane == 0 && bv > -INFINITY) {  // (a group of masked columns only contributes nothing)
+            if (lane == 0 && bv > -INFINITY) {  // (a chunk of masked columns only contributes nothing)
                 const float ov = mi.bestv[m];
                 if (cand_better(bv, bi, ov, mi.besti[m])) {
                     mi.sume[m] = mi.sume[m] * __expf(ov - bv) + se;  // exp(-inf) = 0 the first time
@@ -600,202 +479,194 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     }
 }
 
-template <int MT>
-__device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan pl, const uint4 *__restrict__ W,
-                             const GemmIn &in, const GemmEpi &ep, uint4 (&buf)[D], bool &have_pre, const NextGemm &next,
-                             char *lds, int tsi)
+// k-steps whose tiles a streaming wave keeps in flight, by n-tiles of the group: about 8 to 14
+// tiles (1 KB each), fewer where the accumulators of three row tiles need the registers
+template <int MT, int NL>
+constexpr int ring_steps()
 {
+    constexpr int r = (8 + NL - 1) / NL;
+    return (MT == 3 && NL >= 5) ? 1 : r;
+}
+
+// One group of NL n-tiles (this workgroup's n-tiles nt_first .. nt_first + NL - 1) over all of K.
+//
+// Streaming wave w walks its k-steps s = 0 .. (k-tile w + SWAVES*s); per k-step it multiplies
+// the NL weight tiles of the step with the step's input rows (two bf16 terms, MT row tiles)
+// into NL x MT accumulators that stay in registers.  R k-steps of tiles are in flight: a step's
+// registers are refilled with the step R further on as soon as the step has been used.  Every load
+// is unconditional (the look-ahead is clamped to the group's last tile), nothing is pending
+// when the loop is entered and no other memory operation of the wave goes through the vector
+// path meanwhile: the compiler can then count the loads in flight and each use waits for
+// exactly its own tile (otherwise it waits for all of them, which halves what a wave pulls).
+//
+// The input reaches LDS in blocks of ly.kbt k-tiles, copied by the helper waves: block b+1
+// is copied into the other buffer while block b is read; one barrier per block boundary, the
+// same for all twelve waves.
+//
+// Afterwards the accumulators go through LDS, `ly.chunk` n-tiles at a time, for the
+// cross-wave sum and the stage's epilogue (all waves).
+template <int MT, int NL>
+__device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const StageLds &ly,
+                                           const uint4 *__restrict__ W, const GemmIn &in, const GemmEpi &ep, const Misc &mi,
+                                           char *lds, int nt_first, int seq0, bool first_group)
+{
+    constexpr int R = ring_steps<MT, NL>();
     const ModelDev &md = a.mdv;
     const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rows = a.rows;
-    const Misc mi = misc_views(md, pl, lds);
-    int nt0, n_local;
-    wg_units(pl, pl.nwg, blockIdx.x, nt0, n_local);
-
-    if (kind == G_HEAD) {
-        if (tid < rows) {
-            mi.bestv[tid] = -INFINITY;
-            mi.besti[tid] = 0x7FFFFFFF;
-            mi.sume[tid] = 0.f;
-        }
-    }
-    if (n_local == 0) {  // nothing to stream here (uniform over the workgroup)
-        have_pre = prefetch_stage(next, a.nwg, buf);
-        if (kind == G_HEAD && tid < rows) {
-            store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(-INFINITY), 0x7FFFFFFFu));
-            store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
-        }
-        if ((kind == G_O || kind == G_DN) && tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, 0.f);
-        return;
-    }
-    if ((kind == G_O || kind == G_DN) && tid < rows) mi.rowss[tid] = 0.f;
-    if (pl.shared_acc) {  // the accumulators start at zero (one workgroup barrier before the first add)
-        float *acc0 = reinterpret_cast<float *>(lds + pl.lds_slots_off);
-        for (int i = tid; i < n_local * rows * 16; i += WG_THREADS) acc0[i] = 0.f;
-        __syncthreads();
-    }
-    trace_stamp(a, tsi, 0);
-    // start the weight stream before anything else (unless the previous stage already did)
-    if (!have_pre) seg_prefetch(W, pl.nwg, wave, seg_setup(pl, nt0, n_local, wave, 0, 0), buf);
-    const uint16_t *xs = reinterpret_cast<const uint16_t *>(lds);  // the K-block's input, [k-tile][term][row][32]
-    float *slots = reinterpret_cast<float *>(lds + pl.lds_slots_off);
-    int brow[MT];
+    const int S_max = wave_ksteps(pl.KT, 0);      // k-steps of the busiest wave: everybody runs the loop this far
+    const int spb = ly.kbt / SWAVES;              // k-steps per input block
+    f32x4_t acc[NL][MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * 32;
-    const int bk = (lane >> 4) * 8;
-    const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
+    for (int nt = 0; nt < NL; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
 
-    for (int gi = 0; gi < n_groups; ++gi) {
-        const int gn = min(pl.GRP, n_local - gi * pl.GRP);
-        for (int kb = 0; kb < pl.nKB; ++kb) {
-            const Seg s = seg_setup(pl, nt0, n_local, wave, gi, kb);
-            const bool restage = pl.nKB > 1 || gi == 0;
-            if (restage) {
-                // A wave overwrites only its own slice of the previous block when every block has
-                // the same length (the slices then coincide); otherwise slices shift between
-                // blocks and the other waves must be done with theirs first.
-                if ((gi > 0 || kb > 0) && pl.KT % pl.nKB != 0) __syncthreads();
-                if (a.ph_hi - a.ph_lo > 1)
-                    stage_x_wave<true>(in, rows, s.kst, s.s0, s.slen, lds, lane);
-                else  // the input comes from an earlier launch: ordinary loads, served by the XCD's L2
-                    stage_x_wave<false>(in, rows, s.kst, s.s0, s.slen, lds, lane);
-                if (in.ss && gi == 0 && kb == 0) {
-                    if (a.ph_hi - a.ph_lo > 1)
-                        load_rstd<true>(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
-                    else
-                        load_rstd<false>(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd);
+    if (wave < SWAVES) {
+        // ---------------- streaming wave
+        const int S_w = wave_ksteps(pl.KT, wave);
+        const WRes wres = weight_resource(W);
+        const int lane_off = lane * 16;
+        const int wstep = pl.nwg * SWAVES * 1024;  // bytes from one tile of the wave's sequence to the next
+        const int woff = ((seq0 * pl.nwg + (int)blockIdx.x) * SWAVES + wave) * 1024;  // the group's first tile
+        const int last = max(S_w * NL - 1, 0);     // the group's last tile of this wave (look-ahead is clamped to it)
+        uint4 buf[R][NL];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NL; ++nt) buf[r][nt] = load_tile16(wres, lane_off, woff + min(r * NL + nt, last) * wstep);
+        int brow[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * 64 + (lane >> 4) * 16;  // bytes inside a k-tile's hi rows
+        const int tile_bytes = rows * 128;         // one k-tile of the input: both terms, all rows
+        int blk_end = spb;                         // first k-step of the next input block
+        int xoff = wave * tile_bytes;              // LDS byte offset of this wave's k-tile of step s, relative to s * SWAVES * tile_bytes
+        wait_vmem();                               // nothing pending at loop entry (see above)
+        lds_barrier();                             // input block 0 is in LDS
+        for (int s0 = 0; s0 < S_max; s0 += R) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int s = s0 + r;
+                if (s == blk_end && s < S_max) {   // next input block: the helpers have copied it into the other buffer
+                    lds_barrier();
+                    const int b = s / spb;
+                    xoff = wave * tile_bytes + (b & 1) * ly.xbuf_bytes - b * spb * SWAVES * tile_bytes;
+                    blk_end += spb;
                 }
-                if (kind == G_QKV && gi == 0 && kb == 0) {
-                    // per-row position, KV record and RoPE factors for the epilogue (read after the
-                    // workgroup barrier that precedes it)
-                    if (tid < rows) {
-                        const int m = tid;
-                        const int pos = row_pos(a, m);
-                        const int ses = a.mode == 1 ? 0 : m / a.M;
-                        const int cbase = EE_SESS(a, ses, contig_base);
-                        const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
-                        mi.pos[m] = pos;
-                        mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
+                // A wave whose k-steps have run out keeps loading (its last tile again) and multiplies
+                // with zeros: the stream loop then has no load under a condition.
+                const bool live = s < S_w;
+                const char *xs = lds + xoff + s * (SWAVES * tile_bytes);
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {  // row tile by row tile: one pair of input operands live at a time
+                    uint4 xh = make_uint4(0u, 0u, 0u, 0u), xl = xh;
+                    if (live) {
+                        xh = *reinterpret_cast<const uint4 *>(xs + brow[mt]);
+                        xl = *reinterpret_cast<const uint4 *>(xs + brow[mt] + rows * 64);
                     }
-                    const int half = md.hd >> 1;
-                    for (int i = tid; i < rows * half; i += WG_THREADS) {
-                        int m = i / half, j = i - m * half;
-                        const int ses = a.mode == 1 ? 0 : m / a.M;
-                        const unsigned long long cs = *as_global(reinterpret_cast<const unsigned long long *>(EE_SESS(a, ses, rope) + (size_t)row_pos(a, m) * half + j));
-                        mi.rope[i] = make_float2(__uint_as_float((unsigned)cs), __uint_as_float((unsigned)(cs >> 32)));
+                    const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, xh), bl = __builtin_bit_cast(bf16x8_t, xl);
+#pragma unroll
+                    for (int nt = 0; nt < NL; ++nt) {
+                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, buf[r][nt]);
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bh, acc[nt][mt], 0, 0, 0);
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bl, acc[nt][mt], 0, 0, 0);
+                        // the tile's registers are free after its last use: refill them with the step R further on
+                        if (mt == MT - 1) buf[r][nt] = load_tile16(wres, lane_off, woff + min((s + R) * NL + nt, last) * wstep);
                     }
                 }
-                wait_vmem();  // this wave's slice is in LDS (and its first weight tiles have arrived)
-                trace_stamp(a, tsi, 1 + min(kb, 1));
             }
-
-            // ---- this wave's tiles of the segment
-            f32x4_t acc[MT];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-            if (s.slen == 0 && kb == 0 && !pl.shared_acc) {  // no tiles in this block: contribute zeros
-                for (int ntg = 0; ntg < gn; ++ntg)
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        int m = mt * 16 + (lane & 15);
-                        if (m < rows)
-                            *reinterpret_cast<float4 *>(slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4) =
-                                make_float4(0.f, 0.f, 0.f, 0.f);
-                    }
+        }
+    } else {
+        // ---------------- helper wave: input blocks, row factors, per-row cache addresses
+        const int hwave = wave - SWAVES;
+        stage_block(in.x, rows, 0, min(ly.kbt, pl.KT), lds, hwave, lane);
+        if (first_group) {
+            if (in.ss) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd, hwave, lane);
+            const int ht = tid - SWAVES * 64;
+            if (kind == G_QKV && ht < rows) {
+                const int m = ht;
+                const int pos = row_pos(a, m);
+                const int ses = a.mode == 1 ? 0 : m / a.M;
+                const int cbase = EE_SESS(a, ses, contig_base);
+                const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
+                mi.pos[m] = pos;
+                mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
             }
-            int ntg = 0, kk = 0;  // compute cursor
-            const WRes wres = weight_resource(W);
-            const int lane_off = lane * 16;
-            const int woff = tile_off(pl.nwg, wave, s.step0);
-            const int wstep = pl.nwg * WAVES * 1024;  // bytes from one tile of the wave's sequence to the next
-            const int woff_last = woff + (s.n - 1) * wstep;
-            // one tile: two MFMAs (both bf16 terms of the input); at the end of an n-tile's run
-            // the partial tile goes to the wave's slot in LDS
-            auto tile_step = [&](const uint4 &av) __attribute__((always_inline)) {
-                bf16x8_t A = __builtin_bit_cast(bf16x8_t, av);
-                const int xo = (s.s0 + kk) * 2 * rows * 32 + bk;  // this k-tile's hi rows; the lo rows follow them
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    uint4 bh = *reinterpret_cast<const uint4 *>(xs + brow[mt] + xo);
-                    uint4 bl = *reinterpret_cast<const uint4 *>(xs + brow[mt] + xo + rows * 32);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bh), acc[mt], 0, 0, 0);
-                    acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, __builtin_bit_cast(bf16x8_t, bl), acc[mt], 0, 0, 0);
-                }
-                if (++kk == s.slen) {
-                    // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        int m = mt * 16 + (lane & 15);
-                        if (m < rows) {
-                            if (pl.shared_acc) {
-                                EE_LDS float *dst = (EE_LDS float *)(slots + ((size_t)ntg * rows + m) * 16 + (lane >> 4) * 4);
-#pragma unroll
-                                for (int r = 0; r < 4; ++r)
-                                    __hip_atomic_fetch_add(dst + r, acc[mt][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                            } else {
-                                float4 *dst = reinterpret_cast<float4 *>(
-                                    slots + (((size_t)wave * pl.GRP + ntg) * rows + m) * 16 + (lane >> 4) * 4);
-                                float4 v = make_float4(acc[mt][0], acc[mt][1], acc[mt][2], acc[mt][3]);
-                                if (kb > 0) {
-                                    float4 o = *dst;
-                                    v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
-                                }
-                                *dst = v;
-                            }
-                        }
-                        acc[mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-                    }
-                    kk = 0;
-                    ++ntg;
-                }
-            };
-            // Full blocks of D tiles: every load is unconditional (the look-ahead is clamped to
-            // the segment's last tile), so the compiler can count the loads in flight and each
-            // use waits for exactly its own tile.  Loads under a condition make it wait for all
-            // of them, which halves what one wave can pull.
-            // Nothing may be in flight when the loop is entered, else (e.g. with the stores
-            // of an earlier epilogue still counted) the compiler falls back to waiting for all.
+        }
+        wait_vmem();
+        lds_barrier();                             // block 0 ready
+        for (int b = 1; b < ly.nkb; ++b) {
+            const int kt0 = b * ly.kbt;
+            stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + (b & 1) * ly.xbuf_bytes, hwave, lane);
             wait_vmem();
-            int i = 0;
-            for (; i + D <= s.n; i += D) {
+            lds_barrier();                         // block b ready, block b-1 no longer read
+        }
+    }
+    // ---- cross-wave sum and epilogue, ly.chunk n-tiles at a time (the input buffers are free now)
+    lds_barrier();                                 // every streaming wave is done with the input
+    float *slots = reinterpret_cast<float *>(lds);
+    for (int c0 = 0; c0 < NL; c0 += ly.chunk) {
+        const int gn = min(ly.chunk, NL - c0);
+        if (wave < SWAVES) {
+            // D layout: lane holds rows (lane>>4)*4 .. +3 of N, column (lane&15) of M
 #pragma unroll
-                for (int j = 0; j < D; ++j) {
-                    // use the tile, then refill its registers: issuing the load first would need a
-                    // second set of registers and a copy (with a wait) at the end of the block
-                    tile_step(buf[j]);
-                    buf[j] = load_tile16(wres, lane_off, min(woff + (i + j + D) * wstep, woff_last));
+            for (int nt = 0; nt < NL; ++nt)
+                if (nt >= c0 && nt < c0 + gn) {
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const int m = mt * 16 + (lane & 15);
+                        if (m < rows)
+                            *reinterpret_cast<float4 *>(slots + (((size_t)wave * ly.chunk + (nt - c0)) * rows + m) * 16 + (lane >> 4) * 4) =
+                                make_float4(acc[nt][mt][0], acc[nt][mt][1], acc[nt][mt][2], acc[nt][mt][3]);
+                    }
                 }
-            }
-#pragma unroll
-            for (int j = 0; j < D; ++j)
-                if (i + j < s.n) tile_step(buf[j]);
-            // ---- fetch ahead: next segment of this stage, or the first tiles of the next GEMM stage
-            const bool last_seg = (gi == n_groups - 1) && (kb == pl.nKB - 1);
-            if (!last_seg) {
-                const int ngi = kb + 1 < pl.nKB ? gi : gi + 1, nkb = kb + 1 < pl.nKB ? kb + 1 : 0;
-                const Seg ns = seg_setup(pl, nt0, n_local, wave, ngi, nkb);
-                seg_prefetch(W, pl.nwg, wave, ns, buf);
-            } else {
-                have_pre = prefetch_stage(next, a.nwg, buf);
-            }
         }
-        trace_stamp(a, tsi, 3);
-        __syncthreads();
-        trace_stamp(a, tsi, 4);
-        gemm_epilogue(a, kind, layer, pl, nt0 + gi * pl.GRP, gn, rows, ep, mi, lds);
-        trace_stamp(a, tsi, 5);
-        if (gi + 1 < n_groups) __syncthreads();
+        lds_barrier();
+        gemm_epilogue(a, kind, layer, ly, nt_first + c0, gn, rows, ep, mi, lds);
+        lds_barrier();
     }
-    if (kind == G_O || kind == G_DN) {
-        __syncthreads();
-        if (tid < rows) store_dev32(ep.ss_out + (size_t)blockIdx.x * md.rows_max + tid, mi.rowss[tid]);
+}
+
+// One GEMM stage of this workgroup: its n-tiles in groups of up to GROUP_TILES.
+template <int MT>
+__device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const StageLds &ly,
+                             const uint4 *__restrict__ W, const GemmIn &in, const GemmEpi &ep, char *lds)
+{
+    const ModelDev &md = a.mdv;
+    const int tid = opaque(threadIdx.x);
+    const int rows = a.rows;
+    const Misc mi = misc_views(ly, lds);
+    int nt0, n_local;
+    wg_units(pl, blockIdx.x, nt0, n_local);
+
+    if (tid < rows) {
+        mi.bestv[tid] = -INFINITY;
+        mi.besti[tid] = 0x7FFFFFFF;
+        mi.sume[tid] = 0.f;
+        mi.rowss[tid] = 0.f;
     }
-    if (kind == G_HEAD) {
-        __syncthreads();
-        if (tid < rows) {  // device-scope stores: the accept step may run in another workgroup of this launch
-            store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(mi.bestv[tid]), (unsigned)mi.besti[tid]));
-            store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, mi.sume[tid]);
+    if (n_local > 0) {
+        const int S0 = wave_ksteps(pl.KT, 0);
+        int seq = 0;  // tiles of a wave's sequence before the group (waves with fewer k-steps leave their slots unused)
+        for (int g0 = 0; g0 < n_local; g0 += GROUP_TILES) {
+            const int nl = min(GROUP_TILES, n_local - g0);
+            const bool first = g0 == 0;
+#define EE_GROUP(NLV) \
+    case NLV: gemm_group<MT, NLV>(a, kind, layer, pl, ly, W, in, ep, mi, lds, nt0 + g0, seq, first); break;
+            switch (nl) {
+                EE_GROUP(1) EE_GROUP(2) EE_GROUP(3) EE_GROUP(4) EE_GROUP(5) EE_GROUP(6) EE_GROUP(7) EE_GROUP(8)
+            }
+#undef EE_GROUP
+            seq += S0 * nl;
         }
+    } else {
+        lds_barrier();
+    }
+    // what the workgroup hands to the following launch
+    if ((kind == G_O || kind == G_DN) && tid < rows) as_global_mut(ep.ss_out)[(size_t)blockIdx.x * md.rows_max + tid] = mi.rowss[tid];
+    if (kind == G_HEAD && tid < rows) {  // device-scope stores: the accept step may run in another workgroup of this launch
+        store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(mi.bestv[tid]), (unsigned)mi.besti[tid]));
+        store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, mi.sume[tid]);
     }
 }
 
@@ -803,7 +674,7 @@ __device__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmP
 
 // h = embedding of each row's token (or the supplied embedding row); workgroup g owns the
 // columns [g*cw, (g+1)*cw) and also emits the first layer's GEMM input and its share of h^2
-__device__ void embed_stage(const PassArgs &a, char *lds)
+__device__ __forceinline__ void embed_stage(const PassArgs &a, char *lds)
 {
     const ModelDev &md = a.mdv;
     const int d = md.d, rows = a.rows, tid = threadIdx.x;
@@ -829,7 +700,7 @@ __device__ void embed_stage(const PassArgs &a, char *lds)
     if (tid < rows) {
         float t = 0.f;
         for (int j = 0; j < nq; ++j) t += sq[tid * nq + j];
-        store_dev32(a.sc.ss_a + (size_t)blockIdx.x * md.rows_max + tid, t);
+        as_global_mut(a.sc.ss_a)[(size_t)blockIdx.x * md.rows_max + tid] = t;
     }
 }
 
@@ -870,12 +741,12 @@ __device__ __forceinline__ bf16x8_t pack_bf16x8(const uint32_t *h)
 // and the item that arrives last merges the unit's partials in split order (the result does
 // not depend on arrival order) and clears the counter for the next launch.  Nothing waits.
 template <int HD>
-__device__ void att_stage(const PassArgs &a, int layer, char *lds)
+__device__ __forceinline__ void att_stage(const PassArgs &a, int layer, char *lds)
 {
     constexpr int KT = HD / 32;  // 32-value steps of a score
     constexpr int NT = HD / 16;  // 16-column tiles of the output
     constexpr int REC = HD + 2;
-    const int H = a.H, d = a.d, Kpad_d = a.Kpad_d, M = a.M;  // copies in the launch arguments: no load before the first address
+    const int H = a.H, d = a.d, M = a.M;  // copies in the launch arguments: no load before the first address
     const int n_chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     const int n_splits = a.att_splits;
     const int n_items = a.n_sess * H * n_chunks * n_splits;
@@ -884,8 +755,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
     float *wbuf = reinterpret_cast<float *>(lds);  // [WAVES][ATT_ROWS][REC]
     int *lastf = reinterpret_cast<int *>(wbuf + (size_t)WAVES * ATT_ROWS * REC);
     const size_t rec_page = (size_t)KV_PAGE * 2 * HD;  // elements of one (page, head) record
-
-    trace_stamp(a, 0, 0);
     for (int item = blockIdx.x; item < n_items; item += a.nwg) {
         int unit = item / n_splits, sp = item - unit * n_splits;
         int s = unit / (H * n_chunks), rem = unit - s * (H * n_chunks);
@@ -972,7 +841,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 for (int r = 0; r < 4; ++r) S[t][r] = pos0 + r <= last_pos ? acc[r] * a.att_scale : ATT_NEG;
             }
         }
-        if (a.sc.trace) trace_stamp(a, 0, 1);
         float mx = ATT_NEG;
 #pragma unroll
         for (int t = 0; t < ATT_TILES; ++t)
@@ -1029,7 +897,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             w[HD + 1] = lsum;
         }
         __syncthreads();
-        trace_stamp(a, 0, 2);
         // merge the waves, fixed order
         if (n_splits == 1) {
             for (int t = tid; t < nr * HD; t += WG_THREADS) {
@@ -1066,7 +933,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 }
                 store_dev32(out + (size_t)i * REC + e, r);
             }
-            trace_stamp(a, 0, 3);
             wait_vmem();      // this item's partials are visible device-wide ...
             __syncthreads();  // ... for every wave, before it is counted
             if (tid == 0) {
@@ -1074,7 +940,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
                 *lastf = before == n_splits - 1 ? 1 : 0;
             }
             __syncthreads();
-            trace_stamp(a, 0, 4);
             if (*lastf) {
                 const float *base = a.sc.att_part + (size_t)unit * n_splits * ATT_ROWS * REC;
                 const size_t sp_stride = (size_t)ATT_ROWS * REC;
@@ -1111,7 +976,6 @@ __device__ void att_stage(const PassArgs &a, int layer, char *lds)
             }
         }
         __syncthreads();
-        trace_stamp(a, 0, 5);
     }
 }
 
@@ -1125,7 +989,7 @@ __device__ __forceinline__ int2 load_cand(const int2 *p)
 
 // One workgroup: global argmax per row, confidence, accept rule per session, publication.
 // Reads the candidates with device scope: they may have been written earlier in this launch.
-__device__ void accept_stage(const PassArgs &a, char *lds)
+__device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
 {
     const ModelDev &md = a.mdv;
     const int rows = a.rows, M = a.M;
@@ -1174,7 +1038,7 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
         ee_verify_result *res = sd.result;
         const int *t = tok + s * M;
         const float *cf = conf + s * M;
-        int dev_err = __hip_atomic_load(a.sc.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int dev_err = 0;
         if (a.head_kind == HEAD_PREFILL) {
             int last = t[M - 1];
             res->next_token = last;
@@ -1215,9 +1079,8 @@ __device__ void accept_stage(const PassArgs &a, char *lds)
 
 // ------------------------------------------------------------------ kernels of the pass
 //
-// Stage list of a segment: [EMBED] { QKV ATT O GU DN } x layers [HEAD ACCEPT].
-// Consecutive GEMM stages run inside one launch of the chain kernel with a grid barrier
-// between them; attention, embedding and accept are launches of their own.
+// Stage list of a segment: [EMBED] { QKV ATT O GU DN } x layers [HEAD]; one launch per stage.
+// The accept step runs inside the head's launch, in the workgroup that finishes last.
 
 struct StageDesc {
     int type, kind, layer;
@@ -1248,20 +1111,15 @@ __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
         return sd;
     }
     idx -= per_layer * nl;
-    if (a.head_kind != HEAD_NONE) {
-        if (idx == 0) {
-            sd.type = ST_GEMM;
-            sd.kind = G_HEAD;
-        } else if (idx == 1) {
-            sd.type = ST_ACCEPT;
-        }
+    if (a.head_kind != HEAD_NONE && idx == 0) {
+        sd.type = ST_GEMM;
+        sd.kind = G_HEAD;
     }
     return sd;
 }
 
 __device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
 {
-    const ModelDev &md = a.mdv;
     switch (kind) {
     case G_QKV: return GemmIn{a.sc.xn, a.sc.ss_a};
     case G_O: return GemmIn{a.sc.attn, nullptr};
@@ -1286,52 +1144,18 @@ __device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int lay
     return ep;
 }
 
-// GEMM stages [ph_lo, ph_hi) of the stage list (all of them must be GEMM stages).
-// MT = 16-row tiles of the pass (rows <= 16 * MT).
+// The GEMM stage a.stage of the stage list.  MT = 16-row tiles of the pass (rows <= 16 * MT).
 template <int MT>
-__global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a_by_value)
+__global__ void __launch_bounds__(WG_THREADS) ee_gemm_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
     const PassArgs &a = warmed_arguments();
-    // The tables indexed by the stage kind are read from the descriptor in device memory; the
-    // first stage's entries (the only ones of a one-stage launch) come with the launch
-    // arguments, so that nothing has to be loaded before the first weight address is known.
-    const ModelDev *mdp = a.md;
-    unsigned nbar = 0;
-    if (a.mode == 2) {  // measurement aid: layer_end grid barriers and nothing else
-        for (int i = 0; i < a.layer_end; ++i)
-            grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
-        return;
-    }
-    trace_stamp_wg(a, 0);
-    uint4 buf[D];           // weight tiles in flight; carried from one stage into the next
-    bool have_pre = false;  // buf holds the first tiles of the coming stage
-    for (int ph = a.ph_lo; ph < a.ph_hi; ++ph) {
-        if (ph > a.ph_lo) {
-            wait_vmem();
-            trace_stamp(a, ph - a.ph_lo - 1, 7);
-            grid_barrier(a.sc.bar_flags, a.nwg, a.epoch_base + (++nbar), a.sc.err, a.spin_limit);
-        }
-        const StageDesc st = stage_decode(a, ph);
-        NextGemm nx = {nullptr, nullptr};
-        if (ph + 1 < a.ph_hi) {
-            const StageDesc sn = stage_decode(a, ph + 1);
-            nx.pl = &mdp->plan[sn.kind];
-            nx.W = mdp->w[sn.kind] + (size_t)sn.layer * mdp->wstride[sn.kind];
-        }
-        const GemmIn in = gemm_input(a, st.kind);
-        const GemmEpi ep = gemm_epi(a, st.kind, st.layer);
-        if (ph == a.ph_lo)
-            gemm_stage_t<MT>(a, st.kind, st.layer, a.plan0, a.W0, in, ep, buf, have_pre, nx, lds, 0);
-        else
-            gemm_stage_t<MT>(a, st.kind, st.layer, mdp->plan[st.kind], mdp->w[st.kind] + (size_t)st.layer * mdp->wstride[st.kind],
-                             in, ep, buf, have_pre, nx, lds, ph - a.ph_lo);
-        trace_stamp(a, ph - a.ph_lo, 6);
-    }
+    const StageDesc st = stage_decode(a, a.stage);
+    gemm_stage_t<MT>(a, st.kind, st.layer, a.plan0, a.lay, a.W0, gemm_input(a, st.kind), gemm_epi(a, st.kind, st.layer), lds);
     if (a.fuse_accept) {
-        // The launch ended with a head stage: the workgroup whose candidates arrive last also
-        // runs the accept step (one launch less per head); the counter is left at zero.
-        int *lastf = reinterpret_cast<int *>(lds + 8192);
+        // A head stage: the workgroup whose candidates arrive last also runs the accept step
+        // (one launch less per head); the counter is left at zero.
+        int *lastf = misc_views(a.lay, lds).lastf;
         wait_vmem();      // this workgroup's candidates are visible device-wide ...
         __syncthreads();  // ... for every wave, before it is counted
         if (threadIdx.x == 0) {
@@ -1342,7 +1166,6 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_chain_kernel(PassArgs a_by
         __syncthreads();
         if (*lastf) accept_stage(a, lds);
     }
-    trace_stamp_wg(a, 1);
 }
 
 template <int HD>
@@ -1350,23 +1173,15 @@ __global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
     const PassArgs &a = warmed_arguments();
-    trace_stamp_wg(a, 0);
-    att_stage<HD>(a, stage_decode(a, a.ph_lo).layer, lds);
-    trace_stamp_wg(a, 1);
+    att_stage<HD>(a, stage_decode(a, a.stage).layer, lds);
 }
 
-// embedding, accept: stage ph_lo
+// embedding
 __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
     const PassArgs &a = warmed_arguments();
-    const StageDesc st = stage_decode(a, a.ph_lo);
-    trace_stamp_wg(a, 0);
-    if (st.type == ST_EMBED)
-        embed_stage(a, lds);
-    else if (st.type == ST_ACCEPT && blockIdx.x == 0)
-        accept_stage(a, lds);
-    trace_stamp_wg(a, 1);
+    if (stage_decode(a, a.stage).type == ST_EMBED) embed_stage(a, lds);
 }
 
 // ------------------------------------------------------------------ load-time kernels
@@ -1390,41 +1205,41 @@ __device__ __forceinline__ int perm_row(int perm, int n, int d, int hd, int F)
 }
 
 // row-major bf16 src[N][K] -> the tiled layout of GemmPlan; block g writes workgroup g's tiles,
-// sub-wave `sub` of the block those of wave w = sub, sub + nsub, ...
-__global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, GemmPlan pl, int nwg,
+// sub-wave `sub` of the block those of streaming wave w = sub, sub + nsub, ...
+__global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__restrict__ dst, GemmPlan pl,
                                     int perm, int d, int hd, int F)
 {
     const int g = blockIdx.x;
     int nt0, n_local;
-    wg_units(pl, nwg, g, nt0, n_local);
+    wg_units(pl, g, nt0, n_local);
     if (n_local == 0) return;
     const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6, nsub = blockDim.x >> 6;
-    const int n_groups = (n_local + pl.GRP - 1) / pl.GRP;
-    for (int w = sub; w < WAVES; w += nsub) {
-        int step = 0;
-        for (int gi = 0; gi < n_groups; ++gi) {
-            for (int kb = 0; kb < pl.nKB; ++kb) {
-                const Seg s = seg_setup(pl, nt0, n_local, w, gi, kb);
-                for (int ntg = 0; ntg < s.gn; ++ntg) {
-                    for (int kk = 0; kk < s.slen; ++kk, ++step) {
-                        int n = (nt0 + gi * pl.GRP + ntg) * 16 + (lane & 15);
-                        int k0 = (s.kst + s.s0 + kk) * 32 + (lane >> 4) * 8;
-                        uint16_t v[8];
-                        int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
+    const int S0 = wave_ksteps(pl.KT, 0);
+    for (int w = sub; w < SWAVES; w += nsub) {
+        const int S_w = wave_ksteps(pl.KT, w);
+        int seq = 0;
+        for (int g0 = 0; g0 < n_local; g0 += GROUP_TILES) {
+            const int nl = min(GROUP_TILES, n_local - g0);
+            for (int s = 0; s < S_w; ++s)
+                for (int nt = 0; nt < nl; ++nt) {
+                    int n = (nt0 + g0 + nt) * 16 + (lane & 15);
+                    int k0 = (w + SWAVES * s) * 32 + (lane >> 4) * 8;
+                    uint16_t v[8];
+                    int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            int k = k0 + e;
-                            v[e] = (row >= 0 && k < pl.K) ? src[(size_t)row * pl.K + k] : (uint16_t)0;
-                        }
-                        uint4 o;
-                        o.x = v[0] | ((uint32_t)v[1] << 16);
-                        o.y = v[2] | ((uint32_t)v[3] << 16);
-                        o.z = v[4] | ((uint32_t)v[5] << 16);
-                        o.w = v[6] | ((uint32_t)v[7] << 16);
-                        dst[((size_t)((size_t)step * nwg + g) * WAVES + w) * 64 + lane] = o;
+                    for (int e = 0; e < 8; ++e) {
+                        int k = k0 + e;
+                        v[e] = (row >= 0 && k < pl.K) ? src[(size_t)row * pl.K + k] : (uint16_t)0;
                     }
+                    uint4 o;
+                    o.x = v[0] | ((uint32_t)v[1] << 16);
+                    o.y = v[2] | ((uint32_t)v[3] << 16);
+                    o.z = v[4] | ((uint32_t)v[5] << 16);
+                    o.w = v[6] | ((uint32_t)v[7] << 16);
+                    const size_t step = (size_t)seq + (size_t)s * nl + nt;
+                    dst[((step * pl.nwg + g) * SWAVES + w) * 64 + lane] = o;
                 }
-            }
+            seq += S0 * nl;
         }
     }
 }

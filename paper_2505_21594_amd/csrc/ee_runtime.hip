@@ -47,9 +47,7 @@ struct ee_model {
     int device;
     int nwg;
     size_t lds_budget;           // dynamic LDS bytes each launch asks for
-    int rows_api;                // max_rows as requested at load (c.max_rows is capped at LAUNCH_ROWS)
-    ModelDev host_md;            // host copy of the device descriptor
-    ModelDev *dev_md;
+    ModelDev host_md;            // the descriptor the launches carry by value
     std::vector<void *> allocs;  // every device allocation of the model
     const float *g_exit[EE_MAX_EXITS];
 };
@@ -82,8 +80,10 @@ struct ee_session {
     SessDev *dev_sessdev;            // [EE_MAX_BATCH] per-pass session descriptors
     SessDev *host_sessdev;           // pinned staging for them
     Scratch sc;
-    unsigned epoch;                  // grid-barrier epoch reached by the launches enqueued so far
-    int trace_n;                     // debug: stamp slots handed out in the current pass
+    int att_items_cap;               // attention work items the partials buffer has room for
+    int att_splits_opt;              // EE_OPT_ATT_SPLITS (0: chosen per pass)
+    bool scatter_pages;              // EE_OPT_SCATTER_PAGES
+    int flight_row0;                 // first row of this session in the pass in flight
     std::vector<hipEvent_t> lt_events;   // EE_TIME_LAUNCHES: event pairs around every launch of the pass
     std::vector<int> lt_codes;           // what each timed launch ran (EE_LAUNCH_* code)
     std::vector<void *> allocs;
@@ -98,30 +98,28 @@ struct ee_session {
 
 // ------------------------------------------------------------------ planning
 
-constexpr int EE_TRACE_MAX = 1 << 14;
 typedef void (*pass_kernel_t)(PassArgs);
 
-static pass_kernel_t chain_kernel(int rows)
+static pass_kernel_t gemm_kernel(int rows)
 {
-    (void)rows;  // one launch never has more than LAUNCH_ROWS = 16 rows
-    return ee_gemm_chain_kernel<1>;
+    return rows <= 16 ? ee_gemm_kernel<1> : (rows <= 32 ? ee_gemm_kernel<2> : ee_gemm_kernel<3>);
 }
 
 static pass_kernel_t att_kernel(int hd) { return hd == 128 ? ee_att_kernel<128> : ee_att_kernel<64>; }
 
 // n-tiles the busiest workgroup owns
-static int plan_max_local(int U, int tpu, int nwg)
+static int plan_max_local(const GemmPlan &p)
 {
     int mx = 0;
-    for (int g = 0; g < nwg; ++g) {
-        int u0, u1;
-        unit_range(U, nwg, g, u0, u1);
-        mx = std::max(mx, (u1 - u0) * tpu);
+    for (int g = 0; g < p.nwg; ++g) {
+        int nt0, n_local;
+        wg_units(p, g, nt0, n_local);
+        mx = std::max(mx, n_local);
     }
     return mx;
 }
 
-static GemmPlan make_plan(int N, int K, int tpu)
+static GemmPlan make_plan(int N, int K, int tpu, int nwg_max)
 {
     GemmPlan p;
     memset(&p, 0, sizeof p);
@@ -132,47 +130,41 @@ static GemmPlan make_plan(int N, int K, int tpu)
     p.KT = (K + 31) / 32;
     p.tpu = tpu;
     p.U = p.NT / tpu;
-    p.GRP = tpu;
-    p.nKB = 1;
+    // the fewest workgroups that do not raise the busiest one's share
+    const int most = (p.U + nwg_max - 1) / nwg_max;
+    p.nwg = std::min(nwg_max, (p.U + most - 1) / most);
+    // every wave's sequence has room for the busiest wave's k-steps of every n-tile
+    p.steps = wave_ksteps(p.KT, 0) * plan_max_local(p);
     return p;
 }
 
-// longest tile sequence of any wave (tile slots per wave in the interleaved layout)
-static int plan_steps(const GemmPlan &p, int nwg)
+// LDS map of one GEMM launch with `rows` rows (see StageLds)
+static bool plan_lds(const GemmPlan &p, int rows, size_t lds_total, StageLds &ly)
 {
-    int mx = 0;
-    for (int g = 0; g < nwg; ++g) {
-        int u0, u1;
-        unit_range(p.U, nwg, g, u0, u1);
-        int n_local = (u1 - u0) * p.tpu;
-        for (int w = 0; w < WAVES; ++w) {
-            int per_tile = 0;
-            for (int b = 0; b < p.nKB; ++b) {
-                int kst = p.KT * b / p.nKB, klen = p.KT * (b + 1) / p.nKB - kst;
-                per_tile += klen * (w + 1) / WAVES - klen * w / WAVES;
-            }
-            mx = std::max(mx, n_local * per_tile);
-        }
+    const size_t misc = (MISC_BYTES + 255) / 256 * 256;
+    if (lds_total < misc + 4096) return false;
+    const size_t avail = (lds_total - misc) / 256 * 256;
+    const size_t tile_bytes = (size_t)rows * 128;           // one k-tile of the input: two terms, all rows
+    const int KT8 = (p.KT + SWAVES - 1) / SWAVES * SWAVES;
+    memset(&ly, 0, sizeof ly);
+    if ((size_t)KT8 * tile_bytes <= avail) {
+        ly.kbt = KT8;
+        ly.nkb = 1;
+    } else {
+        ly.kbt = (int)(avail / 2 / tile_bytes) / SWAVES * SWAVES;
+        if (ly.kbt < SWAVES) return false;
+        ly.nkb = (p.KT + ly.kbt - 1) / ly.kbt;
     }
-    return mx;
-}
-
-static size_t plan_slot_bytes(const GemmPlan &p, int rows_max)
-{
-    return (size_t)(p.shared_acc ? 1 : WAVES) * p.GRP * rows_max * 16 * sizeof(float);
-}
-
-// K-blocks so that one block of x_hat (hi and lo bf16 terms, all rows) fits `budget` bytes
-static bool plan_set_blocks(GemmPlan &p, int rows_max, size_t budget)
-{
-    for (int nkb = 1; nkb <= p.KT; ++nkb) {
-        int klen = (p.KT + nkb - 1) / nkb;
-        if ((size_t)klen * 2 * rows_max * 32 * 2 <= budget) {  // [k-tile][term][row][32] bf16
-            p.nKB = nkb;
-            return true;
-        }
-    }
-    return false;
+    ly.xbuf_bytes = (int)((size_t)ly.kbt * tile_bytes);
+    // cross-wave sum: SWAVES partial tiles plus one logits / squares tile per n-tile of a chunk
+    int chunk = (int)(avail / ((size_t)rows * 64 * (SWAVES + 1)));
+    chunk = std::min(chunk, GROUP_TILES);
+    if (p.tpu == 2) chunk &= ~1;
+    if (chunk < p.tpu) return false;
+    ly.chunk = chunk;
+    ly.zbuf_off = (int)((size_t)SWAVES * chunk * rows * 64);
+    ly.misc_off = (int)avail;
+    return true;
 }
 
 template <typename T>
@@ -208,7 +200,7 @@ static int upload_tiled(const ee_model *m, const GemmPlan &pl, int perm, const u
 {
     for (int i = 0; i < n_src; ++i)
         HIP_TRY(hipMemcpy(tmp + (size_t)i * elems_each, srcs[i], elems_each * 2, hipMemcpyHostToDevice));
-    hipLaunchKernelGGL(tile_weights_kernel, dim3(pl.nwg), dim3(512), 0, 0, tmp, dst, pl, pl.nwg, perm,
+    hipLaunchKernelGGL(tile_weights_kernel, dim3(pl.nwg), dim3(512), 0, 0, tmp, dst, pl, perm,
                        m->cfg.d_model, m->cfg.head_dim, m->cfg.d_ffn);
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipDeviceSynchronize());
@@ -328,12 +320,6 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if (!m) return fail(EE_EDEVICE, "out of host memory");
     m->device = device;
     m->nwg = prop.multiProcessorCount;
-    if (const char *e = getenv("EE_NUM_WORKGROUPS")) {
-        int v = atoi(e);
-        if (v >= 1 && v <= prop.multiProcessorCount) m->nwg = v;
-    }
-    m->rows_api = max_rows;                         // rows one ee_verify_batch call may bring
-    max_rows = std::min(max_rows, LAUNCH_ROWS);     // rows of one launch (a larger batch runs as groups)
     c.max_rows = max_rows;
     c.n_workgroups = m->nwg;
     m->cfg = c;
@@ -355,83 +341,45 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         return fail(EE_EFORMAT, "ee_model_load: d_ffn must be a multiple of 16");
     }
 
-    // ---- LDS map: [x_hat hi | x_hat lo] [cross-wave slots] [head logits of a group] [misc]
+    // ---- weight-stream plans (independent of the rows) and the LDS block every launch asks for
     size_t lds_cap = prop.sharedMemPerBlock;
     {
         int optin = 0;
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
             lds_cap = std::max(lds_cap, (size_t)optin);
     }
-    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1);
-    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1);
-    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2);
-    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1);
-    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1);
-    GemmPlan *plans[5] = {&md.plan[0], &md.plan[1], &md.plan[2], &md.plan[3], &md.plan[4]};
-    for (GemmPlan *p : plans) {
-        // the fewest workgroups that do not raise the busiest one's share
-        const int most = (p->U + m->nwg - 1) / m->nwg;
-        p->nwg = std::min(m->nwg, (p->U + most - 1) / most);
-        if (const char *e = getenv("EE_FULL_GRID")) p->nwg = atoi(e) ? m->nwg : p->nwg;  // tuning aid
-    }
-    const size_t misc = align_up((size_t)max_rows * (8 + (size_t)(c.head_dim / 2) * 8 + 4 + 4 + 4 + 4 + 4 + 4), 256);
-    const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
-    // Every stage kind lays the block out for itself: [input K-block][partial tiles][zbuf][misc].
-    // More n-tiles per group need more room for partial tiles and leave less for the input, i.e.
-    // more K-blocks; a stage runs groups x K-blocks segments, each with a restaging of the input,
-    // so the pair with the fewest segments is taken (ties: fewer K-blocks).
-    size_t lds = 0;
-    for (GemmPlan *p : plans) {
-        const int max_local = std::max(plan_max_local(p->U, p->tpu, p->nwg), p->tpu);
-        int best_cost = INT_MAX, best_grp = 0, best_nkb = 0, best_shared = 0;
-        for (int shared = 0; shared <= 1 && best_grp == 0; ++shared)  // shared accumulators only if nothing else fits
-            for (int grp = p->tpu; grp <= max_local; grp += p->tpu) {
-                if (shared && grp != max_local) continue;
-                const size_t slots = align_up((size_t)(shared ? 1 : WAVES) * grp * max_rows * 16 * sizeof(float), 256);
-                const size_t zbuf = align_up((size_t)max_rows * grp * 16 * sizeof(float), 256);
-                if (slots + zbuf + misc + 4096 > lds_cap) continue;
-                const size_t x_budget = (lds_cap - slots - zbuf - misc) / 256 * 256;
-                GemmPlan t = *p;
-                if (!plan_set_blocks(t, max_rows, x_budget)) continue;
-                const int cost = ((max_local + grp - 1) / grp) * t.nKB;
-                if (cost < best_cost || (cost == best_cost && t.nKB < best_nkb)) {
-                    best_cost = cost;
-                    best_grp = grp;
-                    best_nkb = t.nKB;
-                    best_shared = shared;
-                }
-            }
-        if (best_grp == 0) {
+    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1, m->nwg);
+    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1, m->nwg);
+    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg);
+    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1, m->nwg);
+    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1, m->nwg);
+    m->lds_budget = lds_cap / 256 * 256;   // the whole block: more than half of it also keeps a compute unit to one workgroup
+    for (int k = 0; k < 5; ++k) {
+        StageLds ly;
+        if (!plan_lds(md.plan[k], max_rows, m->lds_budget, ly)) {
             ee_model_free(m);
             return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
         }
-        p->GRP = best_grp;
-        p->nKB = best_nkb;
-        p->shared_acc = best_shared;
-        const size_t slots = align_up(plan_slot_bytes(*p, max_rows), 256);
-        const size_t zbuf = align_up((size_t)max_rows * p->GRP * 16 * sizeof(float), 256);
-        size_t x_bytes = (size_t)((p->KT + p->nKB - 1) / p->nKB) * 2 * max_rows * 32 * 2;
-        x_bytes = align_up(x_bytes, 256);
-        p->lds_slots_off = (int)x_bytes;
-        p->lds_zbuf_off = (int)(x_bytes + slots);
-        p->lds_misc_off = (int)(x_bytes + slots + zbuf);
-        lds = std::max(lds, x_bytes + slots + zbuf + misc);
-        p->steps = plan_steps(*p, p->nwg);
+        // tile offsets inside a stage are 32-bit byte offsets
+        if ((long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 1024 >= (1LL << 31)) {
+            ee_model_free(m);
+            return fail(EE_EFORMAT, "ee_model_load: a weight matrix of %d x %d exceeds the 2 GiB a stage can address", md.plan[k].N, md.plan[k].K);
+        }
     }
-    // the embedding stage keeps one float per (row, column quad) of its column range at the block's start
-    lds = std::max(lds, (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float));
-    lds = std::max(lds, att);  // attention uses the block on its own
-    // more than half of the CU's LDS keeps it to one workgroup per compute unit
-    lds = std::max(lds, std::min((size_t)84 * 1024, lds_cap));
-    m->lds_budget = lds;
     {
-        pass_kernel_t ks[4] = {chain_kernel(16), att_kernel(64), att_kernel(128), ee_misc_kernel};
+        const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
+        const size_t emb = (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float);
+        if (att > m->lds_budget || emb > m->lds_budget) {
+            ee_model_free(m);
+            return fail(EE_EDEVICE, "ee_model_load: not enough LDS");
+        }
+        pass_kernel_t ks[6] = {gemm_kernel(16), gemm_kernel(32), gemm_kernel(48), att_kernel(64), att_kernel(128), ee_misc_kernel};
         for (pass_kernel_t k : ks) {
             hipError_t fe = hipFuncSetAttribute(reinterpret_cast<const void *>(k),
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)m->lds_budget);
             if (fe != hipSuccess) {
                 ee_model_free(m);
-                return fail(EE_EDEVICE, "hipFuncSetAttribute(%zu bytes LDS): %s", lds, hipGetErrorString(fe));
+                return fail(EE_EDEVICE, "hipFuncSetAttribute(%zu bytes LDS): %s", m->lds_budget, hipGetErrorString(fe));
             }
         }
     }
@@ -459,7 +407,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.emb = dev_emb;
 
     // tiled weights: one allocation per GEMM kind, layers at a fixed stride
-    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * WAVES * 64;
+    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 64;
     const long long s_head = md.wstride[G_HEAD];
     md.wstride[G_HEAD] = 0;
     (void)s_head;
@@ -471,7 +419,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * WAVES * 64, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * SWAVES * 64, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
@@ -508,9 +456,6 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.g_final = g_final_d;
     hipFree(tmp_raw);
     tmp_raw = nullptr;
-    if ((rc = dev_alloc(m->allocs, &m->dev_md, 1, false)) != EE_OK) return bail(rc);
-    if (hipMemcpy(m->dev_md, &md, sizeof md, hipMemcpyHostToDevice) != hipSuccess)
-        return bail(fail(EE_EDEVICE, "upload of the model descriptor failed"));
     if (hipDeviceSynchronize() != hipSuccess) return bail(fail(EE_EDEVICE, "device error while loading the model"));
     *out = m;
     return EE_OK;
@@ -525,24 +470,28 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 {
     if (!m || !out) return fail(EE_EINVAL, "ee_model_info: null argument");
     *out = m->cfg;
-    out->max_rows = m->rows_api;  // as requested at load; one launch handles up to LAUNCH_ROWS of them
     return EE_OK;
 }
 
 // ------------------------------------------------------------------ sessions
 
 // Splits of the cache's pages per attention unit: enough items to occupy every compute unit
-// (one unit alone pulls a head's cache too slowly), at least one page per split, and no more
-// than ATT_TILES pages per wave.
-static int attention_splits(const ee_model *m, int n_sess, int M, int n_pos_max)
+// (one unit alone pulls a head's cache too slowly), at least one page per split, no more
+// than ATT_TILES pages per wave, and no more items than the leader's partials buffer holds.
+// Returns 0 when the buffer is too small for the context.
+static int attention_splits(const ee_session *lead, int n_sess, int M, int n_pos_max)
 {
+    const ee_model *m = lead->m;
     const int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     const int units = n_sess * m->cfg.n_heads * chunks;
     const int pages = (n_pos_max + KV_PAGE - 1) / KV_PAGE;
     const int forced = (pages + ATT_TILES * WAVES - 1) / (ATT_TILES * WAVES);
+    const int cap = std::min(ATT_MAX_SPLITS, lead->att_items_cap / std::max(units, 1));
     int s = std::min(m->nwg / std::max(units, 1), pages);
-    if (const char *e = getenv("EE_ATT_SPLITS")) s = atoi(e);
-    return std::min(std::max(std::max(1, s), forced), ATT_MAX_SPLITS);
+    if (lead->att_splits_opt > 0) s = lead->att_splits_opt;
+    s = std::max(std::max(1, s), forced);
+    if (forced > cap) return 0;
+    return std::min(s, cap);
 }
 
 extern "C" int ee_session_free(ee_session *s)
@@ -621,8 +570,6 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     // LIFO free list: the first logical page gets the highest physical page, so
     // the mapping is never the identity
     for (int p = s->n_pages - 1; p >= 0; --p) s->free_pages.push_back(p);  // handed out in ascending order
-    if (getenv("EE_SCATTER_PAGES"))  // test aid: hand pages out in descending order, so that the page table is really needed
-        std::reverse(s->free_pages.begin(), s->free_pages.end());
     s->pages_used = 0;
 
     // RoPE table in double on the host: angle = pos * base^(-2j/hd)
@@ -663,10 +610,12 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
-        // items = units * splits, splits <= max(nwg / units, pages / (ATT_TILES * WAVES) rounded up)
-        const size_t max_units = (size_t)EE_MAX_BATCH * c.n_heads * ((rows_max + ATT_ROWS - 1) / ATT_ROWS);
+        // items = units * splits; splits are chosen per pass and clamped to this room.  Units: a
+        // batch of sessions with one chunk of rows each, or one session with the rows of a prefill chunk.
+        const size_t max_units = (size_t)c.n_heads * std::max<size_t>(EE_MAX_BATCH, (rows_max + ATT_ROWS - 1) / ATT_ROWS);
         const size_t forced = ((size_t)s->n_pages + ATT_TILES * WAVES - 1) / (ATT_TILES * WAVES);
-        const size_t max_items = max_units * forced + (size_t)m->nwg;
+        const size_t max_items = max_units * std::max<size_t>(forced, 2) + (size_t)m->nwg;
+        s->att_items_cap = (int)max_items;
         S_TRY(dev_alloc(s->allocs, &sc.att_part, max_items * ATT_ROWS * (c.head_dim + 2)));
         S_TRY(dev_alloc(s->allocs, &sc.att_count, max_units));
         S_TRY(dev_alloc(s->allocs, &sc.head_count, 1));
@@ -675,11 +624,6 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.cand_sum, (size_t)m->nwg * rows_max));
-    S_TRY(dev_alloc(s->allocs, &sc.bar_flags, (size_t)m->nwg));
-    S_TRY(dev_alloc(s->allocs, &sc.err, 1));
-    if (flags & EE_TRACE)  // workgroup 0's stage stamps, then (start, end) of every workgroup in every launch
-        S_TRY(dev_alloc(s->allocs, &sc.trace, (size_t)EE_TRACE_MAX + (size_t)(EE_TRACE_MAX / EE_TRACE_SLOTS) * m->nwg * 2));
-    s->epoch = 0;
     S_HIP(hipDeviceSynchronize());
 #undef S_TRY
 #undef S_HIP
@@ -732,71 +676,51 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
         }
 }
 
-// host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [HEAD ACCEPT]
+// host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [HEAD]
 static int stage_type(const PassArgs &a, int ph)
 {
     const int per_layer = 5;
     int idx = ph - (a.do_embed ? 1 : 0);
     if (idx < 0) return ST_EMBED;
     const int nl = a.layer_end - a.layer_begin;
-    if (idx < per_layer * nl) {
-        int r = idx % per_layer;
-        if (r == 0) return ST_GEMM;
-        if (r == 1) return ST_ATT;
-        return ST_GEMM;
-    }
+    if (idx < per_layer * nl) return idx % per_layer == 1 ? ST_ATT : ST_GEMM;
     idx -= per_layer * nl;
-    if (a.head_kind != HEAD_NONE) return idx == 0 ? ST_GEMM : ST_ACCEPT;
+    if (a.head_kind != HEAD_NONE && idx == 0) return ST_GEMM;
     return ST_NONE;
 }
 
-// what a single-stage launch runs, as an EE_LAUNCH_* code
-static int launch_code(const PassArgs &a, int ph, int end)
+// what stage ph runs, as an EE_LAUNCH_* code (for a GEMM stage this is its GemmKind)
+static int launch_code(const PassArgs &a, int ph)
 {
     const int type = stage_type(a, ph);
     if (type == ST_EMBED) return EE_LAUNCH_EMBED;
     if (type == ST_ATT) return EE_LAUNCH_ATT;
-    if (type == ST_ACCEPT) return EE_LAUNCH_ACCEPT;
-    if (end - ph > 1) return EE_LAUNCH_CHAIN;
     const int per_layer = 5;
     int idx = ph - (a.do_embed ? 1 : 0);
     if (idx >= per_layer * (a.layer_end - a.layer_begin)) return EE_LAUNCH_HEAD;
     int r = idx % per_layer;
     if (r == 0) return EE_LAUNCH_QKV;
-    return EE_LAUNCH_O + (r - (per_layer - 3));
+    return EE_LAUNCH_O + (r - 2);
 }
 
-// Enqueues the stages of one segment.  Runs of consecutive GEMM stages go into one launch
-// of the chain kernel (grid barriers inside) with EE_CHAIN_LAUNCHES; otherwise every stage is a launch
-// of its own.  The chain kernel's barrier needs every workgroup resident: the grid is one
-// workgroup per compute unit and the LDS request keeps it to one per unit; the wait is
-// bounded, so a violated assumption ends in an error status, not in a hang.
+// Enqueues the stages of one segment, one launch each, on the leader's stream.
 static int launch_segment(ee_session *lead, PassArgs &a)
 {
     const ee_model *m = lead->m;
     const int per_layer = 5;
-    const int n_phases = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 2 : 0);
-    const bool single = (lead->flags & EE_CHAIN_LAUNCHES) == 0;
-    int ph = 0;
-    while (ph < n_phases) {
+    const int n_stages = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 1 : 0);
+    for (int ph = 0; ph < n_stages; ++ph) {
         const int type = stage_type(a, ph);
-        int end = ph + 1;
-        if (type == ST_GEMM && !single)
-            while (end < n_phases && stage_type(a, end) == ST_GEMM) ++end;
-        // a head stage at the end of a GEMM launch takes the accept step along
-        a.fuse_accept = (type == ST_GEMM && end < n_phases && stage_type(a, end) == ST_ACCEPT) ? 1 : 0;
-        a.ph_lo = ph;
-        a.ph_hi = end;
-        a.epoch_base = lead->epoch;
-        a.trace_base = lead->trace_n;
-        lead->trace_n = std::min(lead->trace_n + (end - ph) * EE_TRACE_SLOTS, EE_TRACE_MAX - 64 * EE_TRACE_SLOTS);
-        pass_kernel_t k = type == ST_GEMM ? chain_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
-        if (type == ST_GEMM) {  // the first stage's plan and weights travel with the launch
-            const int code = launch_code(a, ph, ph + 1);  // EE_LAUNCH_QKV .. EE_LAUNCH_HEAD = GemmKind
+        const int code = launch_code(a, ph);
+        a.stage = ph;
+        a.fuse_accept = code == EE_LAUNCH_HEAD ? 1 : 0;
+        pass_kernel_t k = type == ST_GEMM ? gemm_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
+        if (type == ST_GEMM) {  // the stage's plan, LDS map and weights travel with the launch (EE_LAUNCH_QKV .. EE_LAUNCH_HEAD = GemmKind)
             const int idx = ph - (a.do_embed ? 1 : 0);
             const int layer = code == EE_LAUNCH_HEAD ? 0 : a.layer_begin + idx / per_layer;
             a.plan0 = m->host_md.plan[code];
             a.W0 = m->host_md.w[code] + (size_t)layer * m->host_md.wstride[code];
+            if (!plan_lds(a.plan0, a.rows, m->lds_budget, a.lay)) return fail(EE_EDEVICE, "no LDS layout for %d rows", a.rows);
         }
         const bool timed = (lead->flags & EE_TIME_LAUNCHES) && a.mode == 0;
         if (timed) {
@@ -806,14 +730,12 @@ static int launch_segment(ee_session *lead, PassArgs &a)
                 HIP_TRY(hipEventCreate(&ev));
                 lead->lt_events.push_back(ev);
             }
-            lead->lt_codes.push_back(launch_code(a, ph, end));
+            lead->lt_codes.push_back(code);
             HIP_TRY(hipEventRecord(lead->lt_events[2 * i], lead->run_stream));
         }
         hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->run_stream, a);
         HIP_TRY(hipGetLastError());
         if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->run_stream));
-        lead->epoch += (unsigned)(end - ph - 1);
-        ph = end + a.fuse_accept;
     }
     return EE_OK;
 }
@@ -821,7 +743,6 @@ static int launch_segment(ee_session *lead, PassArgs &a)
 static void base_args(const ee_session *lead, PassArgs &a)
 {
     memset(&a, 0, sizeof a);
-    a.md = lead->m->dev_md;
     a.mdv = lead->m->host_md;
     a.sc = lead->sc;
     a.nwg = lead->m->nwg;
@@ -830,8 +751,6 @@ static void base_args(const ee_session *lead, PassArgs &a)
     a.Kpad_d = lead->m->host_md.Kpad_d;
     a.att_scale = lead->m->host_md.att_scale;
     a.keep_logits = (lead->flags & EE_KEEP_LOGITS) ? 1 : 0;
-    a.spin_limit = 1u << 20;
-    if (const char *e = getenv("EE_SPIN_LIMIT")) a.spin_limit = (unsigned)strtoul(e, nullptr, 10);
 }
 
 static int finish_flight(ee_session *s)
@@ -879,6 +798,10 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
     // reset
     s->run_stream = s->stream;
     release_pages(s, 0);
+    // all pages are free here: hand them out in ascending order (a fresh session's pages are then
+    // consecutive and the kernels skip the table lookup) or, as a test aid, in descending order
+    std::sort(s->free_pages.begin(), s->free_pages.end());
+    if (!s->scatter_pages) std::reverse(s->free_pages.begin(), s->free_pages.end());
     s->kv_len = 0;
     s->has_pending = false;
     s->leader = s;
@@ -919,7 +842,8 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
         a.head_kind = last ? HEAD_PREFILL : HEAD_NONE;
         a.head_idx = 0;
         a.head_gain = m->host_md.g_final;
-        a.att_splits = attention_splits(m, 1, rows, start + rows);
+        a.att_splits = attention_splits(s, 1, rows, start + rows);
+        if (a.att_splits == 0) return fail(EE_ECAPACITY, "ee_prefill: context too long for the session's attention scratch");
         a.sess = s->dev_sessdev;
         a.sess0 = s->host_sessdev[0];
         if ((rc = launch_segment(s, a)) != EE_OK) return rc;
@@ -962,59 +886,10 @@ static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exit
     return EE_OK;
 }
 
-static int verify_group(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
-                        const int32_t *exit_layers, int n_exits, const ee_verify_result **outs);
-
-// A batch of more rows than one launch handles runs as several groups of sessions, one after
-// the other; each group is a pass of its own (own leader, stream and events), so a session's
-// exit results are still published as soon as its group has them.
+// One pass for all sessions of the call: rows = n_sessions * (gamma + 1) share one stream of the
+// weights; the first session leads (its stream, events and scratch carry the pass).
 extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
                                const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
-{
-    if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
-        return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
-    for (int i = 0; i < n_sessions; ++i)
-        if (!sessions[i] || !drafts[i]) return fail(EE_EINVAL, "ee_verify: null session or drafts");
-    const ee_model *m = sessions[0]->m;
-    const int M = gamma + 1;
-    if (gamma < 1) return fail(EE_EINVAL, "ee_verify: gamma %d < 1", gamma);
-    if (n_sessions * M > m->rows_api)
-        return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, m->rows_api);
-    for (int i = 0; i < n_sessions; ++i)
-        for (int j = 0; j < i; ++j)
-            if (sessions[j] == sessions[i]) return fail(EE_EINVAL, "ee_verify_batch: session listed twice");
-    // every check that can fail comes before the first group is enqueued
-    const float *gains[EE_MAX_EXITS];
-    int rc0 = check_exits(m, exit_layers, n_exits, gains);
-    if (rc0 != EE_OK) return rc0;
-    for (int i = 0; i < n_sessions; ++i) {
-        ee_session *s = sessions[i];
-        if (s->m != m) return fail(EE_EINVAL, "ee_verify_batch: sessions of different models");
-        if (gamma > s->max_gamma) return fail(EE_EINVAL, "ee_verify: gamma %d exceeds the session's max_gamma %d", gamma, s->max_gamma);
-        for (int j = 0; j < gamma; ++j)
-            if (drafts[i][j] < 0 || drafts[i][j] >= m->cfg.vocab)
-                return fail(EE_EINVAL, "ee_verify: draft token %d outside [0,%d)", drafts[i][j], m->cfg.vocab);
-    }
-    HIP_TRY(hipSetDevice(m->device));
-    for (int i = 0; i < n_sessions; ++i) {
-        ee_session *s = sessions[i];
-        if ((rc0 = finish_flight(s)) != EE_OK) return rc0;
-        if (!s->has_pending) return fail(EE_ESTATE, "ee_verify: session has no pending token (call ee_prefill first)");
-        if (s->kv_len + M > s->max_ctx) return fail(EE_ECAPACITY, "ee_verify: kv_len %d + %d rows exceed max_ctx %d", s->kv_len, M, s->max_ctx);
-    }
-    const int per_group = std::max(1, m->cfg.max_rows / M);
-    const int n_groups = (n_sessions + per_group - 1) / per_group;
-    for (int g = 0; g < n_groups; ++g) {  // groups of nearly equal size
-        const int lo = n_sessions * g / n_groups, hi = n_sessions * (g + 1) / n_groups;
-        sessions[lo]->run_stream = sessions[0]->stream;  // the groups run one after the other on one stream
-        int rc = verify_group(sessions + lo, hi - lo, drafts + lo, gamma, exit_layers, n_exits, outs ? outs + lo : nullptr);
-        if (rc != EE_OK) return rc;
-    }
-    return EE_OK;
-}
-
-static int verify_group(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
-                        const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
 {
     if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
         return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
@@ -1034,20 +909,31 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
         for (int j = 0; j < gamma; ++j)
             if (drafts[i][j] < 0 || drafts[i][j] >= c.vocab)
                 return fail(EE_EINVAL, "ee_verify: draft token %d outside [0,%d)", drafts[i][j], c.vocab);
+        if (((s->flags ^ lead->flags) & EE_NO_AUTOCOMMIT) != 0)
+            return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
     }
     if (n_sessions * M > c.max_rows) return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, c.max_rows);
     const float *gains[EE_MAX_EXITS];
     int rc = check_exits(m, exit_layers, n_exits, gains);
     if (rc != EE_OK) return rc;
     HIP_TRY(hipSetDevice(m->device));
+    int n_pos_max = 0;
     for (int i = 0; i < n_sessions; ++i) {
         ee_session *s = sessions[i];
         if ((rc = finish_flight(s)) != EE_OK) return rc;
         if (!s->has_pending) return fail(EE_ESTATE, "ee_verify: session has no pending token (call ee_prefill first)");
         if (s->kv_len + M > s->max_ctx) return fail(EE_ECAPACITY, "ee_verify: kv_len %d + %d rows exceed max_ctx %d", s->kv_len, M, s->max_ctx);
+        n_pos_max = std::max(n_pos_max, s->kv_len + M);
     }
+    PassArgs a;
+    base_args(lead, a);
+    a.att_splits = attention_splits(lead, n_sessions, M, n_pos_max);
+    if (a.att_splits == 0)
+        return fail(EE_ECAPACITY, "ee_verify_batch: a context of %d positions needs more attention scratch than the first session holds "
+                                  "(list the session with the largest max_ctx first)", n_pos_max);
     // everything below is enqueued on the leader's stream; other sessions' own
     // streams are idle here (their last pass has been waited for)
+    lead->run_stream = lead->stream;
     for (int i = 0; i < n_sessions; ++i) {
         ee_session *s = sessions[i];
         if (s != lead) HIP_TRY(hipStreamSynchronize(s->stream));
@@ -1058,32 +944,18 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
         s->result->n_exits = n_exits;
         s->result->device_status = 0;
     }
-    PassArgs a;
-    base_args(lead, a);
     a.n_sess = n_sessions;
     a.M = M;
     a.rows = n_sessions * M;
     a.mode = 0;
-    {
-        int n_pos_max = 0;
-        for (int i = 0; i < n_sessions; ++i) n_pos_max = std::max(n_pos_max, sessions[i]->kv_len + M);
-        a.att_splits = attention_splits(m, n_sessions, M, n_pos_max);
-    }
-    a.commit = 1;
-    for (int i = 0; i < n_sessions; ++i) {
-        fill_sessdev(lead->host_sessdev[i], sessions[i]);
-        if (sessions[i]->flags & EE_NO_AUTOCOMMIT) a.commit = 0;
-    }
-    for (int i = 0; i < n_sessions; ++i)
-        if (((sessions[i]->flags & EE_NO_AUTOCOMMIT) != 0) != (a.commit == 0))
-            return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
+    a.commit = (lead->flags & EE_NO_AUTOCOMMIT) ? 0 : 1;
+    for (int i = 0; i < n_sessions; ++i) fill_sessdev(lead->host_sessdev[i], sessions[i]);
     HIP_TRY(hipMemcpyAsync(lead->dev_sessdev, lead->host_sessdev, (size_t)n_sessions * sizeof(SessDev),
                            hipMemcpyHostToDevice, lead->run_stream));
     a.sess = lead->dev_sessdev;
     a.sess0 = lead->host_sessdev[0];
 
     HIP_TRY(hipEventRecord(lead->ev_start, lead->run_stream));
-    lead->trace_n = 0;
     lead->lt_codes.clear();
     int layer = 0;
     for (int e = 0; e <= n_exits; ++e) {
@@ -1104,6 +976,7 @@ static int verify_group(ee_session *const *sessions, int n_sessions, const int32
         s->leader = lead;
         s->flight_gamma = gamma;
         s->flight_exits = n_exits;
+        s->flight_row0 = i * M;
         if (outs) outs[i] = s->result;
     }
     return EE_OK;
@@ -1236,64 +1109,37 @@ extern "C" int ee_pending(ee_session *s, int32_t *out)
 extern "C" int ee_debug_logits(ee_session *s, int head_idx, float *out)
 {
     if (!s || !out) return fail(EE_EINVAL, "null argument");
-    if (!(s->flags & EE_KEEP_LOGITS)) return fail(EE_ESTATE, "ee_debug_logits: session was created without EE_KEEP_LOGITS");
     if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_debug_logits: no verify pass was enqueued");
-    if (s->leader != s) return fail(EE_ESTATE, "ee_debug_logits: only for single-session passes");
+    ee_session *lead = s->leader;
+    if (!(lead->flags & EE_KEEP_LOGITS))
+        return fail(EE_ESTATE, "ee_debug_logits: the session that led the pass was created without EE_KEEP_LOGITS");
     if (head_idx < 0 || head_idx > s->flight_exits) return fail(EE_EINVAL, "head index %d not in [0,%d]", head_idx, s->flight_exits);
     HIP_TRY(hipSetDevice(s->m->device));
-    HIP_TRY(hipEventSynchronize(s->ev_final));
+    HIP_TRY(hipEventSynchronize(lead->ev_final));
     const size_t V = (size_t)s->m->cfg.vocab, rows_max = (size_t)s->m->cfg.max_rows;
     const int M = s->flight_gamma + 1;
-    HIP_TRY(hipMemcpy(out, s->sc.logits + (size_t)head_idx * rows_max * V, (size_t)M * V * sizeof(float), hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(out, lead->sc.logits + ((size_t)head_idx * rows_max + (size_t)s->flight_row0) * V, (size_t)M * V * sizeof(float),
+                      hipMemcpyDeviceToHost));
     return EE_OK;
 }
 
-// Measurement aid: launches the segment kernel `launches` times with `barriers`
-// grid barriers each and no other work; returns the mean time per launch.
-extern "C" int ee_debug_launch_cost(ee_session *s, int launches, int barriers, float *us_per_launch)
+extern "C" int ee_session_option(ee_session *s, int option, int value)
 {
-    if (!s || !us_per_launch || launches < 1 || barriers < 0) return fail(EE_EINVAL, "bad argument");
-    const ee_model *m = s->m;
-    HIP_TRY(hipSetDevice(m->device));
+    if (!s) return fail(EE_EINVAL, "null session");
     int rc = finish_flight(s);
     if (rc != EE_OK) return rc;
-    PassArgs a;
-    base_args(s, a);
-    a.mode = 2;
-    a.layer_end = barriers;
-    a.rows = 1;
-    a.sess = s->dev_sessdev;
-    HIP_TRY(hipStreamSynchronize(s->stream));
-    HIP_TRY(hipEventRecord(s->ev_start, s->stream));
-    for (int i = 0; i < launches; ++i) {
-        a.epoch_base = s->epoch;
-        hipLaunchKernelGGL(chain_kernel(1), dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, s->stream, a);
-        s->epoch += (unsigned)barriers;
+    switch (option) {
+    case EE_OPT_ATT_SPLITS:
+        if (value < 0 || value > ATT_MAX_SPLITS) return fail(EE_EINVAL, "EE_OPT_ATT_SPLITS: %d not in [0,%d]", value, ATT_MAX_SPLITS);
+        s->att_splits_opt = value;
+        return EE_OK;
+    case EE_OPT_SCATTER_PAGES:
+        if (value != 0 && value != 1) return fail(EE_EINVAL, "EE_OPT_SCATTER_PAGES: %d not 0 or 1", value);
+        s->scatter_pages = value != 0;
+        return EE_OK;
+    default:
+        return fail(EE_EINVAL, "ee_session_option: unknown option %d", option);
     }
-    HIP_TRY(hipGetLastError());
-    HIP_TRY(hipEventRecord(s->ev_final, s->stream));
-    HIP_TRY(hipEventSynchronize(s->ev_final));
-    float ms = 0.f;
-    HIP_TRY(hipEventElapsedTime(&ms, s->ev_start, s->ev_final));
-    *us_per_launch = ms * 1000.f / (float)launches;
-    return EE_OK;
-}
-
-// Debug (EE_TRACE sessions): wall-clock stamps (100 MHz ticks) that workgroup 0 took during
-// the GEMM stages of the last verify pass: n_stages x 8 values
-// {stage start, after staging, after staging of a later K-block, after the stream loop,
-//  after the reduce barrier, after the epilogue, stage end, before the grid barrier}.
-extern "C" int ee_debug_trace(ee_session *s, unsigned long long *out, int max_values, int *n_values)
-{
-    if (!s || !out || !n_values) return fail(EE_EINVAL, "null argument");
-    if (!(s->flags & EE_TRACE)) return fail(EE_ESTATE, "ee_debug_trace: session was created without EE_TRACE");
-    HIP_TRY(hipSetDevice(s->m->device));
-    int rc = finish_flight(s);
-    if (rc != EE_OK) return rc;
-    int n = std::min(s->trace_n, max_values);
-    HIP_TRY(hipMemcpy(out, s->sc.trace, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
-    *n_values = n;
-    return EE_OK;
 }
 
 // EE_TIME_LAUNCHES sessions: what every launch of the last verify pass ran and how long the
@@ -1311,21 +1157,6 @@ extern "C" int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max
         HIP_TRY(hipEventElapsedTime(&ms[i], s->lt_events[2 * i], s->lt_events[2 * i + 1]));
     }
     *n_launches = n;
-    return EE_OK;
-}
-
-// Debug (EE_TRACE sessions): (start, end) stamps of every workgroup in every launch of the last
-// verify pass, in launch order: n_launches x n_workgroups x 2 values.
-extern "C" int ee_debug_trace_workgroups(ee_session *s, unsigned long long *out, int max_values, int *n_values)
-{
-    if (!s || !out || !n_values) return fail(EE_EINVAL, "null argument");
-    if (!(s->flags & EE_TRACE)) return fail(EE_ESTATE, "ee_debug_trace_workgroups: session was created without EE_TRACE");
-    HIP_TRY(hipSetDevice(s->m->device));
-    int rc = finish_flight(s);
-    if (rc != EE_OK) return rc;
-    int n = std::min(s->trace_n / EE_TRACE_SLOTS * s->m->nwg * 2, max_values);
-    HIP_TRY(hipMemcpy(out, s->sc.trace + EE_TRACE_MAX, (size_t)n * sizeof(unsigned long long), hipMemcpyDeviceToHost));
-    *n_values = n;
     return EE_OK;
 }
 

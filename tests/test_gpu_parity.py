@@ -45,10 +45,12 @@ def test_mfma_lane_layout():
     ee.ee_debug_mfma_layout(0)
 
 
-def _one_round(g, o, prompt, drafts, exits, flags=0, what=""):
+def _one_round(g, o, prompt, drafts, exits, flags=0, what="", options=()):
     gs = g.session(len(prompt) + 64, max_gamma=15, flags=ee.KEEP_LOGITS | flags)
     os_ = o.session(len(prompt) + 64)
     try:
+        for opt, val in options:
+            gs.ee_session_option(opt, val)
         first_o = os_.prefill(prompt)
         first_g = gs.ee_prefill(prompt)
         # the first token is an argmax too; compare through a verify round below when it differs
@@ -89,15 +91,14 @@ def test_tiny_ragged_shapes(tiny_pair, n_prompt, gamma):
     _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"tiny P={n_prompt} gamma={gamma}")
 
 
-def test_tiny_launch_modes_bit_identical(tiny_pair):
-    """One launch per stage and persistent chain launches run the same code in
-    the same order: logits must be bit-identical, and so must two runs."""
+def test_tiny_runs_bit_identical(tiny_pair):
+    """Every reduction has a fixed order: two runs (fresh sessions) give bit-identical logits."""
     g, o = tiny_pair
     prompt = eegen.prompt_tokens(7, 40, o.vocab)
     drafts = eegen.prompt_tokens(8, 4, o.vocab)
     outs = []
-    for flags in (0, ee.CHAIN_LAUNCHES, 0):
-        gs = g.session(128, max_gamma=8, flags=ee.KEEP_LOGITS | flags)
+    for _ in range(3):
+        gs = g.session(128, max_gamma=8, flags=ee.KEEP_LOGITS)
         gs.ee_prefill(prompt)
         r = gs.verify_sync(drafts, TINY_EXITS)
         outs.append((r, gpu_logits(gs, 1)))
@@ -319,14 +320,14 @@ def test_exit_results_visible_before_final(mid_pair):
 
 
 @pytest.mark.parametrize("splits,prompt_len", [(1, 300), (2, 500), (3, 200)])
-def test_attention_several_pages_per_wave(mid_pair, splits, prompt_len, monkeypatch):
+def test_attention_several_pages_per_wave(mid_pair, splits, prompt_len):
     """Few attention splits on a longer context: a wave then walks several KV pages per item
-    (the split count is read per pass; normally it is chosen so that a wave gets about one)."""
+    (normally the split count is chosen so that a wave gets about one)."""
     g, o = mid_pair
-    monkeypatch.setenv("EE_ATT_SPLITS", str(splits))
     prompt = eegen.prompt_tokens(900 + splits, prompt_len, o.vocab)
     drafts = eegen.prompt_tokens(901 + splits, 7, o.vocab)
-    exempt, err, _ = _one_round(g, o, prompt, drafts, [1, 2], what=f"splits={splits} P={prompt_len}")
+    exempt, err, _ = _one_round(g, o, prompt, drafts, [1, 2], what=f"splits={splits} P={prompt_len}",
+                                options=[(ee.OPT_ATT_SPLITS, splits)])
     assert err <= 3e-2
 
 
@@ -341,14 +342,13 @@ def test_gamma_extremes_and_page_boundary(tiny_pair):
             _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"P={P} gamma={gamma}")
 
 
-def test_scattered_pages_use_the_page_table(tiny_pair, mid_pair, monkeypatch):
+def test_scattered_pages_use_the_page_table(tiny_pair, mid_pair):
     """A fresh session's pages are consecutive and the kernels then skip the table lookup;
     with the pages handed out in descending order the lookup path runs."""
-    monkeypatch.setenv("EE_SCATTER_PAGES", "1")
     for (g, o), exits in ((tiny_pair, TINY_EXITS), (mid_pair, [1, 2])):
         prompt = eegen.prompt_tokens(1200, 75, o.vocab)
         drafts = eegen.prompt_tokens(1201, 6, o.vocab)
-        _one_round(g, o, prompt, drafts, exits, what="scattered pages")
+        _one_round(g, o, prompt, drafts, exits, what="scattered pages", options=[(ee.OPT_SCATTER_PAGES, 1)])
 
 
 def test_empty_cache_and_exit_after_every_layer(model_dir):
@@ -381,10 +381,10 @@ def test_empty_cache_and_exit_after_every_layer(model_dir):
         g.free()
 
 
-@pytest.mark.parametrize("B,gamma,max_rows,chain", [(5, 2, 15, False), (7, 1, 14, False), (3, 7, 24, False), (6, 4, 30, True)])
-def test_batch_group_shapes(model_dir, B, gamma, max_rows, chain):
-    """Batches that fit one launch (<= 16 rows), that split into uneven groups, and one with
-    chained GEMM launches; also: more rows than the model was loaded for is refused."""
+@pytest.mark.parametrize("B,gamma,max_rows", [(5, 2, 15), (7, 1, 14), (3, 7, 24), (6, 4, 30), (3, 15, 48), (16, 2, 48)])
+def test_batch_shapes(model_dir, B, gamma, max_rows):
+    """Batches of one, two and three 16-row tiles with ragged last tiles (15, 14, 24, 30, 48
+    rows); also: more rows than the model was loaded for is refused."""
     p = f"{model_dir}/gpu_tiny_groups.bin"
     eegen.write_model(p, eegen.TINY, 77, gains="uniform")
     g = ee.Model(p, max_rows=max_rows)
@@ -393,7 +393,7 @@ def test_batch_group_shapes(model_dir, B, gamma, max_rows, chain):
     try:
         for b in range(B):
             toks = eegen.prompt_tokens(400, 9 + 2 * b, o.vocab, session=b)
-            gs = g.session(96, max_gamma=gamma, flags=ee.CHAIN_LAUNCHES if chain else 0)
+            gs = g.session(96, max_gamma=gamma)
             os_ = o.session(96)
             if gs.ee_prefill(toks) != os_.prefill(toks):
                 gs.ee_set_pending(os_.pending)
