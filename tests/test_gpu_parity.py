@@ -6,7 +6,7 @@ import pytest
 import eegen
 import paper_2505_21594_amd as ee
 from oracle import oracle as eo
-from tests.parity import check_pass, gpu_logits
+from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill
 
 pytestmark = pytest.mark.gpu
 
@@ -51,16 +51,14 @@ def _one_round(g, o, prompt, drafts, exits, flags=0, what="", options=()):
     try:
         for opt, val in options:
             gs.ee_session_option(opt, val)
-        first_o = os_.prefill(prompt)
+        first_o, margin = oracle_prefill(os_, prompt)
         first_g = gs.ee_prefill(prompt)
-        # the first token is an argmax too; compare through a verify round below when it differs
-        if first_g != first_o:
-            gs.ee_set_pending(first_o)
+        same = check_first_token(gs, first_g, first_o, margin, what)
         assert gs.ee_kv_len() == os_.kv_len == len(prompt)
         ro = os_.verify(drafts, exits, commit=True, want_logits=True)
         rg = gs.verify_sync(drafts, exits)
         exempt, err = check_pass(ro, rg, gpu_logits(gs, len(exits)), drafts, what)
-        return exempt, err, first_g == first_o
+        return exempt, err, same
     finally:
         gs.free()
 
@@ -71,15 +69,7 @@ def test_tiny_single_round(tiny_pair, seed):
     prompt = eegen.prompt_tokens(seed, 64, o.vocab)
     s = o.session(96)
     s.prefill(prompt)
-    greedy = []
-    for _ in range(4):   # the oracle's own greedy continuation after `pending`
-        r = s.verify([0], commit=False)
-        kv = s.kv_len
-        s.verify([int(r.final_tokens[0])], commit=True)
-        s.kv_truncate(kv + 1)
-        s.set_pending(int(r.final_tokens[0]))
-        greedy.append(int(r.final_tokens[0]))
-    drafts = eegen.corrupt_drafts(greedy, 0.3, o.vocab, seed, 0)
+    drafts = eegen.corrupt_drafts(oracle_greedy(s, 4), 0.3, o.vocab, seed, 0)
     _one_round(g, o, prompt, drafts, TINY_EXITS, what=f"tiny seed {seed}")
 
 
@@ -114,26 +104,12 @@ def _chain(g, o, prompt, gamma, exits, rounds, p_corrupt, seed, max_ctx, what):
     os_ = o.session(max_ctx)
     exempt_rounds, max_err = 0, 0.0
     try:
-        first_o = os_.prefill(prompt)
+        first_o, margin = oracle_prefill(os_, prompt)
         first_g = gs.ee_prefill(prompt)
-        if first_g != first_o:
-            gs.ee_set_pending(first_o)
+        check_first_token(gs, first_g, first_o, margin, what)
         hist = list(prompt) + [first_o]      # every committed token; the last one is pending
         for r_i in range(rounds):
-            # oracle's greedy continuation after pending, by single-row steps rolled back
-            kv0, pend0 = os_.kv_len, os_.pending
-            greedy = []
-            for _ in range(gamma):
-                r = os_.verify([0], commit=False)
-                t = int(r.final_tokens[0])
-                kv = os_.kv_len
-                os_.verify([t], commit=True)
-                os_.kv_truncate(kv + 1)
-                os_.set_pending(t)
-                greedy.append(t)
-            os_.kv_truncate(kv0)
-            os_.set_pending(pend0)
-            drafts = eegen.corrupt_drafts(greedy, p_corrupt, o.vocab, seed, r_i)
+            drafts = eegen.corrupt_drafts(oracle_greedy(os_, gamma), p_corrupt, o.vocab, seed, r_i)
             ro = os_.verify(drafts, exits, commit=True, want_logits=True)
             hist += [int(t) for t in drafts[:ro.accept_len]] + [int(ro.next_token)]
             gs.ee_verify(drafts, exits)
@@ -200,10 +176,12 @@ def test_hold_last_and_embedding_prefix(tiny_pair):
     for flags_o, flags_g in ((0, 0), (eo.HOLD_LAST, ee.HOLD_LAST)):
         gs = g.session(96, max_gamma=4, flags=ee.KEEP_LOGITS)
         os_ = o.session(96)
-        fo = os_.prefill(toks, flags=flags_o, emb=emb)
         fg = gs.ee_prefill(toks, flags=flags_g, emb=emb)
-        if flags_g == 0 and fo != fg:
-            gs.ee_set_pending(fo)
+        if flags_g == 0:
+            fo, margin = oracle_prefill(os_, toks, emb=emb)
+            check_first_token(gs, fg, fo, margin, "embedding prefix")
+        else:
+            os_.prefill(toks, flags=flags_o, emb=emb)
         assert gs.ee_kv_len() == os_.kv_len
         ro = os_.verify(drafts, TINY_EXITS, want_logits=True)
         rg = gs.verify_sync(drafts, TINY_EXITS)
@@ -273,12 +251,10 @@ def test_batched_sessions_match_single(model_dir):
     for b in range(B):
         emb = eegen.embedding_prefix(300, 20 + 3 * b, o.d_model, session=b)
         toks = eegen.prompt_tokens(301, 5 + b, o.vocab, session=b)
-        gs = g.session(128, max_gamma=gamma, flags=0)
+        gs = g.session(128, max_gamma=gamma, flags=ee.KEEP_LOGITS if b == 0 else 0)
         os_ = o.session(128)
-        fo = os_.prefill(toks, emb=emb)
-        fg = gs.ee_prefill(toks, emb=emb)
-        if fo != fg:
-            gs.ee_set_pending(fo)
+        fo, margin = oracle_prefill(os_, toks, emb=emb)
+        check_first_token(gs, gs.ee_prefill(toks, emb=emb), fo, margin, f"batch session {b}")
         sess.append(gs)
         osess.append(os_)
     for rnd in range(3):
@@ -293,7 +269,7 @@ def test_batched_sessions_match_single(model_dir):
             sess[b].ee_wait_final()
             ro = osess[b].verify(drafts[b], TINY_EXITS, want_logits=True)
             rg = sess[b].final_result()
-            check_pass(ro, rg, None, drafts[b], f"batch round {rnd} session {b}")
+            check_pass(ro, rg, gpu_logits(sess[b], 1), drafts[b], f"batch round {rnd} session {b}")
             assert rg.accept_len == ro.accept_len and rg.next_token == ro.next_token, \
                 "low-margin divergence in the batch test: pick another seed"
             assert sess[b].ee_kv_len() == osess[b].kv_len
@@ -311,9 +287,11 @@ def test_exit_results_visible_before_final(mid_pair):
     gs.ee_prefill(prompt)
     gs.ee_verify(eegen.prompt_tokens(62, 4, o.vocab), [1, 2])
     gs.ee_wait_exit(0)
+    assert gs.ee_query_exit(0)                       # EE_OK: published
     toks, delta = gs.exit_result(0)
     assert 0 <= delta <= 4 and all(0 <= t < o.vocab for t in toks)
     gs.ee_wait_final()
+    assert gs.ee_query_final() and gs.ee_query_exit(1)
     t0, t1, tf = gs.ee_pass_time_ms(0), gs.ee_pass_time_ms(1), gs.ee_pass_time_ms(2)
     assert 0 < t0 < t1 < tf
     gs.free()
@@ -395,8 +373,8 @@ def test_batch_shapes(model_dir, B, gamma, max_rows):
             toks = eegen.prompt_tokens(400, 9 + 2 * b, o.vocab, session=b)
             gs = g.session(96, max_gamma=gamma)
             os_ = o.session(96)
-            if gs.ee_prefill(toks) != os_.prefill(toks):
-                gs.ee_set_pending(os_.pending)
+            fo, margin = oracle_prefill(os_, toks)
+            check_first_token(gs, gs.ee_prefill(toks), fo, margin, f"B={B} session {b}")
             sess.append(gs)
             osess.append(os_)
         for rnd in range(2):
@@ -421,4 +399,77 @@ def test_batch_shapes(model_dir, B, gamma, max_rows):
     finally:
         for s in sess:
             s.free()
+        g.free()
+
+
+def _with_duplicated_rows(src_path, dst_path, groups):
+    """Copy of a model file in which, for every (source id, [ids]) in groups, the LM-head rows
+    `ids` are overwritten with the row of the source id: their logits tie exactly."""
+    import shutil
+    shutil.copyfile(src_path, dst_path)
+    cfg = eegen.read_header(dst_path)
+    off, shape = eegen.tensor_table(cfg)[0]["w_lm"]
+    mm = np.memmap(dst_path, dtype=np.uint16, mode="r+", offset=off, shape=shape)
+    for src, ids in groups:
+        for i in ids:
+            mm[i] = mm[src]
+    mm.flush()
+    del mm
+
+
+@pytest.mark.parametrize("which", ["tiny", "mid"])
+def test_argmax_ties_go_to_the_lowest_id(model_dir, tiny_path, which):
+    """The lowest token id wins an exact tie (reading of the paper's argmax; the oracle has the
+    same rule).  The winning LM-head row of one pass row is copied to a lower id in another
+    workgroup's n-tile, to its neighbour in the same n-tile and to a higher id in a third
+    n-tile, for the final head and for an exit head: the lanes of a wave, the waves' candidates
+    and the workgroups' candidates all see equal values with different ids."""
+    if which == "tiny":
+        cfg, src, exits = eegen.TINY, tiny_path, TINY_EXITS
+    else:
+        cfg, exits = MID, [1, 2]
+        src = f"{model_dir}/gpu_mid_tie_src.bin"
+        eegen.write_model(src, MID, 77, gains="uniform", std=0.03)
+    o0 = eo.Model(src)
+    prompt = eegen.prompt_tokens(1500, 37, cfg.vocab)
+    drafts = eegen.prompt_tokens(1501, 5, cfg.vocab)
+    s0 = o0.session(96)
+    s0.prefill(prompt)
+    r0 = s0.verify(drafts, exits, commit=False, want_logits=True)
+    margins = eo.top2_margin(r0.logits)
+    row = int(np.argmax(margins[-1]))                     # the most decisive row of the final head
+    groups, used = [], set()
+    for head_tokens in (r0.final_tokens, r0.exit_tokens[0]):
+        t = int(head_tokens[row])
+        if t in used:
+            continue
+        ids = [i for i in (t - 16 * 3 - 1, t ^ 1, t + 16 * 5 + 2) if 0 <= i < cfg.vocab and i not in used and i != t]
+        groups.append((t, ids))
+        used.update(ids + [t])
+    dst = f"{model_dir}/gpu_{which}_tie.bin"
+    _with_duplicated_rows(src, dst, groups)
+    g, o = ee.Model(dst), eo.Model(dst)
+    try:
+        gs = g.session(96, max_gamma=8, flags=ee.KEEP_LOGITS)
+        os_ = o.session(96)
+        fo, margin = oracle_prefill(os_, prompt)
+        check_first_token(gs, gs.ee_prefill(prompt), fo, margin, "tie")
+        ro = os_.verify(drafts, exits, commit=False, want_logits=True)
+        rg = gs.verify_sync(drafts, exits)
+        lg = gpu_logits(gs, len(exits))
+        check_pass(ro, rg, lg, drafts, f"{which} tie")
+        n_ties = 0
+        for e in range(len(exits) + 1):
+            ot = ro.final_tokens if e == len(exits) else ro.exit_tokens[e]
+            gt = rg.final_tokens if e == len(exits) else rg.exit_tokens[e]
+            for t, ids in groups:
+                if int(ot[row]) == min([t] + ids):        # the tie is at the top of this head's row
+                    n_ties += 1
+                    assert ro.logits[e][row][t] == ro.logits[e][row][ids[0]]
+                    assert int(gt[row]) == min([t] + ids), f"head {e}: GPU picked {gt[row]}, lowest tied id is {min([t] + ids)}"
+                    vals = {float(lg[e][row][i]) for i in [t] + ids}
+                    assert len(vals) == 1, f"head {e}: tied rows give different GPU logits {vals}"
+        assert n_ties >= 1
+        gs.free()
+    finally:
         g.free()
