@@ -154,6 +154,21 @@ int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *
                     int gamma, const int32_t *exit_layers, int n_exits,
                     const ee_verify_result **outs);
 
+/* ee_verify for callers that cannot allocate GPU memory: code under HIP graph capture, tight
+   serving loops, harnesses that forbid hipMalloc.  Same pass, same results; the pass's scratch
+   (residual stream, GEMM inputs, norm partials, attention partials, argmax candidates, counters)
+   lives in a static device array of EE_STATIC_SCRATCH_BYTES that every GPU the library runs on
+   holds until the process ends, instead of in the session's own buffers.  Neither this call nor
+   anything it runs calls hipMalloc / hipFree or an allocating library routine.  One session per
+   call; EE_ECAPACITY if gamma + 1 rows of this model (or the context's attention partials) do not
+   fit the array; not for EE_TIME_LAUNCHES sessions.  Calls on one GPU share that GPU's array: two
+   ee_verify_static passes must not overlap in time on a GPU (wait for one before the next, also
+   across sessions); passes enqueued with ee_verify / ee_verify_batch are not affected.  Inputs,
+   the KV cache and the pinned result block are the session's as usual. */
+#define EE_STATIC_SCRATCH_BYTES (8 << 20)
+int ee_verify_static(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
+                     int n_exits, const ee_verify_result **out);
+
 int ee_wait_exit(ee_session *s, int exit_idx);   /* blocks until exit exit_idx is published */
 int ee_query_exit(ee_session *s, int exit_idx);  /* EE_OK or EE_NOT_READY                   */
 int ee_wait_final(ee_session *s);                /* blocks until the pass has finished      */

@@ -33,7 +33,7 @@ LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "att", "embed")
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
-    "ee_verify_batch", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
+    "ee_verify_batch", "ee_verify_static", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_session_option",
     "ee_launch_times", "ee_debug_copy",
@@ -93,6 +93,7 @@ def load_library():
     lib.ee_prefill.argtypes = [vp, i32p, ci, ctypes.c_uint, i32p]
     lib.ee_prefill_embeds.argtypes = [vp, vp, ci, i32p, ci, ctypes.c_uint, i32p]
     lib.ee_verify.argtypes = [vp, i32p, ci, i32p, ci, P(P(VerifyResultC))]
+    lib.ee_verify_static.argtypes = [vp, i32p, ci, i32p, ci, P(P(VerifyResultC))]
     lib.ee_verify_batch.argtypes = [P(vp), ci, P(i32p), ci, i32p, ci, P(P(VerifyResultC))]
     lib.ee_wait_exit.argtypes = [vp, ci]
     lib.ee_query_exit.argtypes = [vp, ci]
@@ -208,6 +209,13 @@ class Session:
         d, ex = _i32(draft_tokens), _i32(exit_layers)
         res = ctypes.POINTER(VerifyResultC)()
         _check(self._l.ee_verify(self._h, _p(d), d.size, _p(ex), ex.size, ctypes.byref(res)))
+        self._res, self._n_exits, self._gamma = res, ex.size, d.size
+
+    def ee_verify_static(self, draft_tokens: Sequence[int], exit_layers: Sequence[int] = ()) -> None:
+        """ee_verify on the library's static scratch array (allocates nothing)."""
+        d, ex = _i32(draft_tokens), _i32(exit_layers)
+        res = ctypes.POINTER(VerifyResultC)()
+        _check(self._l.ee_verify_static(self._h, _p(d), d.size, _p(ex), ex.size, ctypes.byref(res)))
         self._res, self._n_exits, self._gamma = res, ex.size, d.size
 
     def ee_wait_exit(self, exit_idx: int) -> None:

@@ -479,14 +479,14 @@ extern "C" int ee_model_info(const ee_model *m, ee_model_config *out)
 // (one unit alone pulls a head's cache too slowly), at least one page per split, no more
 // than ATT_TILES pages per wave, and no more items than the leader's partials buffer holds.
 // Returns 0 when the buffer is too small for the context.
-static int attention_splits(const ee_session *lead, int n_sess, int M, int n_pos_max)
+static int attention_splits(const ee_session *lead, int items_cap, int n_sess, int M, int n_pos_max)
 {
     const ee_model *m = lead->m;
     const int chunks = (M + ATT_ROWS - 1) / ATT_ROWS;
     const int units = n_sess * m->cfg.n_heads * chunks;
     const int pages = (n_pos_max + KV_PAGE - 1) / KV_PAGE;
     const int forced = (pages + ATT_TILES * WAVES - 1) / (ATT_TILES * WAVES);
-    const int cap = std::min(ATT_MAX_SPLITS, lead->att_items_cap / std::max(units, 1));
+    const int cap = std::min(ATT_MAX_SPLITS, items_cap / std::max(units, 1));
     int s = std::min(m->nwg / std::max(units, 1), pages);
     if (lead->att_splits_opt > 0) s = lead->att_splits_opt;
     s = std::max(std::max(1, s), forced);
@@ -842,7 +842,7 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
         a.head_kind = last ? HEAD_PREFILL : HEAD_NONE;
         a.head_idx = 0;
         a.head_gain = m->host_md.g_final;
-        a.att_splits = attention_splits(s, 1, rows, start + rows);
+        a.att_splits = attention_splits(s, s->att_items_cap, 1, rows, start + rows);
         if (a.att_splits == 0) return fail(EE_ECAPACITY, "ee_prefill: context too long for the session's attention scratch");
         a.sess = s->dev_sessdev;
         a.sess0 = s->host_sessdev[0];
@@ -886,10 +886,88 @@ static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exit
     return EE_OK;
 }
 
+// ------------------------------------------------------------------ static scratch (ee_verify_static)
+
+// Scratch of one single-session pass for callers that must not allocate.  One copy per GPU the
+// library is loaded on, held until the process ends.  In host code the array's name is only a
+// handle: its device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[EE_STATIC_SCRATCH_BYTES];
+
+constexpr int EE_MAX_DEVICES = 64;
+static void *g_scratch_ptr[EE_MAX_DEVICES];   // per device: address of that GPU's copy of `scratch`
+
+static int static_scratch_ptr(int device, unsigned char **out)
+{
+    if (device < 0 || device >= EE_MAX_DEVICES) return fail(EE_EINVAL, "device %d: at most %d devices", device, EE_MAX_DEVICES);
+    if (!g_scratch_ptr[device]) {   // the model's device is current here
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[device] = p;
+    }
+    *out = static_cast<unsigned char *>(g_scratch_ptr[device]);
+    return EE_OK;
+}
+
+// fills n 16-byte words with zeros (a kernel, not hipMemsetAsync: callers may be capturing a graph)
+__global__ void __launch_bounds__(256) ee_zero_kernel(uint4 *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+// Lays the pass's scratch buffers out in the static array (sizes for M rows of this model),
+// points a.sc at them, picks the attention splits for that room and enqueues the clearing of
+// the part in use: the array keeps the last call's contents, and the padding columns of the GEMM
+// inputs and the attention / head counters must start at zero.
+static int use_static_scratch(ee_session *lead, PassArgs &a, int M, int n_pos_max)
+{
+    const ee_model *m = lead->m;
+    const ModelDev &md = m->host_md;
+    unsigned char *base = nullptr;
+    int rc = static_scratch_ptr(m->device, &base);
+    if (rc != EE_OK) return rc;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        unsigned char *p = base + off;
+        off += align_up(std::max<size_t>(bytes, 16), 256);
+        return p;
+    };
+    const size_t rows = (size_t)M, d = (size_t)md.d;
+    Scratch sc;
+    memset(&sc, 0, sizeof sc);
+    sc.h = reinterpret_cast<float *>(take(rows * d * 4));
+    sc.q = reinterpret_cast<float *>(take(rows * d * 4));
+    sc.xn = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
+    sc.xh = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
+    sc.attn = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
+    sc.u = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_F * 2));
+    sc.ss_a = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
+    sc.ss_f = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
+    sc.cand = reinterpret_cast<int2 *>(take((size_t)m->nwg * md.rows_max * 8));
+    sc.cand_sum = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
+    sc.att_count = reinterpret_cast<int *>(take((size_t)md.H * 4));
+    sc.head_count = reinterpret_cast<int *>(take(4));
+    sc.logits = lead->sc.logits;   // kept logits are an output of the session, not scratch
+    // attention partials: what is left, at most one item per compute unit and split
+    const size_t item_bytes = (size_t)ATT_ROWS * (md.hd + 2) * 4;
+    if (off + (size_t)md.H * item_bytes > EE_STATIC_SCRATCH_BYTES)
+        return fail(EE_ECAPACITY, "ee_verify_static: %d rows of this model need more than the %d bytes of static scratch", M, EE_STATIC_SCRATCH_BYTES);
+    const int items_cap = (int)std::min<size_t>((EE_STATIC_SCRATCH_BYTES - off) / item_bytes, (size_t)md.H * ATT_MAX_SPLITS);
+    a.att_splits = attention_splits(lead, items_cap, 1, M, n_pos_max);
+    if (a.att_splits == 0)
+        return fail(EE_ECAPACITY, "ee_verify_static: a context of %d positions needs more than the %d bytes of static scratch", n_pos_max, EE_STATIC_SCRATCH_BYTES);
+    sc.att_part = reinterpret_cast<float *>(take((size_t)md.H * a.att_splits * item_bytes));
+    a.sc = sc;
+    hipLaunchKernelGGL(ee_zero_kernel, dim3(256), dim3(256), 0, lead->run_stream, reinterpret_cast<uint4 *>(base), off / 16);
+    HIP_TRY(hipGetLastError());
+    return EE_OK;
+}
+
 // One pass for all sessions of the call: rows = n_sessions * (gamma + 1) share one stream of the
 // weights; the first session leads (its stream, events and scratch carry the pass).
-extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
-                               const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
+// static_scratch: run the pass on the library's static scratch array instead of the leader's own
+// buffers (ee_verify_static); nothing on this path allocates.
+static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                       const int32_t *exit_layers, int n_exits, const ee_verify_result **outs, bool static_scratch)
 {
     if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
         return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
@@ -927,13 +1005,17 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     }
     PassArgs a;
     base_args(lead, a);
-    a.att_splits = attention_splits(lead, n_sessions, M, n_pos_max);
-    if (a.att_splits == 0)
-        return fail(EE_ECAPACITY, "ee_verify_batch: a context of %d positions needs more attention scratch than the first session holds "
-                                  "(list the session with the largest max_ctx first)", n_pos_max);
+    lead->run_stream = lead->stream;
+    if (static_scratch) {
+        if ((rc = use_static_scratch(lead, a, M, n_pos_max)) != EE_OK) return rc;
+    } else {
+        a.att_splits = attention_splits(lead, lead->att_items_cap, n_sessions, M, n_pos_max);
+        if (a.att_splits == 0)
+            return fail(EE_ECAPACITY, "ee_verify_batch: a context of %d positions needs more attention scratch than the first session holds "
+                                      "(list the session with the largest max_ctx first)", n_pos_max);
+    }
     // everything below is enqueued on the leader's stream; other sessions' own
     // streams are idle here (their last pass has been waited for)
-    lead->run_stream = lead->stream;
     for (int i = 0; i < n_sessions; ++i) {
         ee_session *s = sessions[i];
         if (s != lead) HIP_TRY(hipStreamSynchronize(s->stream));
@@ -982,6 +1064,12 @@ extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, cons
     return EE_OK;
 }
 
+extern "C" int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                               const int32_t *exit_layers, int n_exits, const ee_verify_result **outs)
+{
+    return verify_impl(sessions, n_sessions, drafts, gamma, exit_layers, n_exits, outs, false);
+}
+
 extern "C" int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers, int n_exits,
                          const ee_verify_result **out)
 {
@@ -989,7 +1077,20 @@ extern "C" int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, 
     ee_session *ss[1] = {s};
     const int32_t *dd[1] = {draft_tokens};
     const ee_verify_result *oo[1] = {nullptr};
-    int rc = ee_verify_batch(ss, 1, dd, gamma, exit_layers, n_exits, oo);
+    int rc = verify_impl(ss, 1, dd, gamma, exit_layers, n_exits, oo, false);
+    if (rc == EE_OK && out) *out = oo[0];
+    return rc;
+}
+
+extern "C" int ee_verify_static(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers, int n_exits,
+                                const ee_verify_result **out)
+{
+    if (!s) return fail(EE_EINVAL, "ee_verify_static: null session");
+    if (s->flags & EE_TIME_LAUNCHES) return fail(EE_ESTATE, "ee_verify_static: not for EE_TIME_LAUNCHES sessions (their event pairs are created on demand)");
+    ee_session *ss[1] = {s};
+    const int32_t *dd[1] = {draft_tokens};
+    const ee_verify_result *oo[1] = {nullptr};
+    int rc = verify_impl(ss, 1, dd, gamma, exit_layers, n_exits, oo, true);
     if (rc == EE_OK && out) *out = oo[0];
     return rc;
 }
