@@ -53,7 +53,8 @@ extern "C" {
 #define EE_MAX_ROWS 48   /* rows per pass over all sessions of a batch                */
 
 #define EE_OK 0
-#define EE_NOT_READY 1        /* ee_query_*: the result is not there yet               */
+#define EE_NOT_READY 1        /* ee_query_*, ee_exit_pop: the result is not there yet  */
+#define EE_DONE 2             /* ee_exit_pop: nothing left to send for this pass       */
 #define EE_EINVAL (-1)        /* bad argument                                          */
 #define EE_ESTATE (-2)        /* call not allowed in this state                        */
 #define EE_ECAPACITY (-3)     /* kv_len + gamma + 1 would exceed max_ctx               */
@@ -173,6 +174,48 @@ int ee_wait_exit(ee_session *s, int exit_idx);   /* blocks until exit exit_idx i
 int ee_query_exit(ee_session *s, int exit_idx);  /* EE_OK or EE_NOT_READY                   */
 int ee_wait_final(ee_session *s);                /* blocks until the pass has finished      */
 int ee_query_final(ee_session *s);
+
+/* The server's SENDER side of the paper (Appendix "System Design", Algorithm 2): exit results
+   wait in a queue Q_e and leave it in the order of their confidence score, because the
+   network is slower than the exits are produced.  The score of exit e is
+   s^(e) = max over rows 0..delta^(e) of the row's largest softmax probability (Alg. 2's
+   max(q^(e)_{1:delta+1}) with Eq. 4's confidence), i.e. of exit_conf[e][0..exit_accept_len[e]].
+   ee_exit_pop: among the exits of the pass in flight that are published and not popped yet,
+   returns the one with the highest score (ties: the earlier exit) in *exit_idx / *score
+   (EE_OK).  Nothing published: waits for the next exit if `wait`, else EE_NOT_READY.  EE_DONE
+   when every exit has been popped or the final result is there (Alg. 2 resets the queue when
+   the final result is sent).  Host-side only: polls the exit events.
+   ee_exit_order: after the pass has finished, all its exits in the order the queue would
+   release them if all were waiting (score descending); order / scores have n_exits entries. */
+int ee_exit_pop(ee_session *s, int wait, int *exit_idx, float *score);
+int ee_exit_order(ee_session *s, int *order, float *scores);
+
+/* The paper's latency model (Experiments, table "Latency calculation"; notation table) and
+   its speed-up projection (Appendix "Speedup Projection Analysis", Eq. 9), fed with measured
+   times.  All times in milliseconds.
+     cloud autoregressive (AR):      2 T_c + n T_q
+     edge-cloud speculative (SD):    (n / tau) (2 T_c + gamma T_p + T_q)
+     with early exits (FSD):         (n / tau) (2 T_c + r gamma T_p + (1 - r) T_r + T_q)
+     c = T_p / T_q;  projected SD -> FSD speed-up (T_c = T_r = 0):  (gamma c + 1) / (r gamma c + 1)
+   EE_EINVAL for non-positive tau, T_q or n, gamma < 1, r outside [0, 1] or negative times.
+   Pure host arithmetic (double); needs no GPU. */
+typedef struct {
+    double T_p;   /* one forward pass of the draft model                          */
+    double T_q;   /* one forward pass (verify pass) of the target model           */
+    double T_c;   /* client <-> server communication latency, one way             */
+    double T_r;   /* thread synchronisation latency on a pre-draft cache hit      */
+    double tau;   /* tokens per draft-verify round: accepted + 1                  */
+    double r;     /* pre-draft cache miss rate                                    */
+    int32_t gamma, n;
+} ee_latency_params;
+typedef struct {
+    double ar_ms, sd_ms, fsd_ms;                       /* n tokens                  */
+    double ar_ms_per_token, sd_ms_per_token, fsd_ms_per_token;
+    double speedup_ar_to_sd, speedup_sd_to_fsd;
+    double c;                                          /* latency ratio T_p / T_q   */
+    double projected_sd_to_fsd;                        /* Eq. 9                     */
+} ee_latency;
+int ee_latency_model(const ee_latency_params *p, ee_latency *out);
 
 /* Milliseconds of GPU time from the start of the last pass to exit exit_idx's
    event (exit_idx in [0, n_exits)) or to the final event (exit_idx == n_exits).

@@ -20,7 +20,7 @@ EE_MAX_EXITS = 16
 EE_MAX_BATCH = 16
 EE_MAX_ROWS = 48
 
-EE_OK, EE_NOT_READY = 0, 1
+EE_OK, EE_NOT_READY, EE_DONE = 0, 1, 2
 EE_EINVAL, EE_ESTATE, EE_ECAPACITY, EE_EIO, EE_EFORMAT, EE_EDEVICE = -1, -2, -3, -4, -5, -6
 
 HOLD_LAST = 1
@@ -36,7 +36,7 @@ EXPORTS = [
     "ee_verify_batch", "ee_verify_static", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_session_option",
-    "ee_launch_times", "ee_debug_copy",
+    "ee_launch_times", "ee_debug_copy", "ee_exit_pop", "ee_exit_order", "ee_latency_model",
 ]
 
 
@@ -62,6 +62,16 @@ class VerifyResultC(ctypes.Structure):
                 ("exit_tokens", (ctypes.c_int32 * EE_MAX_M) * EE_MAX_EXITS),
                 ("device_status", ctypes.c_int32), ("reserved", ctypes.c_int32 * 15),
                 ("final_conf", ctypes.c_float * EE_MAX_M), ("exit_conf", (ctypes.c_float * EE_MAX_M) * EE_MAX_EXITS)]
+
+
+class LatencyParamsC(ctypes.Structure):
+    _fields_ = [("T_p", ctypes.c_double), ("T_q", ctypes.c_double), ("T_c", ctypes.c_double), ("T_r", ctypes.c_double),
+                ("tau", ctypes.c_double), ("r", ctypes.c_double), ("gamma", ctypes.c_int32), ("n", ctypes.c_int32)]
+
+
+class LatencyC(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_double) for k in ("ar_ms", "sd_ms", "fsd_ms", "ar_ms_per_token", "sd_ms_per_token", "fsd_ms_per_token",
+                                                "speedup_ar_to_sd", "speedup_sd_to_fsd", "c", "projected_sd_to_fsd")]
 
 
 _lib = None
@@ -108,6 +118,9 @@ def load_library():
     lib.ee_debug_mfma_layout.argtypes = [ci]
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_session_option.argtypes = [vp, ci, ci]
+    lib.ee_exit_pop.argtypes = [vp, ci, P(ci), P(ctypes.c_float)]
+    lib.ee_exit_order.argtypes = [vp, P(ci), P(ctypes.c_float)]
+    lib.ee_latency_model.argtypes = [P(LatencyParamsC), P(LatencyC)]
     lib.ee_debug_copy.argtypes = [ci, ctypes.c_size_t, ci]
     lib.ee_launch_times.argtypes = [vp, i32p, P(ctypes.c_float), ci, P(ci)]
     for name in EXPORTS:
@@ -256,6 +269,19 @@ class Session:
         _check(self._l.ee_debug_logits(self._h, head_idx, out.ctypes.data))
         return out
 
+    def ee_exit_pop(self, wait: bool = True):
+        """(status, exit index, score): status EE_OK, EE_NOT_READY or EE_DONE."""
+        idx, sc = ctypes.c_int(-1), ctypes.c_float(0.0)
+        rc = _check(self._l.ee_exit_pop(self._h, 1 if wait else 0, ctypes.byref(idx), ctypes.byref(sc)))
+        return rc, int(idx.value), float(sc.value)
+
+    def ee_exit_order(self):
+        """([exit index], [score]) in the order the sender's queue releases them."""
+        n = self._n_exits
+        order, sc = (ctypes.c_int * max(n, 1))(), (ctypes.c_float * max(n, 1))()
+        _check(self._l.ee_exit_order(self._h, order, sc))
+        return [int(order[i]) for i in range(n)], [float(sc[i]) for i in range(n)]
+
     def ee_session_option(self, option: int, value: int) -> None:
         _check(self._l.ee_session_option(self._h, option, value))
 
@@ -289,6 +315,15 @@ class Session:
         self.ee_verify(draft_tokens, exit_layers)
         self.ee_wait_final()
         return self.final_result()
+
+
+def ee_latency_model(T_p: float, T_q: float, T_c: float, tau: float, gamma: int = 4, n: int = 200, r: float = 1.0,
+                     T_r: float = 0.0) -> dict:
+    """The paper's AR / SD / FSD latency formulas and Eq. 9 (times in ms); plain marshalling."""
+    p = LatencyParamsC(T_p, T_q, T_c, T_r, tau, r, gamma, n)
+    out = LatencyC()
+    _check(load_library().ee_latency_model(ctypes.byref(p), ctypes.byref(out)))
+    return {k: getattr(out, k) for k, _ in LatencyC._fields_}
 
 
 def ee_debug_copy(device: int, nbytes: int, reps: int) -> None:

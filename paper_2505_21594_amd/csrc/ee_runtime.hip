@@ -84,6 +84,7 @@ struct ee_session {
     int att_splits_opt;              // EE_OPT_ATT_SPLITS (0: chosen per pass)
     bool scatter_pages;              // EE_OPT_SCATTER_PAGES
     int flight_row0;                 // first row of this session in the pass in flight
+    unsigned popped_mask;            // exits of the pass in flight that ee_exit_pop has handed out
     std::vector<hipEvent_t> lt_events;   // EE_TIME_LAUNCHES: event pairs around every launch of the pass
     std::vector<int> lt_codes;           // what each timed launch ran (EE_LAUNCH_* code)
     std::vector<void *> allocs;
@@ -1059,6 +1060,7 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
         s->flight_gamma = gamma;
         s->flight_exits = n_exits;
         s->flight_row0 = i * M;
+        s->popped_mask = 0;
         if (outs) outs[i] = s->result;
     }
     return EE_OK;
@@ -1144,6 +1146,94 @@ extern "C" int ee_query_final(ee_session *s)
     if (e == hipSuccess) return EE_OK;
     if (e == hipErrorNotReady) return EE_NOT_READY;
     return fail(EE_EDEVICE, "hipEventQuery: %s", hipGetErrorString(e));
+}
+
+// ------------------------------------------------------------------ sender queue, latency model
+
+// s^(e) of Alg. 2: the largest confidence among the rows the exit's result consists of
+static float exit_score(const ee_verify_result *r, int e)
+{
+    float sc = 0.f;
+    for (int i = 0; i <= r->exit_accept_len[e] && i < EE_MAX_M; ++i) sc = std::max(sc, r->exit_conf[e][i]);
+    return sc;
+}
+
+extern "C" int ee_exit_pop(ee_session *s, int wait, int *exit_idx, float *score)
+{
+    if (!s || !exit_idx) return fail(EE_EINVAL, "null argument");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_exit_pop: no verify pass was enqueued");
+    ee_session *lead = s->leader;
+    HIP_TRY(hipSetDevice(s->m->device));
+    for (;;) {
+        if (!s->in_flight || hipEventQuery(lead->ev_final) == hipSuccess) {  // the final result is there: Q_e is reset
+            s->popped_mask = ~0u;
+            return EE_DONE;
+        }
+        int best = -1, first_unpublished = -1;
+        float best_sc = -1.f;
+        for (int e = 0; e < s->flight_exits; ++e) {
+            if (s->popped_mask & (1u << e)) continue;
+            const hipError_t q = hipEventQuery(lead->ev_exit[e]);
+            if (q == hipSuccess) {
+                const float sc = exit_score(s->result, e);
+                if (sc > best_sc) {
+                    best_sc = sc;
+                    best = e;
+                }
+            } else if (q == hipErrorNotReady) {
+                if (first_unpublished < 0) first_unpublished = e;
+            } else {
+                return fail(EE_EDEVICE, "hipEventQuery: %s", hipGetErrorString(q));
+            }
+        }
+        if (best >= 0) {
+            s->popped_mask |= 1u << best;
+            *exit_idx = best;
+            if (score) *score = best_sc;
+            return EE_OK;
+        }
+        if (first_unpublished < 0) return EE_DONE;
+        if (!wait) return EE_NOT_READY;
+        HIP_TRY(hipEventSynchronize(lead->ev_exit[first_unpublished]));
+    }
+}
+
+extern "C" int ee_exit_order(ee_session *s, int *order, float *scores)
+{
+    if (!s || !order) return fail(EE_EINVAL, "null argument");
+    if (s->flight_gamma == 0) return fail(EE_ESTATE, "ee_exit_order: no verify pass was enqueued");
+    int rc = finish_flight(s);
+    if (rc != EE_OK) return rc;
+    const int n = s->flight_exits;
+    float sc[EE_MAX_EXITS];
+    for (int e = 0; e < n; ++e) {
+        sc[e] = exit_score(s->result, e);
+        order[e] = e;
+    }
+    std::stable_sort(order, order + n, [&](int a, int b) { return sc[a] > sc[b]; });  // ties: the earlier exit first
+    if (scores)
+        for (int i = 0; i < n; ++i) scores[i] = sc[order[i]];
+    return EE_OK;
+}
+
+extern "C" int ee_latency_model(const ee_latency_params *p, ee_latency *out)
+{
+    if (!p || !out) return fail(EE_EINVAL, "null argument");
+    if (!(p->tau > 0.0) || !(p->T_q > 0.0) || p->n < 1 || p->gamma < 1 || !(p->r >= 0.0 && p->r <= 1.0) || p->T_p < 0.0 ||
+        p->T_c < 0.0 || p->T_r < 0.0)
+        return fail(EE_EINVAL, "ee_latency_model: tau, T_q, n > 0, gamma >= 1, 0 <= r <= 1 and non-negative times are required");
+    const double n = (double)p->n, g = (double)p->gamma, rounds = n / p->tau;
+    out->ar_ms = 2.0 * p->T_c + n * p->T_q;
+    out->sd_ms = rounds * (2.0 * p->T_c + g * p->T_p + p->T_q);
+    out->fsd_ms = rounds * (2.0 * p->T_c + p->r * g * p->T_p + (1.0 - p->r) * p->T_r + p->T_q);
+    out->ar_ms_per_token = out->ar_ms / n;
+    out->sd_ms_per_token = out->sd_ms / n;
+    out->fsd_ms_per_token = out->fsd_ms / n;
+    out->speedup_ar_to_sd = out->ar_ms / out->sd_ms;
+    out->speedup_sd_to_fsd = out->sd_ms / out->fsd_ms;
+    out->c = p->T_p / p->T_q;
+    out->projected_sd_to_fsd = (g * out->c + 1.0) / (p->r * g * out->c + 1.0);
+    return EE_OK;
 }
 
 extern "C" int ee_pass_time_ms(ee_session *s, int exit_idx, float *ms)

@@ -473,3 +473,55 @@ def test_argmax_ties_go_to_the_lowest_id(model_dir, tiny_path, which):
         gs.free()
     finally:
         g.free()
+
+
+def test_sender_queue_order_and_pop(model_dir):
+    """Exit results leave the server in the order of their confidence score (Algorithm 2):
+    ee_exit_order against the oracle's ordering of its own confidences, and the invariants of
+    the live queue (ee_exit_pop): every exit at most once, only published ones, its score is the
+    one of the published result, EE_DONE at the end."""
+    from oracle import latency as lo
+    cfg = eegen.ModelConfig(n_layers=6, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                            exit_layers=(1, 2, 3, 4, 5))
+    p = f"{model_dir}/gpu_tiny_five_exits.bin"
+    eegen.write_model(p, cfg, 55, gains="uniform", std=0.08)   # wider logits: confidences well apart
+    g, o = ee.Model(p), eo.Model(p)
+    exits = [1, 2, 3, 4, 5]
+    try:
+        gs = g.session(96, max_gamma=4)
+        os_ = o.session(96)
+        prompt = eegen.prompt_tokens(56, 20, cfg.vocab)
+        fo, margin = oracle_prefill(os_, prompt)
+        check_first_token(gs, gs.ee_prefill(prompt), fo, margin, "queue")
+        for rnd in range(4):
+            drafts = eegen.corrupt_drafts(oracle_greedy(os_, 4), 0.3, cfg.vocab, 57, rnd)
+            ro = os_.verify(drafts, exits, commit=True, want_logits=True)
+            gs.ee_verify(drafts, exits)
+            popped = []
+            while True:
+                rc, e, sc = gs.ee_exit_pop(wait=True)
+                if rc == ee.EE_DONE:
+                    break
+                assert rc == ee.EE_OK and e not in popped and gs.ee_query_exit(e)
+                toks, delta = gs.exit_result(e)
+                assert sc == float(gs.exit_conf(e)[: delta + 1].max())
+                popped.append(e)
+            assert gs.ee_exit_pop(wait=False)[0] == ee.EE_DONE
+            gs.ee_wait_final()
+            rg = gs.final_result()
+            exempt, _ = check_pass(ro, rg, None, drafts, f"queue round {rnd}")
+            order_g, scores_g = gs.ee_exit_order()
+            order_o, scores_o = lo.sender_order(ro.exit_conf, ro.exit_accept_len)
+            assert sorted(order_g) == list(range(len(exits)))
+            assert scores_g == sorted(scores_g, reverse=True)
+            if not exempt:
+                np.testing.assert_allclose(scores_g, scores_o, rtol=1e-3)
+                gaps = np.diff(sorted(scores_o))
+                if gaps.size == 0 or gaps.min() > 1e-3 * max(scores_o):   # an order a rounding error cannot change
+                    assert order_g == order_o
+            if rg.accept_len != ro.accept_len or rg.next_token != ro.next_token:
+                gs.ee_kv_truncate(os_.kv_len)
+                gs.ee_set_pending(os_.pending)
+        gs.free()
+    finally:
+        g.free()
