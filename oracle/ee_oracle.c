@@ -40,6 +40,12 @@ struct eo_model {
     size_t map_bytes;
     const uint16_t *emb, *g_final, *w_lm;
     const uint16_t *g_exit[EO_MAX_EXITS];
+    /* exit-head adapters (n_ad bottlenecks of width ad_w each, A = n_ad * ad_w), per stored exit */
+    int n_ad, ad_w;
+    const uint16_t *ad_down[EO_MAX_EXITS];  /* [A][d]    */
+    const uint16_t *ad_bdown[EO_MAX_EXITS]; /* [A]       */
+    const uint16_t *ad_up[EO_MAX_EXITS];    /* [d][A]    */
+    const uint16_t *ad_bup[EO_MAX_EXITS];   /* [n_ad][d] */
     layer_w *layers;
 };
 
@@ -250,6 +256,23 @@ int eo_model_open(const char *path, eo_model **out)
     m->w_lm = take(b, &off, V * d);
     for (int i = 0; i < m->c.n_exits; ++i)
         m->g_exit[i] = take(b, &off, d);
+    {
+        uint32_t ad[2];
+        memcpy(ad, b + 208, sizeof ad);
+        m->n_ad = (int)ad[0];
+        m->ad_w = (int)ad[1];
+        if ((m->n_ad == 0) != (m->ad_w == 0) || m->n_ad < 0 || m->n_ad > 64 || m->ad_w < 0 || m->ad_w > 65536) {
+            eo_model_close(m);
+            return EO_EFORMAT;
+        }
+        const size_t A = (size_t)m->n_ad * (size_t)m->ad_w;
+        for (int i = 0; A && i < m->c.n_exits; ++i) {
+            m->ad_down[i] = take(b, &off, A * d);
+            m->ad_bdown[i] = take(b, &off, A);
+            m->ad_up[i] = take(b, &off, d * A);
+            m->ad_bup[i] = take(b, &off, (size_t)m->n_ad * d);
+        }
+    }
     if (align_up(off) > m->map_bytes) { eo_model_close(m); return EO_EFORMAT; }
     *out = m;
     return EO_OK;
@@ -268,6 +291,14 @@ int eo_model_config(const eo_model *m, eo_config *out)
     if (!m || !out) return EO_EINVAL;
     *out = m->c;
     return EO_OK;
+}
+
+/* index of the stored exit head after layer e, or -1 */
+static int exit_slot(const eo_model *m, int e)
+{
+    for (int i = 0; i < m->c.n_exits; ++i)
+        if (m->c.exit_layers[i] == e) return i;
+    return -1;
 }
 
 /* gain vector of the exit head after layer e, or NULL */
@@ -324,6 +355,36 @@ int eo_kv_truncate(eo_session *s, int new_len)
     if (!s || new_len < 0 || new_len > s->kv_len) return EO_EINVAL;
     s->kv_len = new_len; /* entries past new_len are stale and get overwritten */
     return EO_OK;
+}
+
+/* ---------- exit head with adapters ---------- */
+
+/* The paper's exit heads are "adapter layers after each layer" that connect the layer's
+   output to the shared LM head (Methodology, early-exit fine-tuning; Experimental Setup);
+   the trainable-parameter counts of its fine-tuning table equal three bias-carrying
+   bottlenecks of width 128 per layer.  Reading taken here: the n_ad bottlenecks act in
+   parallel on the layer's output and their results are added to it,
+       a = h + sum_j ( W_up,j . silu(W_down,j . h + b_down,j) + b_up,j ),
+   and the exit's logits are LMHead(RMSNorm(a; g_exit)).  The bottlenecks' rows are stored
+   one after the other (W_down [A][d], W_up [d][A], A = n_ad * width), so the sum over j is the
+   sum over all A hidden units.  h: [M][d] (left unchanged), a: [M][d]. */
+static void adapter_rows(const eo_model *m, int slot, const real *h, int M, real *a)
+{
+    const int d = m->c.d_model, A = m->n_ad * m->ad_w;
+    real *t = (real *)malloc((size_t)M * A * sizeof(real));
+    linear(m->ad_down[slot], A, d, h, M, t);
+    for (int i = 0; i < M; ++i)
+        for (int r = 0; r < A; ++r)
+            t[(size_t)i * A + r] = silu(t[(size_t)i * A + r] + bf16_val(m->ad_bdown[slot][r]));
+    linear(m->ad_up[slot], d, A, t, M, a);
+    for (int i = 0; i < M; ++i)
+        for (int c = 0; c < d; ++c) {
+            real b = 0;
+            for (int j = 0; j < m->n_ad; ++j)
+                b += bf16_val(m->ad_bup[slot][(size_t)j * d + c]);
+            a[(size_t)i * d + c] = h[(size_t)i * d + c] + a[(size_t)i * d + c] + b;
+        }
+    free(t);
 }
 
 /* ---------- one pass over M rows with the KV cache ---------- */
@@ -421,7 +482,13 @@ static void forward_rows(eo_session *s, real *h, int P, int M, const head_req *h
         /* LM head on this layer's hidden state where requested */
         for (int e = 0; hr && e < hr->n_heads; ++e) {
             if (hr->layer[e] != l) continue;
-            rmsnorm(h, hr->gain[e], M, d, eps, x);
+            const int slot = l < L ? exit_slot(m, l) : -1;
+            if (slot >= 0 && m->n_ad > 0) {
+                adapter_rows(m, slot, h, M, o);
+                rmsnorm(o, hr->gain[e], M, d, eps, x);
+            } else {
+                rmsnorm(h, hr->gain[e], M, d, eps, x);
+            }
             linear(m->w_lm, V, d, x, M, hr->logits[e]);
         }
     }
@@ -638,7 +705,12 @@ int eo_full_logits(const eo_model *m, const uint16_t *emb_bf16, int n_emb, const
         for (size_t i = 0; i < Td; ++i)
             h[i] += o[i];
     }
-    rmsnorm(h, gain, T, d, eps, x);
+    if (exit_layer != 0 && m->n_ad > 0) {
+        adapter_rows(m, exit_slot(m, exit_layer), h, T, o);
+        rmsnorm(o, gain, T, d, eps, x);
+    } else {
+        rmsnorm(h, gain, T, d, eps, x);
+    }
     real *z = (real *)malloc((size_t)T * V * sizeof(real));
     linear(m->w_lm, V, d, x, T, z);
     copy_trace(logits_out, z, (size_t)T * V);

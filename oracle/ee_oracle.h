@@ -33,7 +33,7 @@
 extern "C" {
 #endif
 
-#define EO_MAX_EXITS 16
+#define EO_MAX_EXITS 40
 #define EO_MAX_M 64
 
 #define EO_OK 0

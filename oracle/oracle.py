@@ -14,7 +14,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-EO_MAX_EXITS = 16
+EO_MAX_EXITS = 40
 EO_MAX_M = 64
 HOLD_LAST = 1
 

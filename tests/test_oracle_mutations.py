@@ -43,6 +43,14 @@ MUTATIONS = {
     "confidence_of_wrong_head": ("double *conf = e < n_exits ? out->exit_conf[e] : out->final_conf;",
                                  None),
 }
+MUTATIONS["adapter_residual_dropped"] = ("a[(size_t)i * d + c] = h[(size_t)i * d + c] + a[(size_t)i * d + c] + b;",
+                                        "a[(size_t)i * d + c] = a[(size_t)i * d + c] + b;")
+MUTATIONS["adapter_down_bias_dropped"] = ("silu(t[(size_t)i * A + r] + bf16_val(m->ad_bdown[slot][r]))", "silu(t[(size_t)i * A + r])")
+MUTATIONS["adapter_only_first_up_bias"] = ("for (int j = 0; j < m->n_ad; ++j)\n                b +=", "for (int j = 0; j < 1; ++j)\n                b +=")
+MUTATIONS["adapter_no_activation"] = ("t[(size_t)i * A + r] = silu(t[(size_t)i * A + r] + bf16_val(m->ad_bdown[slot][r]));",
+                                     "t[(size_t)i * A + r] = t[(size_t)i * A + r] + bf16_val(m->ad_bdown[slot][r]);")
+MUTATIONS["adapter_on_final_head"] = ("const int slot = l < L ? exit_slot(m, l) : -1;", "const int slot = l < L ? exit_slot(m, l) : 0;")
+MUTATIONS["adapter_of_wrong_exit"] = ("adapter_rows(m, slot, h, M, o);\n                rmsnorm(o, hr->gain[e]", "adapter_rows(m, 0, h, M, o);\n                rmsnorm(o, hr->gain[e]")
 MUTATIONS["q_k_weights_swapped"] = ("linear(w->wq, d, d, x, M, q);\n        linear(w->wk, d, d, x, M, k);",
                                     "linear(w->wk, d, d, x, M, q);\n        linear(w->wq, d, d, x, M, k);")
 MUTATIONS["confidence_of_wrong_head"] = ("conf[i] = max_softmax(hr.logits[e] + (size_t)i * V, V);",

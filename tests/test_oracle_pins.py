@@ -470,3 +470,76 @@ def test_error_paths(tiny):
     assert e.value.code == eo.EO_ECAPACITY
     with pytest.raises(eo.OracleError):
         eo.Model("/nonexistent/file")
+
+
+# ---------------------------------------------------------------- exit heads with adapters
+
+AD_CFG = eegen.ModelConfig(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                           exit_layers=(1, 2, 3), n_adapters=3, adapter_width=16)
+
+
+def test_adapter_parameter_counts_match_the_papers_table():
+    """The fine-tuning table's trainable-parameter counts fix the adapters' shape: three
+    bias-carrying bottlenecks of width 128 after each of the 32 / 40 layers (values in
+    tests/golden/adapter_parameter_counts.txt)."""
+    import os
+    gold = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "adapter_parameter_counts.txt")):
+        t = line.split()
+        if t and not t[0].startswith("#"):
+            gold[t[0]] = int(t[1])
+    for base, key in ((eegen.LLAMA7B, "llama2_7b"), (eegen.LLAMA13B, "vicuna_13b")):
+        cfg = eegen.ModelConfig(base.n_layers, base.d_model, base.n_heads, base.head_dim, base.d_ffn, base.vocab,
+                                tuple(range(1, base.n_layers)), n_adapters=3, adapter_width=128)
+        assert eegen.adapter_parameters(cfg, base.n_layers) == gold[key]
+        # and the file the generator writes holds exactly these tensors per exit head
+        table, _ = eegen.tensor_table(cfg)
+        per_exit = sum(int(np.prod(shape)) for name, (_, shape) in table.items() if name in ("ad_down1", "ad_bdown1", "ad_up1", "ad_bup1"))
+        assert per_exit * base.n_layers == gold[key]
+
+
+def test_adapter_with_zero_output_is_the_plain_exit_head(model_dir):
+    """W_up = 0 and b_up = 0 make every adapter add nothing: the exit head is then RMSNorm +
+    LM head on the layer's output, i.e. the logits of the same model without adapters."""
+    plain = eegen.ModelConfig(AD_CFG.n_layers, AD_CFG.d_model, AD_CFG.n_heads, AD_CFG.head_dim, AD_CFG.d_ffn, AD_CFG.vocab,
+                              AD_CFG.exit_layers)
+    pa = _mk(model_dir, "ad_zero_up", cfg=AD_CFG, gains="uniform", zero=("ad_up*", "ad_bup*"))
+    pp = _mk(model_dir, "ad_plain", cfg=plain, gains="uniform")
+    ma, mp = eo.Model(pa), eo.Model(pp)
+    prompt, drafts = eegen.prompt_tokens(71, 9, plain.vocab), eegen.prompt_tokens(72, 4, plain.vocab)
+    out = []
+    for m in (ma, mp):
+        s = m.session(32)
+        s.prefill(prompt)
+        out.append(s.verify(drafts, [1, 2, 3], commit=False, want_logits=True))
+    assert np.array_equal(out[0].logits, out[1].logits)
+    assert np.array_equal(out[0].exit_tokens, out[1].exit_tokens)
+
+
+@pytest.mark.parametrize("real,tol", [("f64", 1e-9), ("f32", 2e-4)])
+def test_adapter_exit_head_against_numpy(model_dir, real, tol):
+    """a = h + sum_j (W_up,j silu(W_down,j h + b_down,j) + b_up,j), z = W_lm RMSNorm(a; g_exit), restated
+    in float64 numpy on the layer outputs the oracle reports; the final head stays without adapter."""
+    path = _mk(model_dir, "ad_full", cfg=AD_CFG, gains="uniform", std=0.05)
+    m = eo.Model(path, real=real)
+    t = eegen.open_tensors(path)
+    f = lambda name: bf16_to_f32(t[name]).astype(np.float64)
+    prompt, drafts = eegen.prompt_tokens(73, 11, AD_CFG.vocab), eegen.prompt_tokens(74, 5, AD_CFG.vocab)
+    s = m.session(32)
+    s.prefill(prompt)
+    r = s.verify(drafts, [1, 3], commit=False, want_logits=True, want_trace=True)
+    eps = float(m.rms_eps)
+    for idx, e in enumerate((1, 3)):
+        h = r.trace["h"][e]                                    # output of layer e, [M][d]
+        pre = h @ f(f"ad_down{e}").T + f(f"ad_bdown{e}")
+        act = pre / (1.0 + np.exp(-pre))
+        a = h + act @ f(f"ad_up{e}").T + f(f"ad_bup{e}").sum(0)
+        z = _rms(a, f(f"g_exit{e}"), eps) @ f("w_lm").T
+        np.testing.assert_allclose(r.logits[idx], z, atol=tol, rtol=0)
+        # the adapter really changes the logits (the pin would be blind otherwise)
+        assert np.abs(z - _rms(h, f(f"g_exit{e}"), eps) @ f("w_lm").T).max() > 1e-2
+    zf = _rms(r.trace["h"][AD_CFG.n_layers], f("g_final"), eps) @ f("w_lm").T
+    np.testing.assert_allclose(r.logits[2], zf, atol=tol, rtol=0)
+    # brute force without a cache goes through the same head
+    full = m.full_logits(list(prompt) + [s.pending] + list(drafts), exit_layer=3)
+    np.testing.assert_allclose(full[-6:], r.logits[1], atol=max(tol, 1e-5), rtol=0)
