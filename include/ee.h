@@ -19,6 +19,11 @@
  *   - Every exit verifies the drafts on its own logits: Methodology Step 2, Eq. 5.
  *   - Exit results leave the server as soon as they exist: Methodology Step 3;
  *     Appendix "System Design", server LISTENER/SENDER (Algorithm 2).
+ * Exit heads: RMSNorm with the exit's gain, then the shared LM head; when the model file carries
+ * adapters (the paper's "adapter layers after each layer" that connect a layer to the LM head;
+ * Methodology, early-exit fine-tuning), the layer's output first goes through them:
+ *   a = h + sum_j (W_up,j silu(W_down,j h + b_down,j) + b_up,j)   (bottlenecks in parallel),
+ * and the head is evaluated on a.  The final head has no adapter.
  * Verification is greedy exact-match (the temperature-0 case of the paper's
  * criterion): draft j is accepted iff it equals the argmax at row j-1 and all
  * earlier drafts were accepted.  Argmax ties go to the lowest token id.
@@ -48,7 +53,7 @@ extern "C" {
 #endif
 
 #define EE_MAX_M 16      /* rows per session and pass: gamma + 1 <= EE_MAX_M          */
-#define EE_MAX_EXITS 16  /* exit heads per pass                                       */
+#define EE_MAX_EXITS 40  /* exit heads per pass (the paper runs 31 / 39: one after every layer but the last) */
 #define EE_MAX_BATCH 16  /* sessions per ee_verify_batch                              */
 #define EE_MAX_ROWS 48   /* rows per pass over all sessions of a batch                */
 
@@ -78,6 +83,8 @@ typedef struct {
     int32_t n_exits;                       /* exit gains stored in the model            */
     int32_t exit_layers[EE_MAX_EXITS];     /* 1-based: exit e sits after layer e        */
     float rope_base, rms_eps;
+    int32_t n_adapters, adapter_width;     /* bottleneck adapters per exit head and their width
+                                              (0: exit heads are RMSNorm + LM head only)  */
     int32_t max_rows;                      /* rows per pass this instance was laid out for */
     int32_t n_workgroups;                  /* persistent grid size (= compute units)    */
 } ee_model_config;
@@ -249,10 +256,17 @@ int ee_device_synchronize(int device);
      (the default).  A value the context or the scratch cannot take is raised / lowered to
      the nearest that works.
    EE_OPT_SCATTER_PAGES: 1 = hand KV pages out in descending order from the next ee_prefill
-     on, so that a session's pages are not consecutive and every lookup goes through the page
-     table (a fresh session's pages are consecutive and the kernels then skip the lookup). */
+     on, so that the pages of a session are not consecutive and every lookup goes through the page
+     table (the pages of a fresh session are consecutive and the kernels then skip the lookup).
+   EE_OPT_HEAD_BATCH: exit heads evaluated by one launch of the LM head (default 1).  With k > 1
+     every exit still deposits its head input when its layer is done, but the LM head matrix is
+     streamed once for k consecutive exits (as many as the max_rows of the model allow) and their
+     results are published together after the last of them: less traffic when many exits are
+     active (the paper runs one after every layer), later results for the earlier exits of a
+     group. */
 #define EE_OPT_ATT_SPLITS 1
 #define EE_OPT_SCATTER_PAGES 2
+#define EE_OPT_HEAD_BATCH 3
 int ee_session_option(ee_session *s, int option, int value);
 
 /* Measurement (EE_TIME_LAUNCHES sessions, pass led by `s`): for every kernel launch of the
@@ -265,8 +279,10 @@ int ee_session_option(ee_session *s, int option, int value);
 #define EE_LAUNCH_DN 3      /* down projection + residual + next norm inputs             */
 #define EE_LAUNCH_HEAD 4    /* exit or final head: norm + LM head + argmax, accept rule,
                                publication, KV commit                                    */
-#define EE_LAUNCH_ATT 5     /* attention over the paged KV cache                         */
-#define EE_LAUNCH_EMBED 6   /* embedding gather                                          */
+#define EE_LAUNCH_ADAPTER_DOWN 5 /* exit-head adapters: hidden units                     */
+#define EE_LAUNCH_ADAPTER_UP 6   /* exit-head adapters: output + residual + head norm input */
+#define EE_LAUNCH_ATT 8     /* attention over the paged KV cache                         */
+#define EE_LAUNCH_EMBED 7   /* embedding gather                                          */
 int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, int *n_launches);
 
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the

@@ -16,7 +16,7 @@ import numpy as np
 from . import build as _build
 
 EE_MAX_M = 16
-EE_MAX_EXITS = 16
+EE_MAX_EXITS = 40
 EE_MAX_BATCH = 16
 EE_MAX_ROWS = 48
 
@@ -27,8 +27,8 @@ HOLD_LAST = 1
 KEEP_LOGITS = 1
 NO_AUTOCOMMIT = 2
 TIME_LAUNCHES = 16
-OPT_ATT_SPLITS, OPT_SCATTER_PAGES = 1, 2
-LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "att", "embed")
+OPT_ATT_SPLITS, OPT_SCATTER_PAGES, OPT_HEAD_BATCH = 1, 2, 3
+LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "adapter_down", "adapter_up", "embed", "att")
 
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
@@ -51,6 +51,7 @@ class ModelConfigC(ctypes.Structure):
                 ("head_dim", ctypes.c_int32), ("d_ffn", ctypes.c_int32), ("vocab", ctypes.c_int32),
                 ("n_exits", ctypes.c_int32), ("exit_layers", ctypes.c_int32 * EE_MAX_EXITS),
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float),
+                ("n_adapters", ctypes.c_int32), ("adapter_width", ctypes.c_int32),
                 ("max_rows", ctypes.c_int32), ("n_workgroups", ctypes.c_int32)]
 
 

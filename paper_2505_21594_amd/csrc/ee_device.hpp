@@ -84,7 +84,7 @@ __host__ __device__ inline void unit_range(int U, int nwg, int g, int &u0, int &
 }
 
 enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };
-enum GemmKind { G_QKV = 0, G_O = 1, G_GU = 2, G_DN = 3, G_HEAD = 4 };
+enum GemmKind { G_QKV = 0, G_O = 1, G_GU = 2, G_DN = 3, G_HEAD = 4, G_AD = 5, G_AU = 6, G_KINDS = 7 };  // AD / AU: an exit head's adapter, down and up
 enum StageType { ST_EMBED = 0, ST_GEMM = 1, ST_ATT = 2, ST_ACCEPT = 3, ST_NONE = 4 };
 
 struct ModelDev {
@@ -92,10 +92,11 @@ struct ModelDev {
     float eps, att_scale;
     int Kpad_d, Kpad_F;                  // K rounded up to 32
     int rows_max;
-    GemmPlan plan[5];                    // indexed by GemmKind: QKV, O, GU, DN, HEAD (host side; a launch gets its own by value)
-    // tiled weights: one allocation per GEMM kind, layer l at w[kind] + l * wstride[kind] (uint4 units)
-    const uint4 *w[5];
-    long long wstride[5];
+    GemmPlan plan[G_KINDS];              // indexed by GemmKind (host side; a launch gets its own by value)
+    // tiled weights: one allocation per GEMM kind, layer l (adapters: stored exit l) at w[kind] + l * wstride[kind] (uint4 units)
+    const uint4 *w[G_KINDS];
+    long long wstride[G_KINDS];
+    int A, Kpad_A;                       // hidden units of an exit head's adapters (all bottlenecks together; 0: none), rounded up to 32
     const float *g_attn, *g_ffn;         // [L][d]
     const float *g_final;
     const uint16_t *emb;                 // [V][d] bf16, row-major
@@ -121,9 +122,13 @@ struct Scratch {
     // GEMM inputs as two bf16 terms each (x = hi + lo up to ~16 mantissa bits), written by the
     // stage that produces them, k-tile-major: [k-tile][term][row of the pass][32]
     uint16_t *xn;        // [Kpad_d/32][2][rows][32]  gain * h for the next QKV or gate/up GEMM
-    uint16_t *xh;        // [Kpad_d/32][2][rows][32]  head_gain * h for the LM head
+    uint16_t *xh;        // [Kpad_d/32][2][head rows][32]  head_gain * (h, or h after the adapters) for the LM head; the rows
+                         // of all exits that share one launch of the head, exit after exit
     uint16_t *attn;      // [Kpad_d/32][2][rows][32]  attention output
     uint16_t *u;         // [Kpad_F/32][2][rows][32]  silu(gate)*up
+    uint16_t *xa;        // [Kpad_d/32][2][rows][32]  h itself: input of an exit head's adapters
+    uint16_t *t;         // [Kpad_A/32][2][rows][32]  the adapters' hidden units after the activation
+    float *ss_h;         // [nwg][rows_max]      partial sums of squares of the LM-head input's rows (head rows)
     float *ss_a;         // [nwg][rows_max]      partial sums of h^2 after the FFN block / embedding
     float *ss_f;         // [nwg][rows_max]      partial sums of h^2 after the attention block
     float *att_part;     // [items][ATT_ROWS][hd+2] attention partials (only when the position range is split)
@@ -150,8 +155,14 @@ struct PassArgs {
     int pf_pos0;                         // prefill: position of row 0
     int layer_begin, layer_end;          // layers [begin, end) of this segment, 0-based
     int do_embed;
-    int head_kind, head_idx;
+    int head_kind, head_idx;             // head_idx: result slot of the (first) head of this segment's head launch
     const float *head_gain;
+    int n_heads;                         // exit heads evaluated by the head launch (their rows follow each other)
+    int head_rows;                       // rows of the head launch: n_heads * rows
+    int head_row0;                       // first head row this segment's exit writes (its position in the group)
+    int head_stage;                      // 1: this segment ends with the head launch (else its exit only deposits its rows)
+    int adapter;                         // 1: the exit has adapters (stages AD, AU between the last layer and the head)
+    const float *ad_bdown, *ad_bup;      // adapter biases: [A] and [d] (the bottlenecks' output biases summed)
     int commit, keep_logits;
     int fuse_accept;                     // the head launch also runs the accept step (in the workgroup that finishes last)
     int att_splits;

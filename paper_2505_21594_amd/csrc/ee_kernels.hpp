@@ -298,10 +298,13 @@ __device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
     return v > bv || (v == bv && i < bi);
 }
 
-struct GemmEpi {           // what the O / DN epilogue produces besides h
+struct GemmEpi {           // what the O / DN / AU epilogue produces besides h
     const float *gain_xn;  // gain of the next GEMM input (xn), or nullptr
-    const float *gain_xh;  // gain of the LM-head input (xh), or nullptr
-    float *ss_out;         // [nwg][rows_max] partial sums of h^2
+    const float *gain_xh;  // gain of the LM-head input (xh, at the exit's head rows), or nullptr
+    float *ss_out;         // [nwg][rows_max] partial sums of h^2, or nullptr
+    float *ss_head;        // [nwg][rows_max] partial sums of squares of the LM-head input's rows (at the head rows), or nullptr
+    const float *bias;     // AD / AU: bias per output column
+    int xa_out;            // DN: also emit h itself as the adapters' input (xa)
 };
 
 // Epilogue of one chunk of gn n-tiles starting at n-tile nt_first: sum the streaming waves'
@@ -351,13 +354,29 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
         const int n = (nt_first + ntg) * 16 + qd * 4;  // four consecutive output columns
-        if (kind == G_O || kind == G_DN) {
+        if (kind == G_AD) {
+            // hidden units of the exit head's adapters: silu(W_down . h + b_down)
+            if (n < md.A) {
+                const f32x4_t b = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+                float pre[4] = {S.x + b[0], S.y + b[1], S.z + b[2], S.w + b[3]}, o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = pre[e] / (1.0f + __expf(-pre[e]));
+                store_split4(a.sc.t, rows, m, n, o);
+            }
+        } else if (kind == G_O || kind == G_DN || kind == G_AU) {
             float sq = 0.f;
             if (n < md.d) {
                 EE_GLOBAL f32x4_t *hp = reinterpret_cast<EE_GLOBAL f32x4_t *>(as_global_mut(a.sc.h) + (size_t)m * md.d + n);
                 const f32x4_t hv = *hp;
                 float v[4] = {hv[0] + S.x, hv[1] + S.y, hv[2] + S.z, hv[3] + S.w};
-                *hp = (f32x4_t){v[0], v[1], v[2], v[3]};
+                if (kind == G_AU) {  // a side branch: a = h + W_up . t + b_up feeds the exit's LM head, h stays as it is
+                    const f32x4_t b = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += b[e];
+                } else {
+                    *hp = (f32x4_t){v[0], v[1], v[2], v[3]};
+                }
+                if (ep.xa_out) store_split4(a.sc.xa, rows, m, n, v);
                 sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
                 if (ep.gain_xn) {
                     const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xn + n));
@@ -367,7 +386,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                 if (ep.gain_xh) {
                     const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xh + n));
                     float x[4] = {v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]};
-                    store_split4(a.sc.xh, rows, m, n, x);
+                    store_split4(a.sc.xh, a.head_rows, a.head_row0 + m, n, x);
                 }
             }
             zbuf[idx] = sq;  // (ntg, m, quad) order
@@ -419,14 +438,15 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                 zr[e] = z[e];
             }
             if (a.keep_logits) {
-                EE_GLOBAL float *keep = as_global_mut(a.sc.logits) + ((size_t)a.head_idx * md.rows_max + m) * md.V;
+                const int per_head = a.n_sess * a.M, hj = m / per_head;  // the launch's rows: head after head
+                EE_GLOBAL float *keep = as_global_mut(a.sc.logits) + ((size_t)(a.head_idx + hj) * md.rows_max + (m - hj * per_head)) * md.V;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if (n + e < md.V) keep[n + e] = z[e];
             }
         }
     }
-    if (kind == G_O || kind == G_DN) {
+    if (kind == G_O || kind == G_DN || kind == G_AU) {
         lds_barrier();
         if (tid < rows) {  // this chunk's sum of squares per row, fixed order
             float t = 0.f;
@@ -663,7 +683,8 @@ __device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int la
         lds_barrier();
     }
     // what the workgroup hands to the following launch
-    if ((kind == G_O || kind == G_DN) && tid < rows) as_global_mut(ep.ss_out)[(size_t)blockIdx.x * md.rows_max + tid] = mi.rowss[tid];
+    if (ep.ss_out && tid < rows) as_global_mut(ep.ss_out)[(size_t)blockIdx.x * md.rows_max + tid] = mi.rowss[tid];
+    if (ep.ss_head && tid < rows) as_global_mut(ep.ss_head)[(size_t)blockIdx.x * md.rows_max + a.head_row0 + tid] = mi.rowss[tid];
     if (kind == G_HEAD && tid < rows) {  // device-scope stores: the accept step may run in another workgroup of this launch
         store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(mi.bestv[tid]), (unsigned)mi.besti[tid]));
         store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, mi.sume[tid]);
@@ -992,7 +1013,7 @@ __device__ __forceinline__ int2 load_cand(const int2 *p)
 __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
 {
     const ModelDev &md = a.mdv;
-    const int rows = a.rows, M = a.M;
+    const int rows = a.rows, M = a.M;  // rows of the head launch: head after head, session after session, M rows each
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int *tok = reinterpret_cast<int *>(lds);
     float *conf = reinterpret_cast<float *>(lds) + EE_MAX_ROWS;
@@ -1032,17 +1053,17 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
         }
     }
     __syncthreads();
-    const int s = threadIdx.x;
-    if (s < a.n_sess) {
+    // one thread per (head of this launch, session)
+    if ((int)threadIdx.x < a.n_heads * a.n_sess) {
+        const int hj = threadIdx.x / a.n_sess, s = threadIdx.x - hj * a.n_sess, head = a.head_idx + hj;
         const SessDev &sd = a.sess[s];
         ee_verify_result *res = sd.result;
-        const int *t = tok + s * M;
-        const float *cf = conf + s * M;
-        const int dev_err = 0;
+        const int *t = tok + (hj * a.n_sess + s) * M;
+        const float *cf = conf + (hj * a.n_sess + s) * M;
         if (a.head_kind == HEAD_PREFILL) {
             int last = t[M - 1];
             res->next_token = last;
-            res->device_status = dev_err;
+            res->device_status = 0;
             sd.state[1] = last;
         } else {
             const int gamma = M - 1;
@@ -1055,10 +1076,10 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
                 if (delta == i && i < gamma && dr[i] == t[i]) delta = i + 1;
             if (a.head_kind == HEAD_EXIT) {
                 for (int i = 0; i < M; ++i) {
-                    res->exit_tokens[a.head_idx][i] = t[i];
-                    res->exit_conf[a.head_idx][i] = cf[i];
+                    res->exit_tokens[head][i] = t[i];
+                    res->exit_conf[head][i] = cf[i];
                 }
-                res->exit_accept_len[a.head_idx] = delta;
+                res->exit_accept_len[head] = delta;
             } else {
                 for (int i = 0; i < M; ++i) {
                     res->final_tokens[i] = t[i];
@@ -1066,7 +1087,7 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
                 }
                 res->accept_len = delta;
                 res->next_token = t[delta];
-                res->device_status = dev_err;
+                res->device_status = 0;
                 if (a.commit) {
                     sd.state[0] = sd.state[0] + delta + 1;
                     sd.state[1] = t[delta];
@@ -1111,9 +1132,15 @@ __device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
         return sd;
     }
     idx -= per_layer * nl;
-    if (a.head_kind != HEAD_NONE && idx == 0) {
-        sd.type = ST_GEMM;
-        sd.kind = G_HEAD;
+    if (a.head_kind != HEAD_NONE) {  // [AD AU] [HEAD]
+        const int n_ad = a.adapter ? 2 : 0;
+        if (idx < n_ad) {
+            sd.type = ST_GEMM;
+            sd.kind = G_AD + idx;
+        } else if (idx == n_ad && a.head_stage) {
+            sd.type = ST_GEMM;
+            sd.kind = G_HEAD;
+        }
     }
     return sd;
 }
@@ -1125,21 +1152,36 @@ __device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
     case G_O: return GemmIn{a.sc.attn, nullptr};
     case G_GU: return GemmIn{a.sc.xn, a.sc.ss_f};
     case G_DN: return GemmIn{a.sc.u, nullptr};
-    default: return GemmIn{a.sc.xh, a.sc.ss_a};
+    case G_AD: return GemmIn{a.sc.xa, nullptr};
+    case G_AU: return GemmIn{a.sc.t, nullptr};
+    default: return GemmIn{a.sc.xh, a.sc.ss_h};
     }
 }
 
 __device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int layer)
 {
     const ModelDev &md = a.mdv;
-    GemmEpi ep = {nullptr, nullptr, nullptr};
+    GemmEpi ep = {nullptr, nullptr, nullptr, nullptr, nullptr, 0};
     if (kind == G_O) {
         ep.gain_xn = md.g_ffn + (size_t)layer * md.d;
         ep.ss_out = a.sc.ss_f;
     } else if (kind == G_DN) {
         if (layer + 1 < md.L) ep.gain_xn = md.g_attn + (size_t)(layer + 1) * md.d;
-        if (layer + 1 == a.layer_end && a.head_kind != HEAD_NONE) ep.gain_xh = a.head_gain;
+        if (layer + 1 == a.layer_end && a.head_kind != HEAD_NONE) {
+            if (a.adapter) {
+                ep.xa_out = 1;                 // the exit's adapters come first
+            } else {
+                ep.gain_xh = a.head_gain;      // the LM head's input rows and their sums of squares
+                ep.ss_head = a.sc.ss_h;
+            }
+        }
         ep.ss_out = a.sc.ss_a;
+    } else if (kind == G_AD) {
+        ep.bias = a.ad_bdown;
+    } else if (kind == G_AU) {
+        ep.bias = a.ad_bup;
+        ep.gain_xh = a.head_gain;
+        ep.ss_head = a.sc.ss_h;
     }
     return ep;
 }

@@ -50,6 +50,9 @@ struct ee_model {
     ModelDev host_md;            // the descriptor the launches carry by value
     std::vector<void *> allocs;  // every device allocation of the model
     const float *g_exit[EE_MAX_EXITS];
+    // exit-head adapters (per stored exit): biases of the hidden units and the summed output biases
+    const float *ad_bdown[EE_MAX_EXITS];
+    const float *ad_bup[EE_MAX_EXITS];
 };
 
 struct ee_session {
@@ -82,9 +85,10 @@ struct ee_session {
     Scratch sc;
     int att_items_cap;               // attention work items the partials buffer has room for
     int att_splits_opt;              // EE_OPT_ATT_SPLITS (0: chosen per pass)
+    int head_batch;                  // EE_OPT_HEAD_BATCH: exit heads per launch of the LM head
     bool scatter_pages;              // EE_OPT_SCATTER_PAGES
     int flight_row0;                 // first row of this session in the pass in flight
-    unsigned popped_mask;            // exits of the pass in flight that ee_exit_pop has handed out
+    unsigned long long popped_mask;  // exits of the pass in flight that ee_exit_pop has handed out
     std::vector<hipEvent_t> lt_events;   // EE_TIME_LAUNCHES: event pairs around every launch of the pass
     std::vector<int> lt_codes;           // what each timed launch ran (EE_LAUNCH_* code)
     std::vector<void *> allocs;
@@ -270,8 +274,16 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         return fail(EE_EFORMAT, "ee_model_load: head_dim %d unsupported (64 or 128)", c.head_dim);
     if (c.d_model % 16 != 0 || c.d_ffn % 2 != 0)
         return fail(EE_EFORMAT, "ee_model_load: d_model must be a multiple of 16, d_ffn even");
-    uint32_t ex[EE_MAX_EXITS];
+    uint32_t ex[EE_MAX_EXITS], ad[2];
+    static_assert(EE_MAX_EXITS == 40, "the header's exit table has 40 entries");
     memcpy(ex, b + 48, sizeof ex);
+    memcpy(ad, b + 208, sizeof ad);
+    const int n_ad = (int)ad[0], ad_w = (int)ad[1];
+    if ((n_ad == 0) != (ad_w == 0) || n_ad < 0 || n_ad > 64 || ad_w < 0 || ad_w > 4096 || (n_ad * ad_w) % 16 != 0)
+        return fail(EE_EFORMAT, "ee_model_load: bad adapter shape %d x %d (the hidden units together must be a multiple of 16)", n_ad, ad_w);
+    const size_t A = (size_t)n_ad * (size_t)ad_w;
+    c.n_adapters = n_ad;
+    c.adapter_width = ad_w;
     for (int i = 0; i < c.n_exits; ++i) {
         c.exit_layers[i] = (int)ex[i];
         if (c.exit_layers[i] < 1 || c.exit_layers[i] >= c.n_layers || (i > 0 && c.exit_layers[i] <= c.exit_layers[i - 1]))
@@ -306,6 +318,16 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     const uint16_t *w_lm = take(V * d);
     const uint16_t *g_exit_src[EE_MAX_EXITS];
     for (int i = 0; i < c.n_exits; ++i) g_exit_src[i] = take(d);
+    struct AdapterSrc {
+        const uint16_t *down, *bdown, *up, *bup;
+    };
+    std::vector<AdapterSrc> ads((size_t)(A ? c.n_exits : 0));
+    for (auto &x : ads) {
+        x.down = take(A * d);
+        x.bdown = take(A);
+        x.up = take(d * A);
+        x.bup = take((size_t)n_ad * d);
+    }
     if (off > fm.n) return fail(EE_EFORMAT, "ee_model_load: %s is truncated (%zu < %zu bytes)", path, fm.n, off);
 
     int n_dev = 0;
@@ -337,6 +359,8 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.Kpad_d = (int)align_up(d, 32);
     md.Kpad_F = (int)align_up(F, 32);
     md.rows_max = max_rows;
+    md.A = (int)A;
+    md.Kpad_A = (int)align_up(A, 32);
     if (c.d_ffn % 16 != 0) {
         ee_model_free(m);
         return fail(EE_EFORMAT, "ee_model_load: d_ffn must be a multiple of 16");
@@ -354,8 +378,10 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg);
     md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1, m->nwg);
     md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1, m->nwg);
+    md.plan[G_AD] = make_plan(A ? (int)A : 16, c.d_model, 1, m->nwg);
+    md.plan[G_AU] = make_plan(c.d_model, A ? (int)A : 32, 1, m->nwg);
     m->lds_budget = lds_cap / 256 * 256;   // the whole block: more than half of it also keeps a compute unit to one workgroup
-    for (int k = 0; k < 5; ++k) {
+    for (int k = 0; k < G_KINDS; ++k) {
         StageLds ly;
         if (!plan_lds(md.plan[k], max_rows, m->lds_budget, ly)) {
             ee_model_free(m);
@@ -387,7 +413,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
 
     int rc = EE_OK;
     uint16_t *tmp = nullptr;
-    size_t tmp_elems = std::max({V * d, 3 * d * d, 2 * F * d});
+    size_t tmp_elems = std::max({V * d, 3 * d * d, 2 * F * d, A * d});
     void *tmp_raw = nullptr;
     if (hipMalloc(&tmp_raw, tmp_elems * 2) != hipSuccess) {
         ee_model_free(m);
@@ -407,8 +433,10 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if (hipMemcpy(dev_emb, emb, V * d * 2, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of the embedding table failed"));
     md.emb = dev_emb;
 
-    // tiled weights: one allocation per GEMM kind, layers at a fixed stride
-    for (int k = 0; k < 5; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 64;
+    // tiled weights: one allocation per GEMM kind, layers at a fixed stride.  Zero-filled: tile slots no wave's
+    // sequence reaches (a wave without k-steps, the shorter sequences' tails) are still loaded by the clamped
+    // look-ahead and multiplied with zeros, so they must hold finite values.
+    for (int k = 0; k < G_KINDS; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 64;
     const long long s_head = md.wstride[G_HEAD];
     md.wstride[G_HEAD] = 0;
     (void)s_head;
@@ -416,11 +444,11 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     uint4 *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdn = nullptr, *wlm = nullptr;
     float *g_attn = nullptr, *g_ffn = nullptr, *g_final_d = nullptr;
     const size_t Lz = (size_t)c.n_layers;
-    if ((rc = dev_alloc(m->allocs, &wqkv, Lz * s_qkv, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, false)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * SWAVES * 64, false)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wqkv, Lz * s_qkv, true)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, true)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, true)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, true)) != EE_OK) return bail(rc);
+    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * SWAVES * 64, true)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
@@ -446,6 +474,40 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
             if ((rc = upload_gain(g_exit_src[i], c.d_model, tmp, ge)) != EE_OK) return bail(rc);
             m->g_exit[i] = ge;
         }
+    }
+    if (A) {
+        // adapters: weights in tile order per stored exit; biases as fp32, the bottlenecks' output biases summed in order
+        const long long s_ad = md.wstride[G_AD], s_au = md.wstride[G_AU];
+        uint4 *wad = nullptr, *wau = nullptr;
+        if ((rc = dev_alloc(m->allocs, &wad, (size_t)c.n_exits * s_ad, true)) != EE_OK) return bail(rc);
+        if ((rc = dev_alloc(m->allocs, &wau, (size_t)c.n_exits * s_au, true)) != EE_OK) return bail(rc);
+        for (int i = 0; i < c.n_exits; ++i) {
+            const uint16_t *sd_[1] = {ads[(size_t)i].down}, *su_[1] = {ads[(size_t)i].up};
+            if ((rc = upload_tiled(m, md.plan[G_AD], PERM_NONE, sd_, 1, A * d, tmp, wad + (size_t)i * s_ad)) != EE_OK) return bail(rc);
+            if ((rc = upload_tiled(m, md.plan[G_AU], PERM_NONE, su_, 1, d * A, tmp, wau + (size_t)i * s_au)) != EE_OK) return bail(rc);
+            float *bd = nullptr, *bu = nullptr;
+            if ((rc = dev_alloc(m->allocs, &bd, A, false)) != EE_OK) return bail(rc);
+            if ((rc = dev_alloc(m->allocs, &bu, d, false)) != EE_OK) return bail(rc);
+            std::vector<float> hb(std::max(A, d));
+            auto bf = [](uint16_t v) {
+                uint32_t u32 = (uint32_t)v << 16;
+                float f;
+                memcpy(&f, &u32, 4);
+                return f;
+            };
+            for (size_t r = 0; r < A; ++r) hb[r] = bf(ads[(size_t)i].bdown[r]);
+            if (hipMemcpy(bd, hb.data(), A * 4, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of adapter biases failed"));
+            for (size_t col = 0; col < d; ++col) {
+                float acc = 0.f;
+                for (int j = 0; j < n_ad; ++j) acc += bf(ads[(size_t)i].bup[(size_t)j * d + col]);
+                hb[col] = acc;
+            }
+            if (hipMemcpy(bu, hb.data(), d * 4, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of adapter biases failed"));
+            m->ad_bdown[i] = bd;
+            m->ad_bup[i] = bu;
+        }
+        md.w[G_AD] = wad;
+        md.w[G_AU] = wau;
     }
     md.w[G_QKV] = wqkv;
     md.w[G_O] = wo;
@@ -534,6 +596,7 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     s->max_ctx = max_ctx;
     s->max_gamma = max_gamma;
     s->leader = s;
+    s->head_batch = 1;
     const ee_model_config &c = m->cfg;
     const int rows_max = c.max_rows;
     const size_t d = (size_t)c.d_model;
@@ -608,6 +671,9 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     S_TRY(dev_alloc(s->allocs, &sc.xh, (size_t)2 * rows_max * md.Kpad_d));
     S_TRY(dev_alloc(s->allocs, &sc.attn, (size_t)2 * rows_max * md.Kpad_d));
     S_TRY(dev_alloc(s->allocs, &sc.u, (size_t)2 * rows_max * md.Kpad_F));
+    S_TRY(dev_alloc(s->allocs, &sc.xa, (size_t)2 * rows_max * md.Kpad_d));
+    S_TRY(dev_alloc(s->allocs, &sc.t, (size_t)2 * rows_max * std::max(md.Kpad_A, 32)));
+    S_TRY(dev_alloc(s->allocs, &sc.ss_h, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_a, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.ss_f, (size_t)m->nwg * rows_max));
     {
@@ -677,50 +743,50 @@ static void fill_sessdev(SessDev &sd, const ee_session *s)
         }
 }
 
-// host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [HEAD]
-static int stage_type(const PassArgs &a, int ph)
-{
-    const int per_layer = 5;
-    int idx = ph - (a.do_embed ? 1 : 0);
-    if (idx < 0) return ST_EMBED;
-    const int nl = a.layer_end - a.layer_begin;
-    if (idx < per_layer * nl) return idx % per_layer == 1 ? ST_ATT : ST_GEMM;
-    idx -= per_layer * nl;
-    if (a.head_kind != HEAD_NONE && idx == 0) return ST_GEMM;
-    return ST_NONE;
-}
-
-// what stage ph runs, as an EE_LAUNCH_* code (for a GEMM stage this is its GemmKind)
+// host mirror of the kernels' stage list: [EMBED] { QKV ATT O GU DN } x layers [AD AU] [HEAD];
+// returns the stage's EE_LAUNCH_* code (for a GEMM stage: its GemmKind), or -1 past the end
 static int launch_code(const PassArgs &a, int ph)
 {
-    const int type = stage_type(a, ph);
-    if (type == ST_EMBED) return EE_LAUNCH_EMBED;
-    if (type == ST_ATT) return EE_LAUNCH_ATT;
     const int per_layer = 5;
     int idx = ph - (a.do_embed ? 1 : 0);
-    if (idx >= per_layer * (a.layer_end - a.layer_begin)) return EE_LAUNCH_HEAD;
-    int r = idx % per_layer;
-    if (r == 0) return EE_LAUNCH_QKV;
-    return EE_LAUNCH_O + (r - 2);
+    if (idx < 0) return EE_LAUNCH_EMBED;
+    const int nl = a.layer_end - a.layer_begin;
+    if (idx < per_layer * nl) {
+        const int r = idx % per_layer;
+        if (r == 0) return EE_LAUNCH_QKV;
+        if (r == 1) return EE_LAUNCH_ATT;
+        return EE_LAUNCH_O + (r - 2);
+    }
+    idx -= per_layer * nl;
+    if (a.head_kind != HEAD_NONE) {
+        const int n_ad = a.adapter ? 2 : 0;
+        if (idx < n_ad) return EE_LAUNCH_ADAPTER_DOWN + idx;
+        if (idx == n_ad && a.head_stage) return EE_LAUNCH_HEAD;
+    }
+    return -1;
 }
 
 // Enqueues the stages of one segment, one launch each, on the leader's stream.
-static int launch_segment(ee_session *lead, PassArgs &a)
+static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
 {
     const ee_model *m = lead->m;
     const int per_layer = 5;
-    const int n_stages = (a.do_embed ? 1 : 0) + per_layer * (a.layer_end - a.layer_begin) + (a.head_kind != HEAD_NONE ? 1 : 0);
-    for (int ph = 0; ph < n_stages; ++ph) {
-        const int type = stage_type(a, ph);
+    const int rows = a.rows;
+    for (int ph = 0;; ++ph) {
         const int code = launch_code(a, ph);
+        if (code < 0) break;
+        const bool gemm = code != EE_LAUNCH_EMBED && code != EE_LAUNCH_ATT;
         a.stage = ph;
         a.fuse_accept = code == EE_LAUNCH_HEAD ? 1 : 0;
-        pass_kernel_t k = type == ST_GEMM ? gemm_kernel(a.rows) : (type == ST_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
-        if (type == ST_GEMM) {  // the stage's plan, LDS map and weights travel with the launch (EE_LAUNCH_QKV .. EE_LAUNCH_HEAD = GemmKind)
+        a.rows = code == EE_LAUNCH_HEAD ? a.head_rows : rows;   // the head launch carries the rows of all exits of its group
+        pass_kernel_t k = gemm ? gemm_kernel(a.rows) : (code == EE_LAUNCH_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
+        if (gemm) {  // the stage's plan, LDS map and weights travel with the launch
+            static_assert(EE_LAUNCH_QKV == G_QKV && EE_LAUNCH_HEAD == G_HEAD && EE_LAUNCH_ADAPTER_DOWN == G_AD && EE_LAUNCH_ADAPTER_UP == G_AU,
+                          "launch codes of GEMM stages are their GemmKind");
             const int idx = ph - (a.do_embed ? 1 : 0);
-            const int layer = code == EE_LAUNCH_HEAD ? 0 : a.layer_begin + idx / per_layer;
+            const int slice = code == EE_LAUNCH_HEAD ? 0 : (code >= EE_LAUNCH_ADAPTER_DOWN ? adapter_slot : a.layer_begin + idx / per_layer);
             a.plan0 = m->host_md.plan[code];
-            a.W0 = m->host_md.w[code] + (size_t)layer * m->host_md.wstride[code];
+            a.W0 = m->host_md.w[code] + (size_t)slice * m->host_md.wstride[code];
             if (!plan_lds(a.plan0, a.rows, m->lds_budget, a.lay)) return fail(EE_EDEVICE, "no LDS layout for %d rows", a.rows);
         }
         const bool timed = (lead->flags & EE_TIME_LAUNCHES) && a.mode == 0;
@@ -738,6 +804,7 @@ static int launch_segment(ee_session *lead, PassArgs &a)
         HIP_TRY(hipGetLastError());
         if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->run_stream));
     }
+    a.rows = rows;
     return EE_OK;
 }
 
@@ -843,11 +910,15 @@ extern "C" int ee_prefill_embeds(ee_session *s, const uint16_t *emb_bf16, int n_
         a.head_kind = last ? HEAD_PREFILL : HEAD_NONE;
         a.head_idx = 0;
         a.head_gain = m->host_md.g_final;
+        a.n_heads = 1;
+        a.head_rows = rows;
+        a.head_row0 = 0;
+        a.head_stage = 1;
         a.att_splits = attention_splits(s, s->att_items_cap, 1, rows, start + rows);
         if (a.att_splits == 0) return fail(EE_ECAPACITY, "ee_prefill: context too long for the session's attention scratch");
         a.sess = s->dev_sessdev;
         a.sess0 = s->host_sessdev[0];
-        if ((rc = launch_segment(s, a)) != EE_OK) return rc;
+        if ((rc = launch_segment(s, a, 0)) != EE_OK) return rc;
     }
     HIP_TRY(hipStreamSynchronize(s->stream));
     s->kv_len = total;
@@ -871,7 +942,7 @@ extern "C" int ee_prefill(ee_session *s, const int32_t *tokens, int n, unsigned 
 
 // ------------------------------------------------------------------ verify
 
-static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exits, const float **gains)
+static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exits, const float **gains, int *slots)
 {
     if (n_exits < 0 || n_exits > EE_MAX_EXITS || (n_exits > 0 && !exit_layers))
         return fail(EE_EINVAL, "ee_verify: n_exits %d not in [0,%d]", n_exits, EE_MAX_EXITS);
@@ -881,7 +952,10 @@ static int check_exits(const ee_model *m, const int32_t *exit_layers, int n_exit
         if (e > 0 && exit_layers[e] <= exit_layers[e - 1]) return fail(EE_EINVAL, "ee_verify: exit layers must increase strictly");
         gains[e] = nullptr;
         for (int i = 0; i < m->cfg.n_exits; ++i)
-            if (m->cfg.exit_layers[i] == exit_layers[e]) gains[e] = m->g_exit[i];
+            if (m->cfg.exit_layers[i] == exit_layers[e]) {
+                gains[e] = m->g_exit[i];
+                slots[e] = i;
+            }
         if (!gains[e]) return fail(EE_EINVAL, "ee_verify: the model stores no exit gain for layer %d", exit_layers[e]);
     }
     return EE_OK;
@@ -941,6 +1015,9 @@ static int use_static_scratch(ee_session *lead, PassArgs &a, int M, int n_pos_ma
     sc.xh = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
     sc.attn = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
     sc.u = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_F * 2));
+    sc.xa = reinterpret_cast<uint16_t *>(take(2 * rows * md.Kpad_d * 2));
+    sc.t = reinterpret_cast<uint16_t *>(take(2 * rows * std::max(md.Kpad_A, 32) * 2));
+    sc.ss_h = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
     sc.ss_a = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
     sc.ss_f = reinterpret_cast<float *>(take((size_t)m->nwg * md.rows_max * 4));
     sc.cand = reinterpret_cast<int2 *>(take((size_t)m->nwg * md.rows_max * 8));
@@ -993,7 +1070,8 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
     }
     if (n_sessions * M > c.max_rows) return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, c.max_rows);
     const float *gains[EE_MAX_EXITS];
-    int rc = check_exits(m, exit_layers, n_exits, gains);
+    int slots[EE_MAX_EXITS];
+    int rc = check_exits(m, exit_layers, n_exits, gains, slots);
     if (rc != EE_OK) return rc;
     HIP_TRY(hipSetDevice(m->device));
     int n_pos_max = 0;
@@ -1040,17 +1118,35 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
 
     HIP_TRY(hipEventRecord(lead->ev_start, lead->run_stream));
     lead->lt_codes.clear();
+    // Exit heads run in groups of up to head_batch consecutive exits: every exit deposits its
+    // LM-head input rows when its layer is done, and the last one of the group runs the LM head
+    // over the rows of all of them (one stream of W_lm per group), after which the group's results
+    // are published together.  head_batch = 1: every exit is published right after its layer.
+    const int per_group = std::max(1, std::min(lead->head_batch, c.max_rows / a.rows));
     int layer = 0;
     for (int e = 0; e <= n_exits; ++e) {
         const bool fin = (e == n_exits);
+        const int g_first = fin ? e : e / per_group * per_group;             // first exit of e's group
+        const int g_size = fin ? 1 : std::min(per_group, n_exits - g_first);
         a.layer_begin = layer;
         a.layer_end = fin ? c.n_layers : exit_layers[e];
         a.do_embed = (e == 0) ? 1 : 0;
         a.head_kind = fin ? HEAD_FINAL : HEAD_EXIT;
-        a.head_idx = e;
+        a.head_idx = g_first;
         a.head_gain = fin ? m->host_md.g_final : gains[e];
-        if ((rc = launch_segment(lead, a)) != EE_OK) return rc;
-        HIP_TRY(hipEventRecord(fin ? lead->ev_final : lead->ev_exit[e], lead->run_stream));
+        a.n_heads = g_size;
+        a.head_rows = g_size * a.rows;
+        a.head_row0 = (e - g_first) * a.rows;
+        a.head_stage = (e - g_first == g_size - 1) ? 1 : 0;
+        a.adapter = (!fin && m->host_md.A > 0) ? 1 : 0;
+        a.ad_bdown = a.adapter ? m->ad_bdown[slots[e]] : nullptr;
+        a.ad_bup = a.adapter ? m->ad_bup[slots[e]] : nullptr;
+        if ((rc = launch_segment(lead, a, fin ? 0 : slots[e])) != EE_OK) return rc;
+        if (fin) {
+            HIP_TRY(hipEventRecord(lead->ev_final, lead->run_stream));
+        } else if (a.head_stage) {
+            for (int j = g_first; j <= e; ++j) HIP_TRY(hipEventRecord(lead->ev_exit[j], lead->run_stream));
+        }
         layer = a.layer_end;
     }
     for (int i = 0; i < n_sessions; ++i) {
@@ -1166,13 +1262,13 @@ extern "C" int ee_exit_pop(ee_session *s, int wait, int *exit_idx, float *score)
     HIP_TRY(hipSetDevice(s->m->device));
     for (;;) {
         if (!s->in_flight || hipEventQuery(lead->ev_final) == hipSuccess) {  // the final result is there: Q_e is reset
-            s->popped_mask = ~0u;
+            s->popped_mask = ~0ull;
             return EE_DONE;
         }
         int best = -1, first_unpublished = -1;
         float best_sc = -1.f;
         for (int e = 0; e < s->flight_exits; ++e) {
-            if (s->popped_mask & (1u << e)) continue;
+            if (s->popped_mask & (1ull << e)) continue;
             const hipError_t q = hipEventQuery(lead->ev_exit[e]);
             if (q == hipSuccess) {
                 const float sc = exit_score(s->result, e);
@@ -1187,7 +1283,7 @@ extern "C" int ee_exit_pop(ee_session *s, int wait, int *exit_idx, float *score)
             }
         }
         if (best >= 0) {
-            s->popped_mask |= 1u << best;
+            s->popped_mask |= 1ull << best;
             *exit_idx = best;
             if (score) *score = best_sc;
             return EE_OK;
@@ -1323,6 +1419,10 @@ extern "C" int ee_session_option(ee_session *s, int option, int value)
     case EE_OPT_ATT_SPLITS:
         if (value < 0 || value > ATT_MAX_SPLITS) return fail(EE_EINVAL, "EE_OPT_ATT_SPLITS: %d not in [0,%d]", value, ATT_MAX_SPLITS);
         s->att_splits_opt = value;
+        return EE_OK;
+    case EE_OPT_HEAD_BATCH:
+        if (value < 1 || value > EE_MAX_EXITS) return fail(EE_EINVAL, "EE_OPT_HEAD_BATCH: %d not in [1,%d]", value, EE_MAX_EXITS);
+        s->head_batch = value;
         return EE_OK;
     case EE_OPT_SCATTER_PAGES:
         if (value != 0 && value != 1) return fail(EE_EINVAL, "EE_OPT_SCATTER_PAGES: %d not 0 or 1", value);

@@ -29,9 +29,9 @@ def test_header_functions_are_exported():
 
 def test_result_struct_layout_matches_header():
     from paper_2505_21594_amd.binding import VerifyResultC
-    # gamma, n_exits, accept_len, next_token, final[16], exit_accept[16], exit_tokens[16][16], status, reserved[15],
-    # final_conf[16], exit_conf[16][16]
-    assert ctypes.sizeof(VerifyResultC) == 4 * (4 + 16 + 16 + 256 + 1 + 15 + 16 + 256)
+    # gamma, n_exits, accept_len, next_token, final[16], exit_accept[40], exit_tokens[40][16], status, reserved[15],
+    # final_conf[16], exit_conf[40][16]
+    assert ctypes.sizeof(VerifyResultC) == 4 * (4 + 16 + 40 + 640 + 1 + 15 + 16 + 640)
 
 
 def test_model_load_host_errors(tmp_path):

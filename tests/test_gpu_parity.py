@@ -525,3 +525,71 @@ def test_sender_queue_order_and_pop(model_dir):
         gs.free()
     finally:
         g.free()
+
+
+AD_TINY = eegen.ModelConfig(n_layers=6, d_model=256, n_heads=4, head_dim=64, d_ffn=688, vocab=1024,
+                            exit_layers=(1, 2, 3, 4, 5), n_adapters=3, adapter_width=16)
+AD_MID = eegen.ModelConfig(n_layers=3, d_model=1280, n_heads=10, head_dim=128, d_ffn=1072, vocab=3000,
+                           exit_layers=(1, 2), n_adapters=3, adapter_width=128)
+
+
+@pytest.mark.parametrize("which", ["tiny", "mid"])
+def test_adapter_exit_heads(model_dir, which):
+    """Exit heads with adapters (three bottlenecks in parallel on the layer's output, then
+    RMSNorm and the shared LM head): every head's logits and tokens against the oracle, several
+    rounds with commit; an exit after every layer but the last."""
+    cfg = AD_TINY if which == "tiny" else AD_MID
+    p = f"{model_dir}/gpu_ad_{which}.bin"
+    eegen.write_model(p, cfg, 61, gains="uniform", std=0.05 if which == "tiny" else 0.03)
+    g, o = ee.Model(p), eo.Model(p)
+    assert g.config.n_adapters == 3 and g.config.adapter_width == cfg.adapter_width
+    exits = list(cfg.exit_layers)
+    try:
+        prompt = eegen.prompt_tokens(62, 45, cfg.vocab)
+        _chain(g, o, prompt, 4, exits, rounds=4, p_corrupt=0.3, seed=63, max_ctx=128, what=f"adapters {which}")
+        _chain(g, o, prompt[:7], 7, exits[1:], rounds=2, p_corrupt=0.5, seed=64, max_ctx=64, what=f"adapters {which} gamma 7")
+    finally:
+        g.free()
+
+
+@pytest.mark.parametrize("adapters", [False, True])
+def test_exit_heads_in_groups_match_one_by_one(model_dir, adapters):
+    """EE_OPT_HEAD_BATCH: the LM head streamed once for k consecutive exits gives bit-identical
+    logits and results to one launch per exit; the results of a group are published together
+    (after its last exit), never later than the final result."""
+    cfg = AD_TINY if adapters else eegen.ModelConfig(6, 256, 4, 64, 688, 1024, (1, 2, 3, 4, 5))
+    p = f"{model_dir}/gpu_groups_{int(adapters)}.bin"
+    eegen.write_model(p, cfg, 65, gains="uniform", std=0.05)
+    g, o = ee.Model(p, max_rows=48), eo.Model(p)
+    exits = [1, 2, 3, 4, 5]
+    prompt = eegen.prompt_tokens(66, 30, cfg.vocab)
+    drafts = eegen.prompt_tokens(67, 4, cfg.vocab)
+    try:
+        os_ = o.session(64)
+        fo, margin = oracle_prefill(os_, prompt)
+        ro = os_.verify(drafts, exits, commit=False, want_logits=True)
+        ref = None
+        for k in (1, 2, 3, 5, 9):
+            gs = g.session(64, max_gamma=4, flags=ee.KEEP_LOGITS)
+            check_first_token(gs, gs.ee_prefill(prompt), fo, margin, "groups")
+            gs.ee_session_option(ee.OPT_HEAD_BATCH, k)
+            gs.ee_verify(drafts, exits)
+            gs.ee_wait_exit(0)
+            gs.ee_wait_final()
+            rg, lg = gs.final_result(), gpu_logits(gs, len(exits))
+            check_pass(ro, rg, lg, drafts, f"head batch {k}")
+            times = [gs.ee_pass_time_ms(e) for e in range(len(exits) + 1)]
+            assert all(a <= b for a, b in zip(times, times[1:])) and times[-2] < times[-1]
+            if k >= 2:
+                assert times[1] - times[0] < 0.03    # exits 0 and 1 share a group: published together (one launch of the head)
+            if ref is None:
+                ref = (rg, lg)
+            else:
+                assert np.array_equal(rg.exit_tokens, ref[0].exit_tokens) and np.array_equal(rg.final_tokens, ref[0].final_tokens)
+                assert np.array_equal(rg.exit_accept_len, ref[0].exit_accept_len)
+                assert np.array_equal(rg.exit_conf.view(np.uint32), ref[0].exit_conf.view(np.uint32))
+                for a, b in zip(lg, ref[1]):
+                    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+            gs.free()
+    finally:
+        g.free()

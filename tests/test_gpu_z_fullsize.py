@@ -200,3 +200,46 @@ def test_llama13b_gamma5_ctx1024(capsys):
     finally:
         if os.path.exists(path):
             os.remove(path)   # 26 GB of /dev/shm
+
+
+@pytest.mark.timeout(600)
+def test_llama7b_31_exits_with_adapters(capsys):
+    """The regime the paper runs: an exit head after every layer but the last (31 on the 7B
+    shape), each with its adapters (three bottlenecks of width 128), the LM head streamed once
+    for groups of eight exits (40 rows)."""
+    base = eegen.LLAMA7B
+    cfg = eegen.ModelConfig(base.n_layers, base.d_model, base.n_heads, base.head_dim, base.d_ffn, base.vocab,
+                            tuple(range(1, base.n_layers)), n_adapters=3, adapter_width=128)
+    path = _model_file(cfg, "llama7b_31exits")
+    try:
+        g = ee.Model(path, max_rows=40)
+        o = eo.Model(path)
+        exits = list(cfg.exit_layers)
+        prompt = eegen.prompt_tokens(20250525, 128, cfg.vocab)
+        gs = g.session(256, max_gamma=4, flags=ee.KEEP_LOGITS)
+        os_ = o.session(256)
+        try:
+            first_o, margin = oracle_prefill(os_, prompt)
+            check_first_token(gs, gs.ee_prefill(prompt), first_o, margin, "31 exits")
+            gs.ee_session_option(ee.OPT_HEAD_BATCH, 8)
+            worst = 0.0
+            for r in range(3):
+                drafts = eegen.corrupt_drafts(oracle_greedy(os_, 4), 0.3, cfg.vocab, 20250525, r)
+                ro = os_.verify(drafts, exits, commit=True, want_logits=True)
+                rg = gs.verify_sync(drafts, exits)
+                exempt, err = check_pass(ro, rg, gpu_logits(gs, len(exits)), drafts, f"31 exits round {r}")
+                worst = max(worst, err)
+                if rg.accept_len != ro.accept_len or rg.next_token != ro.next_token:
+                    assert exempt
+                    gs.ee_kv_truncate(os_.kv_len)
+                    gs.ee_set_pending(os_.pending)
+                assert gs.ee_kv_len() == os_.kv_len and gs.ee_pending() == os_.pending
+                _say(capsys, f"[7B 31 exits] round {r}: worst logits err {worst:.3g}, exit accept lengths {list(ro.exit_accept_len)}, "
+                             f"final {ro.accept_len}, pass {gs.ee_pass_time_ms(len(exits)):.2f} ms")
+        finally:
+            gs.free()
+            g.free()
+            o.close()
+    finally:
+        if os.path.exists(path):
+            os.remove(path)
