@@ -31,14 +31,22 @@ import eegen  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
 
+_L7 = eegen.LLAMA7B
+# the regime the paper runs: an exit head after every layer but the last, each with its adapters
+LLAMA7B_31 = eegen.ModelConfig(_L7.n_layers, _L7.d_model, _L7.n_heads, _L7.head_dim, _L7.d_ffn, _L7.vocab,
+                               tuple(range(1, _L7.n_layers)), n_adapters=3, adapter_width=128)
+
 WORKLOADS = {
     # name: (model config, model file tag, prompt tokens, gamma, exits, corruption p (None: per session in
-    #        [0.1, 0.6]), sessions, embedding-prefix rows)
-    "llama7b_g4_ctx512": (eegen.LLAMA7B, "llama7b", 512, 4, (8, 16), 0.3, 1, 0),
-    "llama7b_g8_ctx2048": (eegen.LLAMA7B, "llama7b", 2048, 8, (8, 16, 24), 0.5, 1, 0),
-    "llama13b_g5_ctx1024": (eegen.LLAMA13B, "llama13b", 1024, 5, (20,), 0.3, 1, 0),
-    "llama7b_b8_vlm": (eegen.LLAMA7B, "llama7b", 64, 4, (16,), None, 8, 576),
-    "tiny_g4_ctx64": (eegen.TINY, "tiny", 64, 4, (2,), 0.3, 1, 0),
+    #        [0.1, 0.6]), sessions, embedding-prefix rows, exit heads per launch of the LM head)
+    "llama7b_g4_ctx512": (eegen.LLAMA7B, "llama7b", 512, 4, (8, 16), 0.3, 1, 0, 1),
+    "llama7b_g8_ctx2048": (eegen.LLAMA7B, "llama7b", 2048, 8, (8, 16, 24), 0.5, 1, 0, 1),
+    "llama13b_g5_ctx1024": (eegen.LLAMA13B, "llama13b", 1024, 5, (20,), 0.3, 1, 0, 1),
+    "llama7b_b8_vlm": (eegen.LLAMA7B, "llama7b", 64, 4, (16,), None, 8, 576, 1),
+    "llama7b_g15_ctx512": (eegen.LLAMA7B, "llama7b", 512, 15, (8, 16), 0.3, 1, 0, 1),     # 16 rows: one full row tile
+    "llama7b_g4_ctx512_31exits": (LLAMA7B_31, "llama7b_31exits", 512, 4, LLAMA7B_31.exit_layers, 0.3, 1, 0, 1),
+    "llama7b_g4_ctx512_31exits_groups8": (LLAMA7B_31, "llama7b_31exits", 512, 4, LLAMA7B_31.exit_layers, 0.3, 1, 0, 8),
+    "tiny_g4_ctx64": (eegen.TINY, "tiny", 64, 4, (2,), 0.3, 1, 0, 1),
 }
 
 
@@ -46,7 +54,8 @@ def algorithmic_bytes(cfg, n_exits, P, M, B=1):
     """One read of every weight byte each time it is applied, one read of the live
     KV cache, one write of the new KV rows, one read of the embedding rows."""
     L, d, F, V = cfg.n_layers, cfg.d_model, cfg.d_ffn, cfg.vocab
-    weights = 2 * (L * (4 * d * d + 3 * d * F + 2 * d) + (n_exits + 1) * (V * d + d))
+    A = cfg.n_adapters * cfg.adapter_width
+    weights = 2 * (L * (4 * d * d + 3 * d * F + 2 * d) + (n_exits + 1) * (V * d + d) + n_exits * (2 * A * d + A + d))
     kv_read = B * (2 * (P + M) * d * 2 * L)
     kv_write = B * (M * d * 2 * 2 * L)
     return weights + kv_read + kv_write + B * M * d * 2
@@ -61,6 +70,8 @@ def launch_bytes(cfg, code, P, M, B=1):
         "gu": 2 * (2 * d * F + d),
         "dn": 2 * d * F,
         "head": 2 * (V * d + d),
+        "adapter_down": 2 * (cfg.n_adapters * cfg.adapter_width) * (d + 1),
+        "adapter_up": 2 * (cfg.n_adapters * cfg.adapter_width + 1) * d,
         "att": B * 2 * (P + M) * d * 2,
         "embed": B * M * d * 2,
     }.get(code, 0)
@@ -93,8 +104,8 @@ def per_launch_roofline(ee, run, passes):
 class Run:
     """One workload: the model, its sessions' prompts and every round's drafts."""
 
-    def __init__(self, ee, model, cfg, seed, n_prompt, gamma, exits, p, B, n_emb, flags):
-        self.ee, self.model, self.cfg, self.seed = ee, model, cfg, seed
+    def __init__(self, ee, model, cfg, seed, n_prompt, gamma, exits, p, B, n_emb, flags, head_batch=1):
+        self.ee, self.model, self.cfg, self.seed, self.head_batch = ee, model, cfg, seed, head_batch
         self.n_prompt, self.gamma, self.M, self.exits, self.B, self.n_emb, self.flags = n_prompt, gamma, gamma + 1, list(exits), B, n_emb, flags
         self.p = [p if p is not None else eegen.session_corruption_p(seed, b) for b in range(B)]
         self.prompts = [eegen.prompt_tokens(seed, n_prompt, cfg.vocab, session=b) for b in range(B)]
@@ -107,6 +118,8 @@ class Run:
         for b in range(self.B):
             s = self.model.session(max_ctx, max_gamma=self.gamma, flags=self.flags | extra_flags)
             s.first = s.ee_prefill(self.prompts[b], emb=self.embs[b])
+            if self.head_batch > 1:
+                s.ee_session_option(self.ee.OPT_HEAD_BATCH, self.head_batch)
             s.base = self.n_emb + self.n_prompt
             out.append(s)
         return out
@@ -185,27 +198,40 @@ def gpu_greedy(sess, gamma):
     return out
 
 
-def cpu_baseline(path, cfg, gamma, exits, seed, passes=64, ctx=64):
-    """The oracle as it stands, timed on the host cores on a bounded sample."""
+def cpu_baseline(path, run, first_round, budget_s=25.0, prefill_rows_max=1100):
+    """The oracle as it stands, timed on the host cores on a bounded sample of the workload: the
+    same model file, the same prompt (session 0) and the drafts of the timed rounds."""
     from oracle import oracle as eo
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    cfg, gamma, exits = run.cfg, run.gamma, run.exits
     m = eo.Model(path)
-    s = m.session(ctx + (passes + 1) * (gamma + 1) + 8)
-    s.prefill(eegen.prompt_tokens(seed + 1, ctx, cfg.vocab))
+    n_rows = run.n_emb + run.n_prompt
+    prompt, emb, note = run.prompts[0], run.embs[0], "the workload's own prompt"
+    # the oracle's prefill runs at about 50 rows/s per 7e9 parameters: bound it to about 20 s
+    n_params = cfg.n_layers * (4 * cfg.d_model ** 2 + 3 * cfg.d_model * cfg.d_ffn) + 2 * cfg.vocab * cfg.d_model
+    rows_cap = max(64, int(prefill_rows_max * 6.7e9 / n_params))
+    if n_rows > rows_cap:   # keep the tail of the prompt (text rows only)
+        emb = None
+        prompt = prompt[-min(rows_cap, len(prompt)):]
+        note = f"the last {len(prompt)} rows of the workload's {n_rows}-row prompt"
+    rounds = len(run.drafts) - first_round
+    s = m.session((0 if emb is None else run.n_emb) + len(prompt) + (rounds + 1) * (gamma + 1) + 8)
+    t0 = time.perf_counter()
+    s.prefill(prompt, emb=emb)
+    t_prefill = time.perf_counter() - t0
     times = []
     t_all = time.perf_counter()
-    for i in range(passes):
-        drafts = eegen.prompt_tokens(seed + 2, gamma, cfg.vocab, session=i)
+    for r in range(first_round, len(run.drafts)):
         t = time.perf_counter()
-        s.verify(drafts, list(exits))
+        s.verify(run.drafts[r][0], list(exits))
         times.append(time.perf_counter() - t)
-        if time.perf_counter() - t_all > 25.0:  # bounded: about 10-30 s of CPU work
+        if time.perf_counter() - t_all > budget_s and len(times) >= 5:  # bounded: about 10-30 s of CPU work
             break
     m.close()
     med = statistics.median(times)
     return {"value": 1.0 / med, "unit": "verify passes/s", "cores": threads, "kind": "oracle",
-            "sample": f"{len(times)} verify passes (gamma={gamma}, exits={list(exits)}) of the same model at context {ctx} "
-                      f"instead of the workload's prompt (weights are >97% of the bytes); median {med:.2f} s/pass"}
+            "sample": f"{len(times)} consecutive verify passes of one session (gamma={gamma}, {len(exits)} exits) after the oracle's own "
+                      f"prefill of {note} ({t_prefill:.1f} s, untimed), fed the drafts of the timed rounds; median {med:.3f} s/pass"}
 
 
 def main():
@@ -230,17 +256,17 @@ def main():
 
     import paper_2505_21594_amd as ee
 
-    cfg, tag, n_prompt, gamma, exits, p_corrupt, B, n_emb = WORKLOADS[args.workload]
+    cfg, tag, n_prompt, gamma, exits, p_corrupt, B, n_emb, head_batch = WORKLOADS[args.workload]
     M = gamma + 1
     K, W = args.steps, args.warmup
     path = model_file(cfg, tag, args.seed, pick_workdir())
 
     t = time.time()
-    model = ee.Model(path, device=0, max_rows=B * M)
+    model = ee.Model(path, device=0, max_rows=max(B * M, min(48, head_batch * B * M)))
     print(f"[bench] model on GPU in {time.time() - t:.1f}s, {model.n_workgroups} workgroups", file=sys.stderr, flush=True)
     rounds = W + K
     flags = 0
-    run = Run(ee, model, cfg, args.seed, n_prompt, gamma, exits, p_corrupt, B, n_emb, flags)
+    run = Run(ee, model, cfg, args.seed, n_prompt, gamma, exits, p_corrupt, B, n_emb, flags, head_batch)
     t = time.time()
     sessions = run.make_sessions(rounds=rounds)
     print(f"[bench] prefill of {B} x {n_emb + n_prompt} rows in {time.time() - t:.2f}s", file=sys.stderr, flush=True)
@@ -262,8 +288,23 @@ def main():
     ee.ee_device_synchronize(0)
     wall = time.perf_counter() - t0
 
+    # the host holding the first exit's result while the pass is still running (8 further passes of the trajectory)
+    host_lead = []
+    if ex and B == 1:
+        extra = run.make_sessions(rounds=rounds)
+        for r in range(min(rounds, 8)):
+            extra[0].ee_verify(run.drafts[r][0], ex)
+            extra[0].ee_wait_exit(0)
+            t_exit = time.perf_counter()
+            early = not extra[0].ee_query_final()
+            extra[0].ee_wait_final()
+            if early:
+                host_lead.append((time.perf_counter() - t_exit) * 1e3)
+        for sx in extra:
+            sx.free()
+
     kinds = per_launch_roofline(ee, run, min(rounds, 9))
-    gemm = [k for k in ("qkv", "o", "gu", "dn", "head") if k in kinds]
+    gemm = [k for k in ("qkv", "o", "gu", "dn", "head", "adapter_down", "adapter_up") if k in kinds]
     g_n = sum(kinds[k]["launches_per_pass"] for k in gemm)
     g_ms = sum(kinds[k]["launches_per_pass"] * kinds[k]["avg_launch_us"] for k in gemm) * 1e-3
     g_bytes = sum(kinds[k]["launches_per_pass"] * kinds[k]["algorithmic_bytes_per_launch"] for k in gemm)
@@ -286,15 +327,19 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "gamma": gamma, "exit_layers": ex, "prompt": n_prompt,
                    "batch": B, "embedding_prefix_rows": n_emb, "context_first": ctx_at[0], "context_last": ctx_at[-1],
+                   "exit_heads_per_lm_head_launch": head_batch, "adapters": [cfg.n_adapters, cfg.adapter_width],
                    "launch_mode": "stage"},
         "device_ms_per_pass": {"mean": mean_dev_ms, "median": statistics.median(dev_ms),
                                "p10": float(np.percentile(dev_ms, 10)), "p90": float(np.percentile(dev_ms, 90))},
         "verified_tokens_per_s": committed / wall,
         "mean_accept_len": sum(accepted) / len(accepted) / B,
         "exit_lead_ms": [mean_dev_ms - sum(e[i] for e in exit_ms) / len(exit_ms) for i in range(len(ex))],
+        "exit0_lead_seen_by_host_ms": {"median": statistics.median(host_lead), "passes_with_exit_before_final": len(host_lead)} if host_lead else None,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(kernel_name, args.workload),
+                     "traffic_source": "committed rocprofv3 --pmc summary profiles/hbm_traffic_*.md (FETCH_SIZE + WRITE_SIZE, "
+                                       "scaled by a plain copy kernel's reading); not measured in this run",
                      "kernel": kernel_name,
                      "launches_per_pass": g_n, "algorithmic_bytes_per_launch": g_bytes / g_n,
                      "avg_launch_us": g_ms / g_n * 1e3,
@@ -308,7 +353,7 @@ def main():
         sx.free()
     model.free()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(path, cfg, gamma, exits, args.seed)
+        out["cpu_baseline"] = cpu_baseline(path, run, W)
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out), flush=True)

@@ -49,16 +49,17 @@ struct GemmPlan {
 };
 
 // LDS map of one GEMM launch, chosen on the host from the rows of the launch:
-//   [input block 0][input block 1] ... [misc]
+//   [input buffer 0][input buffer 1][input buffer 2] ... [misc]
 // An input block holds kbt k-tiles of the input as [k-tile][term][row][32] bf16 (both bf16
-// terms, all rows); with nkb > 1 blocks the helper waves fill one buffer while the streaming
-// waves read the other.  After a group's last block the same space holds the waves'
+// terms, all rows); with nkb > 1 blocks the helper waves fill the other buffers of a ring of
+// nbuf (2, or 3 when many rows leave room for short blocks only) while the streaming waves read one.  After a group's last block the same space holds the waves'
 // partial tiles for the cross-wave sum ([wave][n-tile of the chunk][row][16] floats, `chunk`
 // n-tiles at a time) and, behind them at zbuf_off, one [row][chunk*16] float tile for the
 // head's logits / the squares of the residual stream.
 struct StageLds {
     int kbt;         // k-tiles per input block (a multiple of SWAVES)
     int nkb;         // input blocks along K
+    int nbuf;        // input buffers (1 when the whole of K fits one)
     int xbuf_bytes;  // bytes of one input buffer
     int chunk;       // n-tiles reduced at a time
     int zbuf_off;

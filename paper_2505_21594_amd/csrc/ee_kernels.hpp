@@ -128,6 +128,20 @@ __device__ __forceinline__ void wait_vmem()
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0), other counters untouched
     asm volatile("" ::: "memory");
 }
+// at most n vector memory operations of this wave are still pending (n is rounded down to a
+// value with an instruction of its own, which only makes the wait stricter)
+__device__ __forceinline__ void wait_vmem_pending(int n)
+{
+#define EE_WAIT_CASE(N) case N: __builtin_amdgcn_s_waitcnt(0x0F70 | ((N) & 15) | (((N) >> 4) << 14)); break;
+    switch (min(n, 31)) {
+        EE_WAIT_CASE(0) EE_WAIT_CASE(1) EE_WAIT_CASE(2) EE_WAIT_CASE(3) EE_WAIT_CASE(4) EE_WAIT_CASE(5) EE_WAIT_CASE(6) EE_WAIT_CASE(7)
+        EE_WAIT_CASE(8) EE_WAIT_CASE(9) EE_WAIT_CASE(10) EE_WAIT_CASE(11) EE_WAIT_CASE(12) EE_WAIT_CASE(13) EE_WAIT_CASE(14) EE_WAIT_CASE(15)
+        EE_WAIT_CASE(16) EE_WAIT_CASE(17) EE_WAIT_CASE(18) EE_WAIT_CASE(19) EE_WAIT_CASE(20) EE_WAIT_CASE(21) EE_WAIT_CASE(22) EE_WAIT_CASE(23)
+        EE_WAIT_CASE(24) EE_WAIT_CASE(25) EE_WAIT_CASE(26) EE_WAIT_CASE(27) EE_WAIT_CASE(28) EE_WAIT_CASE(29) EE_WAIT_CASE(30) EE_WAIT_CASE(31)
+    }
+#undef EE_WAIT_CASE
+    asm volatile("" ::: "memory");
+}
 // Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every
 // vector memory operation of the wave, i.e. for all weight tiles a streaming wave has in
 // flight; nothing that crosses these barriers goes through global memory.
@@ -267,7 +281,7 @@ __device__ __forceinline__ void store_split4(uint16_t *x, int rows, int m, int k
 // Helper waves: copy k-tiles [kt0, kt0 + klen) of the input (all rows, both terms: one
 // contiguous range in memory) straight into LDS at dst.  One load instruction moves 64 x 16
 // bytes; no registers hold the data.  The caller waits (wait_vmem) before it tells the others.
-__device__ __forceinline__ void stage_block(const uint16_t *x, int rows, int kt0, int klen, char *dst, int hwave, int lane)
+__device__ __forceinline__ int stage_block(const uint16_t *x, int rows, int kt0, int klen, char *dst, int hwave, int lane)
 {
     const size_t tile_elems = (size_t)2 * rows * 32;          // one k-tile: both terms, all rows
     const uint16_t *src = x + (size_t)kt0 * tile_elems;
@@ -276,6 +290,7 @@ __device__ __forceinline__ void stage_block(const uint16_t *x, int rows, int kt0
         if (c0 + lane < nchunk)
             __builtin_amdgcn_global_load_lds((const EE_GLOBAL void *)(src + (size_t)(c0 + lane) * 8),
                                              (EE_LDS void *)(dst + (size_t)c0 * 16), 16, 0, 0);
+    return nchunk > hwave * 64 ? (nchunk - hwave * 64 + HWAVES * 64 - 1) / (HWAVES * 64) : 0;  // load instructions of this wave
 }
 
 // rstd[m] = 1/sqrt(sum_g ss[g][m] / d + eps) into LDS, fixed summation order; helper waves only.
@@ -500,7 +515,9 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
 }
 
 // k-steps whose tiles a streaming wave keeps in flight, by n-tiles of the group: about 8 to 14
-// tiles (1 KB each), fewer where the accumulators of three row tiles need the registers
+// tiles (1 KB each), fewer where the accumulators of three row tiles need the registers.  More
+// does not stream faster: 12 and 16 tiles per wave measured the same pass time as 8 (what a
+// compute unit can have in flight is bounded by the hardware, about 64 KB).
 template <int MT, int NL>
 constexpr int ring_steps()
 {
@@ -567,10 +584,10 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int s = s0 + r;
-                if (s == blk_end && s < S_max) {   // next input block: the helpers have copied it into the other buffer
+                if (s == blk_end && s < S_max) {   // next input block: the helpers have copied it into the next buffer of the ring
                     lds_barrier();
                     const int b = s / spb;
-                    xoff = wave * tile_bytes + (b & 1) * ly.xbuf_bytes - b * spb * SWAVES * tile_bytes;
+                    xoff = wave * tile_bytes + (b % ly.nbuf) * ly.xbuf_bytes - b * spb * SWAVES * tile_bytes;
                     blk_end += spb;
                 }
                 // A wave whose k-steps have run out keeps loading (its last tile again) and multiplies
@@ -586,10 +603,11 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
                     }
                     const bf16x8_t bh = __builtin_bit_cast(bf16x8_t, xh), bl = __builtin_bit_cast(bf16x8_t, xl);
 #pragma unroll
+                    for (int nt = 0; nt < NL; ++nt)  // the two terms of a tile in separate sweeps: no MFMA waits for the one before it
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, buf[r][nt]), bh, acc[nt][mt], 0, 0, 0);
+#pragma unroll
                     for (int nt = 0; nt < NL; ++nt) {
-                        const bf16x8_t A = __builtin_bit_cast(bf16x8_t, buf[r][nt]);
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bh, acc[nt][mt], 0, 0, 0);
-                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A, bl, acc[nt][mt], 0, 0, 0);
+                        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, buf[r][nt]), bl, acc[nt][mt], 0, 0, 0);
                         // the tile's registers are free after its last use: refill them with the step R further on
                         if (mt == MT - 1) buf[r][nt] = load_tile16(wres, lane_off, woff + min((s + R) * NL + nt, last) * wstep);
                     }
@@ -599,7 +617,6 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
     } else {
         // ---------------- helper wave: input blocks, row factors, per-row cache addresses
         const int hwave = wave - SWAVES;
-        stage_block(in.x, rows, 0, min(ly.kbt, pl.KT), lds, hwave, lane);
         if (first_group) {
             if (in.ss) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd, hwave, lane);
             const int ht = tid - SWAVES * 64;
@@ -612,14 +629,27 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
                 mi.pos[m] = pos;
                 mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
             }
-        }
-        wait_vmem();
-        lds_barrier();                             // block 0 ready
-        for (int b = 1; b < ly.nkb; ++b) {
-            const int kt0 = b * ly.kbt;
-            stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + (b & 1) * ly.xbuf_bytes, hwave, lane);
             wait_vmem();
-            lds_barrier();                         // block b ready, block b-1 no longer read
+        }
+        // Input blocks through a ring of ly.nbuf buffers: nbuf - 1 blocks are requested ahead of the
+        // one being read, so that the copy of a block has the time of a whole block (or two) to arrive.
+        // Block b is announced (barrier) once its own loads have landed, i.e. when only the loads of
+        // the blocks requested after it are still pending.
+        int issued = 0, cnt[3] = {0, 0, 0};        // cnt[j % 3]: load instructions of block j (nbuf <= 3)
+        auto request = [&](int j) __attribute__((always_inline)) {
+            const int kt0 = j * ly.kbt;
+            cnt[j % 3] = stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + (j % ly.nbuf) * ly.xbuf_bytes, hwave, lane);
+        };
+        for (; issued < max(ly.nbuf - 1, 1) && issued < ly.nkb; ++issued) request(issued);
+        for (int b = 0; b < ly.nkb; ++b) {
+            int after = 0;
+            for (int j = b + 1; j < issued; ++j) after += cnt[j % 3];
+            wait_vmem_pending(after);
+            lds_barrier();                         // block b ready; block b-1 no longer read: its buffer takes the next request
+            if (issued < ly.nkb) {
+                request(issued);
+                ++issued;
+            }
         }
     }
     // ---- cross-wave sum and epilogue, ly.chunk n-tiles at a time (the input buffers are free now)
@@ -679,8 +709,6 @@ __device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int la
 #undef EE_GROUP
             seq += S0 * nl;
         }
-    } else {
-        lds_barrier();
     }
     // what the workgroup hands to the following launch
     if (ep.ss_out && tid < rows) as_global_mut(ep.ss_out)[(size_t)blockIdx.x * md.rows_max + tid] = mi.rowss[tid];

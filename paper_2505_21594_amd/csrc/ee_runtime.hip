@@ -155,10 +155,16 @@ static bool plan_lds(const GemmPlan &p, int rows, size_t lds_total, StageLds &ly
     if ((size_t)KT8 * tile_bytes <= avail) {
         ly.kbt = KT8;
         ly.nkb = 1;
+        ly.nbuf = 1;
     } else {
+        ly.nbuf = 2;
         ly.kbt = (int)(avail / 2 / tile_bytes) / SWAVES * SWAVES;
         if (ly.kbt < SWAVES) return false;
+        // blocks of one k-step per wave: a block is read faster than its copy arrives; a third
+        // buffer lets the copy run two blocks ahead
+        if (ly.kbt == SWAVES && avail / 3 / tile_bytes >= (size_t)SWAVES) ly.nbuf = 3;
         ly.nkb = (p.KT + ly.kbt - 1) / ly.kbt;
+        if (ly.nkb < ly.nbuf) ly.nbuf = std::max(ly.nkb, 1);
     }
     ly.xbuf_bytes = (int)((size_t)ly.kbt * tile_bytes);
     // cross-wave sum: SWAVES partial tiles plus one logits / squares tile per n-tile of a chunk
