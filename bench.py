@@ -338,7 +338,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(kernel_name, args.workload),
-                     "traffic_source": "committed rocprofv3 --pmc summary profiles/hbm_traffic_*.md (FETCH_SIZE + WRITE_SIZE, "
+                     "traffic_source": "committed rocprofv3 --pmc summary profiles/hbm_traffic.md (FETCH_SIZE + WRITE_SIZE, "
                                        "scaled by a plain copy kernel's reading); not measured in this run",
                      "kernel": kernel_name,
                      "launches_per_pass": g_n, "algorithmic_bytes_per_launch": g_bytes / g_n,

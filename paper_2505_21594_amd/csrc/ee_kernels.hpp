@@ -536,9 +536,9 @@ constexpr int ring_steps()
 // path meanwhile: the compiler can then count the loads in flight and each use waits for
 // exactly its own tile (otherwise it waits for all of them, which halves what a wave pulls).
 //
-// The input reaches LDS in blocks of ly.kbt k-tiles, copied by the helper waves: block b+1
-// is copied into the other buffer while block b is read; one barrier per block boundary, the
-// same for all twelve waves.
+// The input reaches LDS in blocks of ly.kbt k-tiles, copied by the helper waves through a ring
+// of ly.nbuf buffers: later blocks are copied while block b is read; one barrier per block
+// boundary, the same for all twelve waves.
 //
 // Afterwards the accumulators go through LDS, `ly.chunk` n-tiles at a time, for the
 // cross-wave sum and the stage's epilogue (all waves).
