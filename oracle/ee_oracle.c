@@ -55,6 +55,7 @@ struct eo_session {
     int kv_len;
     int has_pending;
     int32_t pending;
+    int last_P, last_M; /* position and rows of the last verify pass (for eo_commit_rows) */
     real *kc; /* [L][max_ctx][d] */
     real *vc; /* [L][max_ctx][d] */
 };
@@ -357,6 +358,19 @@ int eo_kv_truncate(eo_session *s, int new_len)
     return EO_OK;
 }
 
+/* Commit of a verify pass whose accept decision was taken outside (probabilistic verification,
+   Eq. 2 with the draft probabilities): the first delta+1 rows of the last pass become part of
+   the sequence (their K/V are in the cache already) and `token` becomes the pending token. */
+int eo_commit_rows(eo_session *s, int delta, int32_t token)
+{
+    if (!s || s->last_M < 1 || delta < 0 || delta >= s->last_M) return EO_EINVAL;
+    if (token < 0 || token >= s->m->c.vocab) return EO_EINVAL;
+    s->kv_len = s->last_P + delta + 1;
+    s->pending = token;
+    s->has_pending = 1;
+    return EO_OK;
+}
+
 /* ---------- exit head with adapters ---------- */
 
 /* The paper's exit heads are "adapter layers after each layer" that connect the layer's
@@ -533,6 +547,7 @@ int eo_prefill_embeds(eo_session *s, const uint16_t *emb_bf16, int n_emb, const 
     if (total + 1 > s->max_ctx) return EO_ECAPACITY;
 
     s->kv_len = 0;
+    s->last_M = 0;
     s->has_pending = 0;
     real *h = (real *)malloc((size_t)PREFILL_CHUNK * d * sizeof(real));
     real *logits = (real *)malloc((size_t)PREFILL_CHUNK * V * sizeof(real));
@@ -628,6 +643,8 @@ int eo_verify(eo_session *s, const int32_t *drafts, int gamma, const int32_t *ex
         if (logits_out)
             copy_trace(logits_out + (size_t)e * M * V, hr.logits[e], (size_t)M * V);
     }
+    s->last_P = P;
+    s->last_M = M;
     if (commit) {
         s->kv_len = P + out->accept_len + 1;
         s->pending = out->next_token;

@@ -102,6 +102,8 @@ int eo_verify(eo_session *s, const int32_t *drafts, int gamma, const int32_t *ex
               int n_exits, int commit, eo_result *out, double *logits_out, const eo_trace *trace);
 
 int eo_kv_truncate(eo_session *s, int new_len);
+/* after eo_verify(commit = 0): kv_len = (position of that pass) + delta + 1, pending = token */
+int eo_commit_rows(eo_session *s, int delta, int32_t token);
 int eo_set_pending(eo_session *s, int32_t token);
 int eo_kv_len(const eo_session *s);
 int eo_pending(const eo_session *s, int32_t *token);

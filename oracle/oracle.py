@@ -89,6 +89,7 @@ def _lib(real: str):
                                   P(_Result), vp, P(_Trace)]
         lib.eo_kv_truncate.argtypes = [vp, ctypes.c_int]
         lib.eo_set_pending.argtypes = [vp, ctypes.c_int32]
+        lib.eo_commit_rows.argtypes = [vp, ctypes.c_int, ctypes.c_int32]
         lib.eo_kv_len.argtypes = [vp]
         lib.eo_pending.argtypes = [vp, i32p]
         lib.eo_full_logits.argtypes = [vp, vp, ctypes.c_int, i32p, ctypes.c_int, ctypes.c_int, vp]
@@ -233,6 +234,10 @@ class Session:
 
     def kv_truncate(self, new_len: int):
         _check(self._l.eo_kv_truncate(self._h, new_len), "eo_kv_truncate")
+
+    def commit_rows(self, delta: int, token: int):
+        """Commit of the last verify(commit=False) pass with an accept decision taken outside."""
+        _check(self._l.eo_commit_rows(self._h, delta, token), "eo_commit_rows")
 
     def set_pending(self, token: int):
         _check(self._l.eo_set_pending(self._h, token), "eo_set_pending")
