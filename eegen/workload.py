@@ -59,3 +59,33 @@ def embedding_prefix(seed: int, n_rows: int, d_model: int, session: int = 0) -> 
     """n_rows vectors ~ N(0,1) rounded to bf16 (raw uint16), image-patch stand-ins."""
     x = _rng(seed, 4, session).standard_normal((n_rows, d_model), dtype=np.float32)
     return f32_to_bf16(x).reshape(n_rows, d_model)
+
+
+def draft_distributions(greedy: Sequence[int], vocab: int, seed: int, round_idx: int, session: int = 0,
+                        n_other: int = 12, floor: float = 0.02):
+    """Stand-in for a draft model's output in probabilistic verification: per position a
+    distribution over the vocabulary (float32 rows that sum to 1), a draft token drawn from it,
+    and the uniform numbers of the round.  A position's distribution puts a share alpha ~ U[0.3, 0.95]
+    on the supplied continuation token, spreads `floor` evenly over the whole vocabulary and the rest
+    over n_other random tokens with random shares -- so that drafts agree with a greedy target most
+    of the time, as a trained draft model's do, without any model being run here.
+    Returns (probs [gamma][vocab] float32, drafts [gamma] int32, u [gamma] float32, v [gamma+1] float32)."""
+    g = np.asarray(greedy, dtype=np.int64)
+    gamma = g.shape[0]
+    r = _rng(seed, 5, session, round_idx)
+    probs = np.full((gamma, vocab), floor / vocab, dtype=np.float64)
+    for i in range(gamma):
+        alpha = r.uniform(0.3, 0.95)
+        probs[i, g[i]] += alpha
+        others = r.integers(0, vocab, size=n_other)
+        share = r.dirichlet(np.ones(n_other)) * (1.0 - floor - alpha)
+        np.add.at(probs[i], others, share)
+    probs32 = probs.astype(np.float32)
+    pick = r.random(gamma)
+    cdf = np.cumsum(probs32.astype(np.float64), axis=1)
+    drafts = np.array([min(vocab - 1, int(np.searchsorted(cdf[i], pick[i] * cdf[i, -1], side="right"))) for i in range(gamma)],
+                      dtype=np.int32)
+    lim = np.float32(1.0) - np.float32(2.0 ** -24)
+    u = np.minimum(r.random(gamma).astype(np.float32), lim)
+    v = np.minimum(r.random(gamma + 1).astype(np.float32), lim)
+    return probs32, drafts, u, v

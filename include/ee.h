@@ -72,6 +72,8 @@ extern "C" {
 /* ee_session_create flags */
 #define EE_KEEP_LOGITS 1u     /* keep every head's logits of the last pass (debug)      */
 #define EE_NO_AUTOCOMMIT 2u   /* final accept does not move kv_len / pending            */
+#define EE_SAMPLING 4u        /* the session can run ee_verify_sampled: it holds device room for
+                                 max_gamma draft distributions and for the heads' logits      */
 #define EE_TIME_LAUNCHES 16u  /* measurement: an event pair around every launch of a verify
                                  pass (see ee_launch_times); perturbs the pass slightly    */
 
@@ -176,6 +178,33 @@ int ee_verify_batch(ee_session *const *sessions, int n_sessions, const int32_t *
 #define EE_STATIC_SCRATCH_BYTES (8 << 20)
 int ee_verify_static(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
                      int n_exits, const ee_verify_result **out);
+
+/* Probabilistic verification: VERIFY with the draft model's probability distributions
+   (paper: Background Eq. 2, Methodology Step 2 Eq. 5, Appendix "System Design" Alg. 2
+   LISTENER, which all pass p to VERIFY; the criterion is that of the speculative sampling
+   scheme the paper builds on).  Same pass as ee_verify; every head (exits and final) decides
+   with its own logits z:  q_i = softmax(z_i / temperature) at row i;  draft i+1 (token x) is
+   kept iff u[i] * p_i(x) < q_i(x);  if the round ends at row i < gamma, the row emits the first
+   token k (in id order) with  sum_{j<=k} w_j > v[i] * sum_j w_j,  w = max(q_i - p_i, 0)  (w = q_i
+   if that is zero everywhere);  row gamma emits the same with w = q_gamma.  accept_len /
+   exit_accept_len = the drafts kept before the first one that is not; final_tokens[i] /
+   exit_tokens[e][i] = the token row i emits if the round ends there; next_token =
+   final_tokens[accept_len]; the confidences are those of ee_verify (Eq. 4 on the logits as
+   they are).  Emitted tokens are then distributed as if the target model had sampled them at
+   that temperature.  The random numbers are the caller's: every head uses the same u and v.
+   All pointers are host memory, read before the call returns:
+     draft_probs  [gamma][vocab] fp32, row i = the distribution draft i+1 was drawn from;
+     u            [gamma] in [0,1);   v  [gamma+1] in [0,1);   temperature > 0.
+   The cumulative sums are taken in 40-bit fixed point (exact, order-free), the probabilities
+   in fp32.  One session per pass, created with EE_SAMPLING; gamma <= its max_gamma. */
+typedef struct ee_sampling {
+    const float *draft_probs;
+    const float *u;
+    const float *v;
+    float temperature;
+} ee_sampling;
+int ee_verify_sampled(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
+                      int n_exits, const ee_sampling *sampling, const ee_verify_result **out);
 
 int ee_wait_exit(ee_session *s, int exit_idx);   /* blocks until exit exit_idx is published */
 int ee_query_exit(ee_session *s, int exit_idx);  /* EE_OK or EE_NOT_READY                   */
@@ -283,6 +312,8 @@ int ee_session_option(ee_session *s, int option, int value);
 #define EE_LAUNCH_ADAPTER_UP 6   /* exit-head adapters: output + residual + head norm input */
 #define EE_LAUNCH_ATT 8     /* attention over the paged KV cache                         */
 #define EE_LAUNCH_EMBED 7   /* embedding gather                                          */
+#define EE_LAUNCH_SAMPLE 9  /* ee_verify_sampled: keep tests and draws of a head's rows, accept
+                               rule, publication, KV commit                              */
 int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, int *n_launches);
 
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the

@@ -26,14 +26,15 @@ EE_EINVAL, EE_ESTATE, EE_ECAPACITY, EE_EIO, EE_EFORMAT, EE_EDEVICE = -1, -2, -3,
 HOLD_LAST = 1
 KEEP_LOGITS = 1
 NO_AUTOCOMMIT = 2
+SAMPLING = 4
 TIME_LAUNCHES = 16
 OPT_ATT_SPLITS, OPT_SCATTER_PAGES, OPT_HEAD_BATCH = 1, 2, 3
-LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "adapter_down", "adapter_up", "embed", "att")
+LAUNCH_NAMES = ("qkv", "o", "gu", "dn", "head", "adapter_down", "adapter_up", "embed", "att", "sample")
 
 EXPORTS = [
     "ee_last_error", "ee_model_load", "ee_model_load_ex", "ee_model_free", "ee_model_info",
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
-    "ee_verify_batch", "ee_verify_static", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
+    "ee_verify_batch", "ee_verify_static", "ee_verify_sampled", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
     "ee_debug_logits", "ee_debug_mfma_layout", "ee_device_synchronize", "ee_session_option",
     "ee_launch_times", "ee_debug_copy", "ee_exit_pop", "ee_exit_order", "ee_latency_model",
@@ -53,6 +54,11 @@ class ModelConfigC(ctypes.Structure):
                 ("rope_base", ctypes.c_float), ("rms_eps", ctypes.c_float),
                 ("n_adapters", ctypes.c_int32), ("adapter_width", ctypes.c_int32),
                 ("max_rows", ctypes.c_int32), ("n_workgroups", ctypes.c_int32)]
+
+
+class SamplingC(ctypes.Structure):
+    _fields_ = [("draft_probs", ctypes.POINTER(ctypes.c_float)), ("u", ctypes.POINTER(ctypes.c_float)),
+                ("v", ctypes.POINTER(ctypes.c_float)), ("temperature", ctypes.c_float)]
 
 
 class VerifyResultC(ctypes.Structure):
@@ -105,6 +111,7 @@ def load_library():
     lib.ee_prefill_embeds.argtypes = [vp, vp, ci, i32p, ci, ctypes.c_uint, i32p]
     lib.ee_verify.argtypes = [vp, i32p, ci, i32p, ci, P(P(VerifyResultC))]
     lib.ee_verify_static.argtypes = [vp, i32p, ci, i32p, ci, P(P(VerifyResultC))]
+    lib.ee_verify_sampled.argtypes = [vp, i32p, ci, i32p, ci, P(SamplingC), P(P(VerifyResultC))]
     lib.ee_verify_batch.argtypes = [P(vp), ci, P(i32p), ci, i32p, ci, P(P(VerifyResultC))]
     lib.ee_wait_exit.argtypes = [vp, ci]
     lib.ee_query_exit.argtypes = [vp, ci]
@@ -230,6 +237,21 @@ class Session:
         d, ex = _i32(draft_tokens), _i32(exit_layers)
         res = ctypes.POINTER(VerifyResultC)()
         _check(self._l.ee_verify_static(self._h, _p(d), d.size, _p(ex), ex.size, ctypes.byref(res)))
+        self._res, self._n_exits, self._gamma = res, ex.size, d.size
+
+    def ee_verify_sampled(self, draft_tokens: Sequence[int], draft_probs, u, v, temperature: float = 1.0,
+                          exit_layers: Sequence[int] = ()) -> None:
+        """ee_verify with the draft model's distributions [gamma][vocab] and the caller's uniform numbers."""
+        d, ex = _i32(draft_tokens), _i32(exit_layers)
+        pr = np.ascontiguousarray(draft_probs, dtype=np.float32)
+        uu = np.ascontiguousarray(u, dtype=np.float32)
+        vv = np.ascontiguousarray(v, dtype=np.float32)
+        if pr.ndim != 2 or pr.shape[0] != d.size or pr.shape[1] != self.model.vocab or uu.size != d.size or vv.size != d.size + 1:
+            raise ValueError("draft_probs [gamma][vocab], u [gamma], v [gamma+1] expected")
+        fp = ctypes.POINTER(ctypes.c_float)
+        sm = SamplingC(pr.ctypes.data_as(fp), uu.ctypes.data_as(fp), vv.ctypes.data_as(fp), float(temperature))
+        res = ctypes.POINTER(VerifyResultC)()
+        _check(self._l.ee_verify_sampled(self._h, _p(d), d.size, _p(ex), ex.size, ctypes.byref(sm), ctypes.byref(res)))
         self._res, self._n_exits, self._gamma = res, ex.size, d.size
 
     def ee_wait_exit(self, exit_idx: int) -> None:

@@ -54,7 +54,7 @@ def check_resources(compiler_output: str):
         if m:
             name = m.group(1)
         m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", line)
-        if m and name and int(m.group(1)) > 0 and any(k in name for k in ("gemm_chain", "att_kernel", "misc_kernel")):
+        if m and name and int(m.group(1)) > 0 and any(k in name for k in ("ee_gemm_kernel", "att_kernel", "misc_kernel", "sample_kernel")):
             out.append(f"WARNING: {name} uses {m.group(1)} bytes of scratch per lane (expect slow launches)")
     return out
 

@@ -142,6 +142,17 @@ struct Scratch {
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
+// Probabilistic verification (one session per pass): inputs and per-row decisions.
+struct SampleDev {
+    const float *probs;  // [gamma][V]  the draft model's distributions
+    const float *uv;     // [gamma] keep tests' uniform numbers, then [gamma+1] the rows' sampling numbers
+    float inv_T;         // 1 / temperature
+    int on;              // 1: the pass decides by the draft probabilities instead of by exact match
+    int *tok;            // [head rows]  token a row emits if the round ends there
+    int *kept;           // [head rows]  1: the row's draft passes its test
+    int *count;          // rows of a sampling launch that have delivered; zero between launches
+};
+
 struct PassArgs {
     ModelDev mdv;                        // the model descriptor by value
     GemmPlan plan0;                      // plan, LDS map and weights of the launch's GEMM stage
@@ -172,6 +183,7 @@ struct PassArgs {
     int stage;                           // index of this launch's stage in the segment's stage list
     const SessDev *sess;                 // device array [n_sess]
     SessDev sess0;                       // copy of sess[0]
+    SampleDev sm;
 };
 
 

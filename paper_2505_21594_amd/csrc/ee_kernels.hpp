@@ -1046,14 +1046,28 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
     int *tok = reinterpret_cast<int *>(lds);
     float *conf = reinterpret_cast<float *>(lds) + EE_MAX_ROWS;
     for (int m = wave; m < rows; m += WAVES) {
+        // all of the row's candidates and partial sums are requested before the first is used
+        constexpr int PER = 4;                     // workgroups per lane: the launch has at most 256
+        int2 c[PER];
+        float sg[PER];
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int g = lane + 64 * j;
+            c[j] = make_int2(__float_as_int(-INFINITY), 0x7FFFFFFF);
+            sg[j] = 0.f;
+            if (g < a.nwg) {
+                c[j] = load_cand(a.sc.cand + (size_t)g * md.rows_max + m);
+                sg[j] = load_dev32(a.sc.cand_sum + (size_t)g * md.rows_max + m);
+            }
+        }
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int g = lane; g < a.nwg; g += 64) {
-            int2 c = load_cand(a.sc.cand + (size_t)g * md.rows_max + m);
-            float v = __int_as_float(c.x);
-            if (cand_better(v, c.y, bv, bi)) {
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const float v = __int_as_float(c[j].x);
+            if (cand_better(v, c[j].y, bv, bi)) {
                 bv = v;
-                bi = c.y;
+                bi = c[j].y;
             }
         }
 #pragma unroll
@@ -1068,11 +1082,9 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
         // confidence (paper Eq. 4): max softmax = 1 / sum_j exp(z_j - z_max), from the
         // workgroups' sums, each rescaled from its own maximum to the global one
         float se = 0.f;
-        for (int g = lane; g < a.nwg; g += 64) {
-            const float vg = __int_as_float(load_cand(a.sc.cand + (size_t)g * md.rows_max + m).x);
-            const float sg = load_dev32(a.sc.cand_sum + (size_t)g * md.rows_max + m);
-            if (sg > 0.f) se += sg * __expf(vg - bv);
-        }
+#pragma unroll
+        for (int j = 0; j < PER; ++j)
+            if (sg[j] > 0.f) se += sg[j] * __expf(__int_as_float(c[j].x) - bv);
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) se += __shfl_xor(se, off, 64);
         if (lane == 0) {
@@ -1095,13 +1107,25 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
             sd.state[1] = last;
         } else {
             const int gamma = M - 1;
-            int dr[EE_MAX_M];
-#pragma unroll
-            for (int i = 0; i < EE_MAX_M - 1; ++i) dr[i] = i < gamma ? sd.drafts[i] : -1;
             int delta = 0;
+            if (a.sm.on) {
+                // probabilistic verification: the rows' decisions were taken by the sampling launch;
+                // the tokens published are the ones each row emits if the round ends there
+                int *ts = tok + (hj * a.n_sess + s) * M;
+                unsigned kept = 0;
+                for (int i = 0; i < M; ++i) {
+                    ts[i] = __hip_atomic_load(a.sm.tok + hj * M + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (i < gamma && __hip_atomic_load(a.sm.kept + hj * M + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) kept |= 1u << i;
+                }
+                delta = __builtin_ctz(~kept);   // drafts kept before the first one that is not (bit gamma is never set)
+            } else {
+                int dr[EE_MAX_M];
 #pragma unroll
-            for (int i = 0; i < EE_MAX_M - 1; ++i)
-                if (delta == i && i < gamma && dr[i] == t[i]) delta = i + 1;
+                for (int i = 0; i < EE_MAX_M - 1; ++i) dr[i] = i < gamma ? sd.drafts[i] : -1;
+#pragma unroll
+                for (int i = 0; i < EE_MAX_M - 1; ++i)
+                    if (delta == i && i < gamma && dr[i] == t[i]) delta = i + 1;
+            }
             if (a.head_kind == HEAD_EXIT) {
                 for (int i = 0; i < M; ++i) {
                     res->exit_tokens[head][i] = t[i];
@@ -1123,6 +1147,189 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
             }
         }
         __threadfence_system();
+    }
+}
+
+// ------------------------------------------------------------------ probabilistic verification
+
+// Weights of the cumulative sums are 40-bit fixed point (integers): their sums do not depend on
+// the order of addition, so every thread's share [exclusive sum, + own sum) of the cumulative
+// distribution tiles it exactly and the search below always ends inside the owner's tokens.
+// A weight is at most 1 (largest exp term, or a probability) and a row has at most 2^15 tokens.
+typedef unsigned long long u64;
+constexpr int SAMPLE_LDS_BYTES = 4096;             // the waves' sums and flags; the accept step's rows
+constexpr float SAMPLE_UNIT = 1099511627776.0f;  // 2^40
+
+__device__ __forceinline__ u64 fixed_weight(float w) { return (u64)(w * SAMPLE_UNIT); }
+
+// e_k = exp((z_k - zmax) / T): un-normalised probability of token k under the target distribution
+__device__ __forceinline__ float target_term(float z, float zmax, float inv_T) { return expf((z - zmax) * inv_T); }
+
+// positive part of q_k - p_k (one fused multiply-add, so that every place that forms it gets the same bits)
+__device__ __forceinline__ float residual_term(float e, float inv_Z, float p) { return fmaxf(__fmaf_rn(e, inv_Z, -p), 0.f); }
+
+// sum of one 64-bit value per lane over the wave (every lane gets it)
+__device__ __forceinline__ u64 wave_sum(u64 x)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+constexpr int SAMPLE_CH = 22;   // blocks of 64 tokens a wave requests in one go (all loads in flight together)
+
+// values first + 64 j + lane, j < SAMPLE_CH, of a row; `fill` past the end t1
+__device__ __forceinline__ void load_chunk(const EE_GLOBAL float *row, int first, int t1, int lane, float fill, float (&out)[SAMPLE_CH])
+{
+#pragma unroll
+    for (int j = 0; j < SAMPLE_CH; ++j) {
+        const int k = first + 64 * j + lane;
+        out[j] = k < t1 ? row[k] : fill;
+    }
+}
+
+// One row of one head under probabilistic verification (Eq. 2 / Eq. 5 of the paper with the
+// draft model's distributions; the keep / replace rule of the speculative sampling scheme the
+// paper builds on).  q = softmax(z / T) of the row's logits.  Row i < gamma: its draft x is kept
+// iff u_i * p_i(x) < q(x), and if the round ends here the row emits a token drawn from the
+// positive part of q - p_i; row gamma emits a token drawn from q.  Drawing = inversion of the
+// cumulative sum in token order with the row's number v_i: the first token whose cumulative
+// weight exceeds v_i * (sum of the weights).
+//
+// Wave w owns the tokens [w * S, (w + 1) * S) and walks them in chunks of SAMPLE_CH blocks of
+// 64 (lane l: token first + 64 j + l, coalesced; a chunk's loads are all requested before the
+// first is used: a pass over the row costs one memory latency per chunk, not one per token).
+// The sums are integers, so the cumulative sum up to a token is the earlier waves' totals + this
+// wave's earlier blocks + a scan inside the block, whatever the order they were added in.
+__device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds)
+{
+    static_assert(WAVES * 8 * 2 + WAVES * 4 + 16 <= SAMPLE_LDS_BYTES && EE_MAX_ROWS * 8 <= SAMPLE_LDS_BYTES, "LDS of the sampling launch");
+    const int V = a.mdv.V, M = a.M, gamma = M - 1;
+    const int hj = r / M, i = r - hj * M;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    u64 *wtot = reinterpret_cast<u64 *>(lds);                   // [WAVES] the waves' totals (target terms)
+    u64 *rtot = wtot + WAVES;                                   // [WAVES] the same for the residual weights
+    float *wmax = reinterpret_cast<float *>(rtot + WAVES);      // [WAVES]
+    int *found = reinterpret_cast<int *>(wmax + WAVES);
+    const EE_GLOBAL float *z = as_global(a.sc.logits) + ((size_t)(a.head_idx + hj) * a.mdv.rows_max + i) * V;
+    const EE_GLOBAL float *p = as_global(a.sm.probs) + (size_t)min(i, gamma - 1) * V;
+    const float inv_T = a.sm.inv_T;
+    const int S = ((V + WAVES - 1) / WAVES + 63) & ~63;         // tokens per wave, whole blocks of 64
+    const int t0 = min(V, wave * S), t1 = min(V, t0 + S);
+    constexpr int CHUNK = SAMPLE_CH * 64;
+    float zc[SAMPLE_CH], pc[SAMPLE_CH];
+
+    // largest logit
+    float mx = -INFINITY;
+    for (int c0 = t0; c0 < t1; c0 += CHUNK) {
+        load_chunk(z, c0, t1, lane, -INFINITY, zc);
+#pragma unroll
+        for (int j = 0; j < SAMPLE_CH; ++j) mx = fmaxf(mx, zc[j]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if (lane == 0) wmax[wave] = mx;
+    if (tid == 0) *found = 0;
+    __syncthreads();
+    float zmax = wmax[0];
+#pragma unroll
+    for (int w = 1; w < WAVES; ++w) zmax = fmaxf(zmax, wmax[w]);
+
+    // Z = sum_k e_k  (a logit of -inf past the row's end contributes exp(-inf) = 0)
+    u64 part = 0;
+    for (int c0 = t0; c0 < t1; c0 += CHUNK) {
+        load_chunk(z, c0, t1, lane, -INFINITY, zc);
+#pragma unroll
+        for (int j = 0; j < SAMPLE_CH; ++j) part += fixed_weight(target_term(zc[j], zmax, inv_T));
+    }
+    part = wave_sum(part);
+    if (lane == 0) wtot[wave] = part;
+    __syncthreads();
+    u64 Zi = 0;
+#pragma unroll
+    for (int w = 0; w < WAVES; ++w) Zi += wtot[w];
+    const float inv_Z = 1.0f / (float)((double)Zi * (1.0 / (double)SAMPLE_UNIT));
+
+    const u64 *tot = wtot;
+    u64 w_total = Zi;
+    bool residual = false;
+    int kept = 0;
+    if (i < gamma) {
+        const int x = as_global(a.sess0.drafts)[i];
+        const float qx = target_term(z[x], zmax, inv_T) * inv_Z;
+        kept = as_global(a.sm.uv)[i] * p[x] < qx ? 1 : 0;
+        u64 rp = 0;
+        for (int c0 = t0; c0 < t1; c0 += CHUNK) {
+            load_chunk(z, c0, t1, lane, -INFINITY, zc);
+            load_chunk(p, c0, t1, lane, 0.f, pc);
+#pragma unroll
+            for (int j = 0; j < SAMPLE_CH; ++j) rp += fixed_weight(residual_term(target_term(zc[j], zmax, inv_T), inv_Z, pc[j]));
+        }
+        rp = wave_sum(rp);
+        if (lane == 0) rtot[wave] = rp;
+        __syncthreads();
+        u64 W = 0;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) W += rtot[w];
+        if (W > 0) {  // otherwise q = p: the draft is always kept and the row never emits; it then draws from q
+            residual = true;
+            tot = rtot;
+            w_total = W;
+        }
+    }
+    // the first token whose cumulative weight exceeds the target; v < 1, so target < w_total
+    const double vd = (double)as_global(a.sm.uv)[gamma + i];
+    u64 target = (u64)(vd * (double)w_total);
+    if (target >= w_total) target = w_total - 1;
+    u64 before = 0;                                              // cumulative weight of the waves before this one
+    for (int w = 0; w < wave; ++w) before += tot[w];
+    if (before <= target && target < before + tot[wave]) {      // exactly one wave
+        u64 run = before;
+        bool done = false;
+        for (int c0 = t0; c0 < t1 && !done; c0 += CHUNK) {
+            load_chunk(z, c0, t1, lane, -INFINITY, zc);
+            if (residual) load_chunk(p, c0, t1, lane, 0.f, pc);
+            // the blocks' sums first, all of them (independent reductions overlap), then the search
+            u64 wk[SAMPLE_CH], blk[SAMPLE_CH];
+#pragma unroll
+            for (int j = 0; j < SAMPLE_CH; ++j) {
+                const float e = target_term(zc[j], zmax, inv_T);
+                wk[j] = fixed_weight(residual ? residual_term(e, inv_Z, pc[j]) : e);
+            }
+#pragma unroll
+            for (int j = 0; j < SAMPLE_CH; ++j) {
+                const u64 t = wave_sum(wk[j]);
+                blk[j] = ((u64)(unsigned)__builtin_amdgcn_readfirstlane((int)(t >> 32)) << 32) | (unsigned)__builtin_amdgcn_readfirstlane((int)t);
+            }
+            int jh = -1;
+            u64 mine = 0;
+#pragma unroll
+            for (int j = 0; j < SAMPLE_CH; ++j)
+                if (jh < 0) {
+                    if (run + blk[j] > target) {
+                        jh = j;
+                        mine = wk[j];
+                    } else {
+                        run += blk[j];
+                    }
+                }
+            if (jh >= 0) {                                       // the token is in block jh: scan it
+                u64 incl = mine;
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const u64 o = __shfl_up(incl, off, 64);
+                    if (lane >= off) incl += o;
+                }
+                const unsigned long long hit = __ballot(run + incl > target);
+                if (lane == 0) *found = c0 + 64 * jh + __builtin_ctzll(hit);
+                done = true;
+            }
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_store(a.sm.tok + r, *found, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.sm.kept + r, kept, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -1236,6 +1443,26 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_kernel(PassArgs a_by_value
         __syncthreads();
         if (*lastf) accept_stage(a, lds);
     }
+}
+
+// Probabilistic verification: one workgroup per row of the head launch before it (whose logits
+// it reads); the workgroup that finishes last applies the accept rule and publishes, as the
+// head launch's last workgroup does under exact-match verification.
+__global__ void __launch_bounds__(WG_THREADS) ee_sample_kernel(PassArgs a_by_value)
+{
+    extern __shared__ __align__(16) char lds[];
+    const PassArgs &a = warmed_arguments();
+    sample_stage(a, blockIdx.x, lds);
+    int *lastf = reinterpret_cast<int *>(lds + SAMPLE_LDS_BYTES - 16);   // behind sample_stage's and the accept step's arrays
+    wait_vmem();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int before = __hip_atomic_fetch_add(a.sm.count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *lastf = before == (int)gridDim.x - 1 ? 1 : 0;
+        if (*lastf) __hip_atomic_store(a.sm.count, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (*lastf) accept_stage(a, lds);
 }
 
 template <int HD>

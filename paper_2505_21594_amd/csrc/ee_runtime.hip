@@ -75,6 +75,9 @@ struct ee_session {
     int *dev_state;
     int *dev_drafts;
     int *host_drafts;                // pinned
+    float *host_sample;              // pinned staging of a sampled pass: draft distributions, then u, then v (EE_SAMPLING)
+    float *dev_sample;               // device copy of the same
+    int *dev_sample_out;             // [2 * EE_MAX_ROWS + 1] rows' tokens, keep flags, arrival counter
     int *dev_pf_tokens;
     int *host_pf_tokens;             // pinned
     uint16_t *dev_pf_emb;
@@ -348,7 +351,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     ee_model *m = new (std::nothrow) ee_model();
     if (!m) return fail(EE_EDEVICE, "out of host memory");
     m->device = device;
-    m->nwg = prop.multiProcessorCount;
+    m->nwg = std::min(prop.multiProcessorCount, 256);   // one workgroup per compute unit; the accept step reads at most 256 candidates per row
     c.max_rows = max_rows;
     c.n_workgroups = m->nwg;
     m->cfg = c;
@@ -571,6 +574,7 @@ extern "C" int ee_session_free(ee_session *s)
     for (void *p : s->allocs) hipFree(p);
     if (s->host_page_table) hipHostFree(s->host_page_table);
     if (s->host_drafts) hipHostFree(s->host_drafts);
+    if (s->host_sample) hipHostFree(s->host_sample);
     if (s->host_pf_tokens) hipHostFree(s->host_pf_tokens);
     if (s->result) hipHostFree(s->result);
     if (s->host_sessdev) hipHostFree(s->host_sessdev);
@@ -693,8 +697,14 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
         S_TRY(dev_alloc(s->allocs, &sc.att_count, max_units));
         S_TRY(dev_alloc(s->allocs, &sc.head_count, 1));
     }
-    if (flags & EE_KEEP_LOGITS)
+    if (flags & (EE_KEEP_LOGITS | EE_SAMPLING))
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
+    if (flags & EE_SAMPLING) {
+        const size_t n = (size_t)max_gamma * c.vocab + 2 * (size_t)max_gamma + 1;
+        S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_sample), n * sizeof(float), hipHostMallocDefault));
+        S_TRY(dev_alloc(s->allocs, &s->dev_sample, n));
+        S_TRY(dev_alloc(s->allocs, &s->dev_sample_out, 2 * EE_MAX_ROWS + 1));
+    }
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.cand_sum, (size_t)m->nwg * rows_max));
     S_HIP(hipDeviceSynchronize());
@@ -783,7 +793,7 @@ static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
         if (code < 0) break;
         const bool gemm = code != EE_LAUNCH_EMBED && code != EE_LAUNCH_ATT;
         a.stage = ph;
-        a.fuse_accept = code == EE_LAUNCH_HEAD ? 1 : 0;
+        a.fuse_accept = (code == EE_LAUNCH_HEAD && !a.sm.on) ? 1 : 0;
         a.rows = code == EE_LAUNCH_HEAD ? a.head_rows : rows;   // the head launch carries the rows of all exits of its group
         pass_kernel_t k = gemm ? gemm_kernel(a.rows) : (code == EE_LAUNCH_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
         if (gemm) {  // the stage's plan, LDS map and weights travel with the launch
@@ -809,6 +819,23 @@ static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
         hipLaunchKernelGGL(k, dim3(m->nwg), dim3(WG_THREADS), m->lds_budget, lead->run_stream, a);
         HIP_TRY(hipGetLastError());
         if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->run_stream));
+        if (code == EE_LAUNCH_HEAD && a.sm.on) {
+            // probabilistic verification: the rows' keep tests and draws, one workgroup per head row,
+            // then the accept rule and the publication (in the workgroup that finishes last)
+            if (timed) {
+                const size_t i = lead->lt_codes.size();
+                while (lead->lt_events.size() < 2 * (i + 1)) {
+                    hipEvent_t ev;
+                    HIP_TRY(hipEventCreate(&ev));
+                    lead->lt_events.push_back(ev);
+                }
+                lead->lt_codes.push_back(EE_LAUNCH_SAMPLE);
+                HIP_TRY(hipEventRecord(lead->lt_events[2 * i], lead->run_stream));
+            }
+            hipLaunchKernelGGL(ee_sample_kernel, dim3(a.head_rows), dim3(WG_THREADS), SAMPLE_LDS_BYTES, lead->run_stream, a);
+            HIP_TRY(hipGetLastError());
+            if (timed) HIP_TRY(hipEventRecord(lead->lt_events[2 * lead->lt_codes.size() - 1], lead->run_stream));
+        }
     }
     a.rows = rows;
     return EE_OK;
@@ -1051,7 +1078,8 @@ static int use_static_scratch(ee_session *lead, PassArgs &a, int M, int n_pos_ma
 // static_scratch: run the pass on the library's static scratch array instead of the leader's own
 // buffers (ee_verify_static); nothing on this path allocates.
 static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
-                       const int32_t *exit_layers, int n_exits, const ee_verify_result **outs, bool static_scratch)
+                       const int32_t *exit_layers, int n_exits, const ee_verify_result **outs, bool static_scratch,
+                       const ee_sampling *sp = nullptr)
 {
     if (!sessions || !drafts || n_sessions < 1 || n_sessions > EE_MAX_BATCH)
         return fail(EE_EINVAL, "ee_verify: n_sessions %d not in [1,%d]", n_sessions, EE_MAX_BATCH);
@@ -1075,6 +1103,20 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
             return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
     }
     if (n_sessions * M > c.max_rows) return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, c.max_rows);
+    if (sp) {
+        if (n_sessions != 1 || static_scratch) return fail(EE_EINVAL, "ee_verify_sampled: one session per pass");
+        if (!(lead->flags & EE_SAMPLING)) return fail(EE_ESTATE, "ee_verify_sampled: the session was created without EE_SAMPLING");
+        if (!sp->draft_probs || !sp->u || !sp->v) return fail(EE_EINVAL, "ee_verify_sampled: null draft_probs, u or v");
+        if (!(sp->temperature > 0.f) || !std::isfinite(sp->temperature)) return fail(EE_EINVAL, "ee_verify_sampled: temperature must be positive");
+        for (int i = 0; i < gamma; ++i)
+            if (!(sp->u[i] >= 0.f && sp->u[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: u[%d] not in [0,1)", i);
+        for (int i = 0; i <= gamma; ++i)
+            if (!(sp->v[i] >= 0.f && sp->v[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: v[%d] not in [0,1)", i);
+        for (int i = 0; i < gamma; ++i) {   // the drafts' own probabilities; the full rows are the caller's responsibility
+            const float px = sp->draft_probs[(size_t)i * c.vocab + drafts[0][i]];
+            if (!(px >= 0.f && px <= 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: draft_probs[%d][draft] = %g is not a probability", i, (double)px);
+        }
+    }
     const float *gains[EE_MAX_EXITS];
     int slots[EE_MAX_EXITS];
     int rc = check_exits(m, exit_layers, n_exits, gains, slots);
@@ -1116,6 +1158,21 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
     a.rows = n_sessions * M;
     a.mode = 0;
     a.commit = (lead->flags & EE_NO_AUTOCOMMIT) ? 0 : 1;
+    if (sp) {
+        const size_t V = (size_t)c.vocab, n = (size_t)gamma * V + 2 * (size_t)gamma + 1;
+        memcpy(lead->host_sample, sp->draft_probs, (size_t)gamma * V * sizeof(float));
+        memcpy(lead->host_sample + (size_t)gamma * V, sp->u, (size_t)gamma * sizeof(float));
+        memcpy(lead->host_sample + (size_t)gamma * V + gamma, sp->v, (size_t)(gamma + 1) * sizeof(float));
+        HIP_TRY(hipMemcpyAsync(lead->dev_sample, lead->host_sample, n * sizeof(float), hipMemcpyHostToDevice, lead->run_stream));
+        a.sm.probs = lead->dev_sample;
+        a.sm.uv = lead->dev_sample + (size_t)gamma * V;
+        a.sm.inv_T = 1.0f / sp->temperature;
+        a.sm.on = 1;
+        a.sm.tok = lead->dev_sample_out;
+        a.sm.kept = lead->dev_sample_out + EE_MAX_ROWS;
+        a.sm.count = lead->dev_sample_out + 2 * EE_MAX_ROWS;
+        a.keep_logits = 1;   // the sampling launch reads the head launch's logits
+    }
     for (int i = 0; i < n_sessions; ++i) fill_sessdev(lead->host_sessdev[i], sessions[i]);
     HIP_TRY(hipMemcpyAsync(lead->dev_sessdev, lead->host_sessdev, (size_t)n_sessions * sizeof(SessDev),
                            hipMemcpyHostToDevice, lead->run_stream));
@@ -1182,6 +1239,19 @@ extern "C" int ee_verify(ee_session *s, const int32_t *draft_tokens, int gamma, 
     const int32_t *dd[1] = {draft_tokens};
     const ee_verify_result *oo[1] = {nullptr};
     int rc = verify_impl(ss, 1, dd, gamma, exit_layers, n_exits, oo, false);
+    if (rc == EE_OK && out) *out = oo[0];
+    return rc;
+}
+
+extern "C" int ee_verify_sampled(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers, int n_exits,
+                                 const ee_sampling *sampling, const ee_verify_result **out)
+{
+    if (!s) return fail(EE_EINVAL, "ee_verify_sampled: null session");
+    if (!sampling) return fail(EE_EINVAL, "ee_verify_sampled: null sampling arguments");
+    ee_session *ss[1] = {s};
+    const int32_t *dd[1] = {draft_tokens};
+    const ee_verify_result *oo[1] = {nullptr};
+    int rc = verify_impl(ss, 1, dd, gamma, exit_layers, n_exits, oo, false, sampling);
     if (rc == EE_OK && out) *out = oo[0];
     return rc;
 }

@@ -6,7 +6,7 @@ import pytest
 import eegen
 import paper_2505_21594_amd as ee
 from oracle import oracle as eo
-from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill
+from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill, sampled_chain
 
 pytestmark = pytest.mark.gpu
 
@@ -593,3 +593,75 @@ def test_exit_heads_in_groups_match_one_by_one(model_dir, adapters):
             gs.free()
     finally:
         g.free()
+
+
+@pytest.mark.parametrize("temperature", [1.0, 0.1, 0.05])
+def test_sampled_verification_tiny(tiny_pair, temperature):
+    g, o = tiny_pair
+    prompt = eegen.prompt_tokens(41, 48, o.vocab)
+    rounds, gamma = 24, 4
+    exempt_rounds, bound, kept, more = sampled_chain(g, o, prompt, gamma, TINY_EXITS, rounds, temperature, seed=21, what=f"sampled tiny T={temperature}")
+    print(f"sampled tiny T={temperature}: bound {bound} of {rounds * 2 * (gamma + 2)}, exempt rounds {exempt_rounds}, drafts kept {kept}, "
+          f"rounds that keep more than exact match {more}")
+    # the comparison must bind almost everywhere: 2 heads x (gamma + 1 draws + 1 accept length) per round
+    assert bound >= 0.8 * rounds * 2 * (gamma + 2), (bound, exempt_rounds)
+
+
+def test_sampled_verification_mid(mid_pair):
+    g, o = mid_pair
+    prompt = eegen.prompt_tokens(43, 90, o.vocab)
+    rounds, gamma = 6, 7
+    exempt_rounds, bound, kept, more = sampled_chain(g, o, prompt, gamma, [1, 2], rounds, 0.2, seed=22, what="sampled mid")
+    print(f"sampled mid: bound {bound} of {rounds * 3 * (gamma + 2)}, exempt rounds {exempt_rounds}, drafts kept {kept}, more than exact match {more}")
+    assert bound >= 0.8 * rounds * 3 * (gamma + 2), (bound, exempt_rounds)
+
+
+def test_sampled_verification_special_cases(tiny_pair):
+    """One-hot draft distributions at a low temperature reproduce the exact-match pass; the draft
+    model's own distribution equal to the target's keeps every draft; argument checks."""
+    g, o = tiny_pair
+    V = o.vocab
+    prompt = eegen.prompt_tokens(44, 40, V)
+    gs = g.session(128, max_gamma=4, flags=ee.KEEP_LOGITS | ee.SAMPLING | ee.NO_AUTOCOMMIT)
+    os_ = o.session(128)
+    try:
+        first_o, margin = oracle_prefill(os_, prompt)
+        check_first_token(gs, gs.ee_prefill(prompt), first_o, margin)
+        greedy = oracle_greedy(os_, 4)
+        drafts = [greedy[0], greedy[1], (greedy[2] + 5) % V, greedy[3]]
+        ro = os_.verify(drafts, TINY_EXITS, commit=False, want_logits=True)
+        exact = gs.verify_sync(drafts, TINY_EXITS)
+        onehot = np.zeros((4, V), dtype=np.float32)
+        onehot[np.arange(4), drafts] = 1.0
+        gs.ee_verify_sampled(drafts, onehot, [0.5] * 4, [0.5] * 5, 1e-3, TINY_EXITS)
+        gs.ee_wait_final()
+        rs = gs.final_result()
+        if eo.top2_margin(ro.logits).min() >= 1e-2:
+            assert rs.accept_len == exact.accept_len == ro.accept_len
+            assert rs.next_token == exact.next_token
+            assert rs.exit_accept_len[0] == exact.exit_accept_len[0]
+            assert rs.exit_tokens[0][rs.exit_accept_len[0]] == exact.exit_tokens[0][exact.exit_accept_len[0]]
+        # p = q (the oracle's own target distribution for these drafts): every draft is kept
+        d2 = [int(t) for t in greedy]
+        ro2 = os_.verify(d2, [], commit=False, want_logits=True)
+        q2 = np.stack([np.exp(ro2.logits[-1][i] - ro2.logits[-1][i].max()) for i in range(4)])
+        q2 = (q2 / q2.sum(axis=1, keepdims=True)).astype(np.float32)
+        gs.ee_verify_sampled(d2, q2, [0.9] * 4, [0.3] * 5, 1.0, [])
+        gs.ee_wait_final()
+        # u = 0.9 < 1 = q/p up to the logit error: kept unless q(x) deviates by 10 %
+        assert gs.final_result().accept_len == 4
+        # argument checks
+        for bad in (dict(u=[1.0, 0, 0, 0]), dict(v=[0, 0, 0, 0, -0.1]), dict(temperature=0.0)):
+            kw = dict(u=[0.5] * 4, v=[0.5] * 5, temperature=1.0)
+            kw.update(bad)
+            with pytest.raises(ee.EEError) as ei:
+                gs.ee_verify_sampled(d2, q2, kw["u"], kw["v"], kw["temperature"], [])
+            assert ei.value.code == ee.EE_EINVAL
+        plain = g.session(64, max_gamma=4)
+        plain.ee_prefill(prompt[:8])
+        with pytest.raises(ee.EEError) as ei:
+            plain.ee_verify_sampled(d2, q2, [0.5] * 4, [0.5] * 5, 1.0, [])
+        assert ei.value.code == ee.EE_ESTATE
+        plain.free()
+    finally:
+        gs.free()

@@ -15,7 +15,7 @@ import pytest
 import eegen
 import paper_2505_21594_amd as ee
 from oracle import oracle as eo
-from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill
+from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill, sampled_chain
 
 pytestmark = pytest.mark.gpu
 
@@ -243,3 +243,24 @@ def test_llama7b_31_exits_with_adapters(capsys):
     finally:
         if os.path.exists(path):
             os.remove(path)
+
+
+@pytest.mark.timeout(600)
+def test_llama7b_probabilistic_verification(llama7b_path, capsys):
+    """Probabilistic verification at full size: 8 rounds, gamma 4, exits 8 and 16, temperature 0.2
+    (the random-weight model's logits have a standard deviation of about 1.3 over 32000 tokens; at
+    this temperature its distributions are as peaked as a trained model's, so keep tests and draws
+    are decided away from their thresholds and the comparison with the oracle binds)."""
+    cfg = eegen.LLAMA7B
+    g = ee.Model(llama7b_path, max_rows=5)
+    o = eo.Model(llama7b_path)
+    prompt = eegen.prompt_tokens(20250522, 128, cfg.vocab)
+    rounds, gamma = 8, 4
+    try:
+        exempt_rounds, bound, kept, more = sampled_chain(g, o, prompt, gamma, [8, 16], rounds, 0.2, 20250522, "7B sampled",
+                                                        say=lambda m: _say(capsys, m))
+        _say(capsys, f"[7B sampled] decisions bound {bound} of {rounds * 3 * (gamma + 2)}, exempt rounds {exempt_rounds}, drafts kept {kept}")
+        assert bound >= 0.7 * rounds * 3 * (gamma + 2)
+    finally:
+        g.free()
+        o.close()
