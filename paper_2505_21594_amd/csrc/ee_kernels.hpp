@@ -300,8 +300,12 @@ __device__ __forceinline__ void load_rstd(const float *ss, int nwg, int rows_max
                                           float *rstd_lds, int hwave, int lane)
 {
     for (int m = hwave; m < rows; m += HWAVES) {
+        float v[4];                                              // at most 256 workgroups: all four requested together
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = lane + 64 * j < nwg ? *as_global(ss + (size_t)(lane + 64 * j) * rows_max + m) : 0.f;
         float s = 0.f;
-        for (int g = lane; g < nwg; g += 64) s += *as_global(ss + (size_t)g * rows_max + m);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) s += v[j];
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
         if (lane == 0) rstd_lds[m] = 1.0f / sqrtf(s / (float)d + eps);
@@ -617,20 +621,6 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
     } else {
         // ---------------- helper wave: input blocks, row factors, per-row cache addresses
         const int hwave = wave - SWAVES;
-        if (first_group) {
-            if (in.ss) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd, hwave, lane);
-            const int ht = tid - SWAVES * 64;
-            if (kind == G_QKV && ht < rows) {
-                const int m = ht;
-                const int pos = row_pos(a, m);
-                const int ses = a.mode == 1 ? 0 : m / a.M;
-                const int cbase = EE_SESS(a, ses, contig_base);
-                const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
-                mi.pos[m] = pos;
-                mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
-            }
-            wait_vmem();
-        }
         // Input blocks through a ring of ly.nbuf buffers: nbuf - 1 blocks are requested ahead of the
         // one being read, so that the copy of a block has the time of a whole block (or two) to arrive.
         // Block b is announced (barrier) once its own loads have landed, i.e. when only the loads of
@@ -650,6 +640,22 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
                 request(issued);
                 ++issued;
             }
+        }
+        // what only the epilogue needs, once the input is on its way: row factors, cache addresses
+        // (ahead of the input copy they delayed the first MFMA of every launch by about 2 us)
+        if (first_group) {
+            if (in.ss) load_rstd(in.ss, a.nwg, md.rows_max, rows, pl.K, md.eps, mi.rstd, hwave, lane);
+            const int ht = tid - SWAVES * 64;
+            if (kind == G_QKV && ht < rows) {
+                const int m = ht;
+                const int pos = row_pos(a, m);
+                const int ses = a.mode == 1 ? 0 : m / a.M;
+                const int cbase = EE_SESS(a, ses, contig_base);
+                const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
+                mi.pos[m] = pos;
+                mi.kvoff[m] = (((long long)layer * EE_SESS(a, ses, n_pages) + page) * md.H) * KV_PAGE * 2 * md.hd;  // record of head 0
+            }
+            wait_vmem();
         }
     }
     // ---- cross-wave sum and epilogue, ly.chunk n-tiles at a time (the input buffers are free now)
