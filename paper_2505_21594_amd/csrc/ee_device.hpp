@@ -71,17 +71,34 @@ struct StageLds {
 // the XCDs and then over the XCD's workgroups: with U not a multiple of nwg, a plain split
 // over g loads some XCDs up to 20 % more than others and the launch ends with them.
 constexpr int NUM_XCD = 8;
+// x / d for 0 <= x <= DIV_SMALL_MAX and d >= 1.  The GPU has no integer division: a 32-bit one is
+// about 40 instructions in a dependent chain, a 64-bit one several hundred, and the kernels divide
+// by run-time values on the way to their first load, at every block boundary of the stream and in
+// every epilogue item.  One reciprocal (1 ulp) and one multiply give the exact quotient in this
+// range: (x + 0.5) / d is at least 0.5 / d away from an integer and the error of the product is
+// below (x + 0.5) / d * 1.8e-7, which is less than 0.5 / d for x < 2.7e6.
+constexpr int DIV_SMALL_MAX = 1 << 21;
+__host__ __device__ inline int div_small(int x, int d)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (int)(((float)x + 0.5f) * __builtin_amdgcn_rcpf((float)d));
+#else
+    return x / d;
+#endif
+}
+
+// (host: U * nwg <= DIV_SMALL_MAX is checked when the model is loaded)
 __host__ __device__ inline void unit_range(int U, int nwg, int g, int &u0, int &u1)
 {
     if (nwg % NUM_XCD != 0) {
-        u0 = (int)((long long)U * g / nwg);
-        u1 = (int)((long long)U * (g + 1) / nwg);
+        u0 = div_small(U * g, nwg);
+        u1 = div_small(U * (g + 1), nwg);
         return;
     }
     const int x = g % NUM_XCD, j = g / NUM_XCD, per = nwg / NUM_XCD;
-    const int x0 = (int)((long long)U * x / NUM_XCD), x1 = (int)((long long)U * (x + 1) / NUM_XCD);
-    u0 = x0 + (int)((long long)(x1 - x0) * j / per);
-    u1 = x0 + (int)((long long)(x1 - x0) * (j + 1) / per);
+    const int x0 = U * x / NUM_XCD, x1 = U * (x + 1) / NUM_XCD;
+    u0 = x0 + div_small((x1 - x0) * j, per);
+    u1 = x0 + div_small((x1 - x0) * (j + 1), per);
 }
 
 enum RowPerm { PERM_NONE = 0, PERM_QKV = 1, PERM_GU = 2 };

@@ -179,14 +179,14 @@ __device__ __forceinline__ T sess_pick(bool first, const T &own, const T *other)
 __device__ __forceinline__ int row_pos(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_pos0 + r;
-    int s = r / a.M;
+    int s = div_small(r, a.M);
     return EE_SESS(a, s, kv_len) + (r - s * a.M);
 }
 
 __device__ __forceinline__ int row_token(const PassArgs &a, int r)
 {
     if (a.mode == 1) return a.pf_tokens[r];
-    int s = r / a.M, i = r - s * a.M;
+    int s = div_small(r, a.M), i = r - s * a.M;
     return i == 0 ? EE_SESS(a, s, pending) : EE_SESS(a, s, drafts)[i - 1];
 }
 
@@ -338,7 +338,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     if (kind == G_GU) {
         const int items = (gn >> 1) * rows * 4;
         for (int idx = tid; idx < items; idx += WG_THREADS) {
-            int p = idx / (rows * 4), rem = idx - p * rows * 4;
+            int p = div_small(idx, rows * 4), rem = idx - p * rows * 4;
             int m = rem >> 2, qd = rem & 3;
             const float *sg = slots + ((size_t)(2 * p) * rows + m) * 16 + qd * 4;
             const float *su = sg + (size_t)rows * 16;
@@ -363,7 +363,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     float *zbuf = reinterpret_cast<float *>(lds + ly.zbuf_off);  // head: [rows][chunk*16] logits of this chunk; O/DN: squares
     const int items = gn * rows * 4;
     for (int idx = tid; idx < items; idx += WG_THREADS) {
-        int ntg = idx / (rows * 4), rem = idx - ntg * rows * 4;
+        int ntg = div_small(idx, rows * 4), rem = idx - ntg * rows * 4;
         int m = rem >> 2, qd = rem & 3;
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -413,9 +413,9 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const int d = md.d, hd = md.hd;
             const float rs = mi.rstd[m];
             float v[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
-            const int sect = n / d, c = n - sect * d;
-            const int head = c / hd, e = c - head * hd;
-            const int ses = a.mode == 1 ? 0 : m / a.M;
+            const int sect = div_small(n, d), c = n - sect * d;
+            const int head = div_small(c, hd), e = c - head * hd;
+            const int ses = a.mode == 1 ? 0 : div_small(m, a.M);
             if (sect < 2) {
                 // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2; (cos, sin) of the row's position
                 const f32x4_t cs = *as_global(reinterpret_cast<const f32x4_t *>(EE_SESS(a, ses, rope) + (size_t)mi.pos[m] * (hd >> 1) + (e >> 1)));
@@ -622,6 +622,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
         for (int mt = 0; mt < MT; ++mt) brow[mt] = min(mt * 16 + (lane & 15), rows - 1) * 64 + (lane >> 4) * 16;  // bytes inside a k-tile's hi rows
         const int tile_bytes = rows * 128;         // one k-tile of the input: both terms, all rows
         int blk_end = spb;                         // first k-step of the next input block
+        int blk = 0, blk_buf = 0;                  // the block being read and its buffer of the ring
         int xoff = wave * tile_bytes;              // LDS byte offset of this wave's k-tile of step s, relative to s * SWAVES * tile_bytes
         wait_vmem();                               // nothing pending at loop entry (see above)
         lds_barrier();                             // input block 0 is in LDS
@@ -631,8 +632,9 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
                 const int s = s0 + r;
                 if (s == blk_end && s < S_max) {   // next input block: the helpers have copied it into the next buffer of the ring
                     lds_barrier();
-                    const int b = s / spb;
-                    xoff = wave * tile_bytes + (b % ly.nbuf) * ly.xbuf_bytes - b * spb * SWAVES * tile_bytes;
+                    ++blk;
+                    blk_buf = blk_buf + 1 == ly.nbuf ? 0 : blk_buf + 1;
+                    xoff = wave * tile_bytes + blk_buf * ly.xbuf_bytes - blk * spb * SWAVES * tile_bytes;
                     blk_end += spb;
                 }
                 // A wave whose k-steps have run out keeps loading (its last tile again) and multiplies
@@ -667,9 +669,11 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
         // Block b is announced (barrier) once its own loads have landed, i.e. when only the loads of
         // the blocks requested after it are still pending.
         int issued = 0, cnt[3] = {0, 0, 0};        // cnt[j % 3]: load instructions of block j (nbuf <= 3)
+        int next_buf = 0;                          // buffer of the ring the next requested block goes to (blocks are requested in order)
         auto request = [&](int j) __attribute__((always_inline)) {
             const int kt0 = j * ly.kbt;
-            cnt[j % 3] = stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + (j % ly.nbuf) * ly.xbuf_bytes, hwave, lane);
+            cnt[j % 3] = stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + next_buf * ly.xbuf_bytes, hwave, lane);
+            next_buf = next_buf + 1 == ly.nbuf ? 0 : next_buf + 1;
         };
         for (; issued < max(ly.nbuf - 1, 1) && issued < ly.nkb; ++issued) request(issued);
         for (int b = 0; b < ly.nkb; ++b) {
@@ -690,7 +694,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
             if (kind == G_QKV && ht < rows) {
                 const int m = ht;
                 const int pos = row_pos(a, m);
-                const int ses = a.mode == 1 ? 0 : m / a.M;
+                const int ses = a.mode == 1 ? 0 : div_small(m, a.M);
                 const int cbase = EE_SESS(a, ses, contig_base);
                 const int page = cbase >= 0 ? cbase + pos / KV_PAGE : as_global(EE_SESS(a, ses, page_table))[pos / KV_PAGE];
                 mi.pos[m] = pos;
@@ -774,13 +778,13 @@ __device__ __forceinline__ void embed_stage(const PassArgs &a, char *lds)
 {
     const ModelDev &md = a.mdv;
     const int d = md.d, rows = a.rows, tid = threadIdx.x;
-    const int cw = ((d + a.nwg - 1) / a.nwg + 3) & ~3;  // columns per workgroup, multiple of 4
+    const int cw = (div_small(d + a.nwg - 1, a.nwg) + 3) & ~3;  // columns per workgroup, multiple of 4
     const int n0 = blockIdx.x * cw;
     const int nq = max(0, min(cw, d - n0)) >> 2;          // quads of columns here
     float *sq = reinterpret_cast<float *>(lds);           // [rows][cw/4]
     const float *gain = md.g_attn + (size_t)a.layer_begin * d;
     for (int it = tid; it < rows * nq; it += WG_THREADS) {
-        int m = it / nq, c = n0 + (it - m * nq) * 4;
+        int m = div_small(it, nq), c = n0 + (it - m * nq) * 4;
         int tok = row_token(a, m);
         const uint16_t *src = tok >= 0 ? md.emb + (size_t)tok * d + c : a.pf_emb + (size_t)m * d + c;
         uint2 r = *reinterpret_cast<const uint2 *>(src);
@@ -852,9 +856,9 @@ __device__ __forceinline__ void att_stage(const PassArgs &a, int layer, char *ld
     int *lastf = reinterpret_cast<int *>(wbuf + (size_t)WAVES * ATT_ROWS * REC);
     const size_t rec_page = (size_t)KV_PAGE * 2 * HD;  // elements of one (page, head) record
     for (int item = blockIdx.x; item < n_items; item += a.nwg) {
-        int unit = item / n_splits, sp = item - unit * n_splits;
-        int s = unit / (H * n_chunks), rem = unit - s * (H * n_chunks);
-        int hh = rem / n_chunks, ch = rem - hh * n_chunks;
+        int unit = div_small(item, n_splits), sp = item - unit * n_splits;
+        int s = div_small(unit, H * n_chunks), rem = unit - s * (H * n_chunks);
+        int hh = div_small(rem, n_chunks), ch = rem - hh * n_chunks;
         int r0 = ch * ATT_ROWS, nr = min(ATT_ROWS, M - r0);
         // session 0's descriptor also travels by value in the launch arguments: no dependent load
         const int *page_table = EE_SESS(a, s, page_table);
@@ -864,7 +868,7 @@ __device__ __forceinline__ void att_stage(const PassArgs &a, int layer, char *ld
         const int P = a.mode == 1 ? a.pf_pos0 : EE_SESS(a, s, kv_len);  // position of the first row
         const int n_pos = P + r0 + nr;  // positions visible to the chunk's last row
         const int n_pg = (n_pos + KV_PAGE - 1) / KV_PAGE;
-        const int pg_lo = n_pg * sp / n_splits, pg_hi = n_pg * (sp + 1) / n_splits;
+        const int pg_lo = div_small(n_pg * sp, n_splits), pg_hi = div_small(n_pg * (sp + 1), n_splits);
         const int T = max(0, (pg_hi - pg_lo - wave + WAVES - 1) / WAVES);  // tiles of this wave, <= ATT_TILES
         const int cbase = EE_SESS(a, s, contig_base);
         int my_pg = 0;  // physical page of this wave's tile number `lane`
@@ -1142,7 +1146,7 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
     __syncthreads();
     // one thread per (head of this launch, session)
     if ((int)threadIdx.x < a.n_heads * a.n_sess) {
-        const int hj = threadIdx.x / a.n_sess, s = threadIdx.x - hj * a.n_sess, head = a.head_idx + hj;
+        const int hj = div_small(threadIdx.x, a.n_sess), s = threadIdx.x - hj * a.n_sess, head = a.head_idx + hj;
         const SessDev &sd = a.sess[s];
         ee_verify_result *res = sd.result;
         const int *t = tok + (hj * a.n_sess + s) * M;
@@ -1252,7 +1256,7 @@ __device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds
 {
     static_assert(WAVES * 8 * 2 + WAVES * 4 + 16 <= SAMPLE_LDS_BYTES && EE_MAX_ROWS * 8 <= SAMPLE_LDS_BYTES, "LDS of the sampling launch");
     const int V = a.mdv.V, M = a.M, gamma = M - 1;
-    const int hj = r / M, i = r - hj * M;
+    const int hj = div_small(r, M), i = r - hj * M;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     u64 *wtot = reinterpret_cast<u64 *>(lds);                   // [WAVES] the waves' totals (target terms)
     u64 *rtot = wtot + WAVES;                                   // [WAVES] the same for the residual weights

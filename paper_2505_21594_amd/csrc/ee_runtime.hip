@@ -396,6 +396,11 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
             ee_model_free(m);
             return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
         }
+        // the kernels' exact small-integer division (div_small) covers the unit arithmetic of this plan
+        if ((long long)md.plan[k].U * md.plan[k].nwg > DIV_SMALL_MAX || md.plan[k].N > DIV_SMALL_MAX) {
+            ee_model_free(m);
+            return fail(EE_EFORMAT, "ee_model_load: a weight matrix with %d rows is beyond what the kernels' index arithmetic covers", md.plan[k].N);
+        }
         // tile offsets inside a stage are 32-bit byte offsets
         if ((long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 1024 >= (1LL << 31)) {
             ee_model_free(m);
