@@ -365,6 +365,30 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     for (int idx = tid; idx < items; idx += WG_THREADS) {
         int ntg = div_small(idx, rows * 4), rem = idx - ntg * rows * 4;
         int m = rem >> 2, qd = rem & 3;
+        const int n = (nt_first + ntg) * 16 + qd * 4;  // four consecutive output columns
+        // What the item reads from global memory is requested first, all of it at once: the sum of
+        // the partial tiles below then runs while it is on its way (one after the other, after the
+        // sum, these loads were two memory latencies at the end of every launch).
+        f32x4_t g_a = (f32x4_t){0.f, 0.f, 0.f, 0.f}, g_b = g_a, g_c = g_a;
+        int qkv_sect = 0, qkv_c = 0, qkv_head = 0, qkv_e = 0, qkv_ses = 0;
+        if (kind == G_O || kind == G_DN || kind == G_AU) {
+            if (n < md.d) {
+                g_a = *as_global(reinterpret_cast<const f32x4_t *>(a.sc.h + (size_t)m * md.d + n));
+                if (kind == G_AU) g_b = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+                if (ep.gain_xn) g_b = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xn + n));
+                if (ep.gain_xh) g_c = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xh + n));
+            }
+        } else if (kind == G_QKV) {
+            qkv_sect = div_small(n, md.d);
+            qkv_c = n - qkv_sect * md.d;
+            qkv_head = div_small(qkv_c, md.hd);
+            qkv_e = qkv_c - qkv_head * md.hd;
+            qkv_ses = a.mode == 1 ? 0 : div_small(m, a.M);
+            if (qkv_sect < 2)  // (cos, sin) of the row's position for the RoPE pairs of these four columns
+                g_a = *as_global(reinterpret_cast<const f32x4_t *>(EE_SESS(a, qkv_ses, rope) + (size_t)mi.pos[m] * (md.hd >> 1) + (qkv_e >> 1)));
+        } else if (kind == G_AD) {
+            if (n < md.A) g_a = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+        }
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
@@ -372,11 +396,10 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
-        const int n = (nt_first + ntg) * 16 + qd * 4;  // four consecutive output columns
         if (kind == G_AD) {
             // hidden units of the exit head's adapters: silu(W_down . h + b_down)
             if (n < md.A) {
-                const f32x4_t b = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+                const f32x4_t b = g_a;
                 float pre[4] = {S.x + b[0], S.y + b[1], S.z + b[2], S.w + b[3]}, o[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = pre[e] / (1.0f + __expf(-pre[e]));
@@ -386,10 +409,10 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             float sq = 0.f;
             if (n < md.d) {
                 EE_GLOBAL f32x4_t *hp = reinterpret_cast<EE_GLOBAL f32x4_t *>(as_global_mut(a.sc.h) + (size_t)m * md.d + n);
-                const f32x4_t hv = *hp;
+                const f32x4_t hv = g_a;
                 float v[4] = {hv[0] + S.x, hv[1] + S.y, hv[2] + S.z, hv[3] + S.w};
                 if (kind == G_AU) {  // a side branch: a = h + W_up . t + b_up feeds the exit's LM head, h stays as it is
-                    const f32x4_t b = *as_global(reinterpret_cast<const f32x4_t *>(ep.bias + n));
+                    const f32x4_t b = g_b;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) v[e] += b[e];
                 } else {
@@ -398,12 +421,12 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
                 if (ep.xa_out) store_split4(a.sc.xa, rows, m, n, v);
                 sq = v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
                 if (ep.gain_xn) {
-                    const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xn + n));
+                    const f32x4_t g = g_b;
                     float x[4] = {v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]};
                     store_split4(a.sc.xn, rows, m, n, x);
                 }
                 if (ep.gain_xh) {
-                    const f32x4_t g = *as_global(reinterpret_cast<const f32x4_t *>(ep.gain_xh + n));
+                    const f32x4_t g = g_c;
                     float x[4] = {v[0] * g[0], v[1] * g[1], v[2] * g[2], v[3] * g[3]};
                     store_split4(a.sc.xh, a.head_rows, a.head_row0 + m, n, x);
                 }
@@ -413,12 +436,10 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const int d = md.d, hd = md.hd;
             const float rs = mi.rstd[m];
             float v[4] = {S.x * rs, S.y * rs, S.z * rs, S.w * rs};
-            const int sect = div_small(n, d), c = n - sect * d;
-            const int head = div_small(c, hd), e = c - head * hd;
-            const int ses = a.mode == 1 ? 0 : div_small(m, a.M);
+            const int sect = qkv_sect, c = qkv_c, head = qkv_head, e = qkv_e, ses = qkv_ses;
             if (sect < 2) {
-                // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2; (cos, sin) of the row's position
-                const f32x4_t cs = *as_global(reinterpret_cast<const f32x4_t *>(EE_SESS(a, ses, rope) + (size_t)mi.pos[m] * (hd >> 1) + (e >> 1)));
+                // columns are pair-interleaved inside a head: (e, e+1) = RoPE pair e/2
+                const f32x4_t cs = g_a;
                 float y0 = v[0] * cs[0] - v[1] * cs[1], y1 = v[1] * cs[0] + v[0] * cs[1];
                 float y2 = v[2] * cs[2] - v[3] * cs[3], y3 = v[3] * cs[2] + v[2] * cs[3];
                 v[0] = y0; v[1] = y1; v[2] = y2; v[3] = y3;
