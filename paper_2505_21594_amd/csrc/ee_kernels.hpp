@@ -611,14 +611,14 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
     const int rows = a.rows;
     const int S_max = wave_ksteps(pl.KT, 0);      // k-steps of the busiest wave: everybody runs the loop this far
     const int spb = ly.kbt / SWAVES;              // k-steps per input block
-    f32x4_t acc[NL][MT];
-#pragma unroll
-    for (int nt = 0; nt < NL; ++nt)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
+    f32x4_t acc[NL][MT];                          // streaming waves only
 
     if (wave < SWAVES) {
         // ---------------- streaming wave
+#pragma unroll
+        for (int nt = 0; nt < NL; ++nt)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
         const int S_w = wave_ksteps(pl.KT, wave);
         const WRes wres = weight_resource(W);
         const int lane_off = lane * 16;
