@@ -159,21 +159,6 @@ struct Scratch {
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
-// Input and epilogue outputs of a GEMM launch's stage (filled in by the host per launch)
-struct GemmIn {
-    const uint16_t *x;  // the input (already scaled by the norm gain) as two bf16 terms, k-tile-major (x_index)
-    const float *ss;    // [nwg][rows_max] partial sums of squares for rstd, or nullptr
-};
-
-struct GemmEpi {           // what the O / DN / AU epilogue produces besides h
-    const float *gain_xn;  // gain of the next GEMM input (xn), or nullptr
-    const float *gain_xh;  // gain of the LM-head input (xh, at the exit's head rows), or nullptr
-    float *ss_out;         // [nwg][rows_max] partial sums of h^2, or nullptr
-    float *ss_head;        // [nwg][rows_max] partial sums of squares of the LM-head input's rows (at the head rows), or nullptr
-    const float *bias;     // AD / AU: bias per output column
-    int xa_out;            // DN: also emit h itself as the adapters' input (xa)
-};
-
 // Probabilistic verification (one session per pass): inputs and per-row decisions.
 struct SampleDev {
     const float *probs;  // [gamma][V]  the draft model's distributions
@@ -213,9 +198,6 @@ struct PassArgs {
     int H, d, Kpad_d;                    // copies of the model descriptor's fields for the attention kernel
     float att_scale;
     int stage;                           // index of this launch's stage in the segment's stage list
-    int kind, layer;                     // of this launch's stage: GemmKind (GEMM launches, else -1); layer (GEMM of a layer, attention)
-    GemmIn in;                           // GEMM launches: the stage's input ...
-    GemmEpi ep;                          // ... and what its epilogue writes besides the stage's own output
     const SessDev *sess;                 // device array [n_sess]
     SessDev sess0;                       // copy of sess[0]
     SampleDev sm;

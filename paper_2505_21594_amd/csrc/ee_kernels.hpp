@@ -243,6 +243,10 @@ __device__ __host__ inline int wave_ksteps(int KT, int w) { return KT > w ? (KT 
 
 // ------------------------------------------------------------------ GEMM stage
 
+struct GemmIn {
+    const uint16_t *x;  // the input (already scaled by the norm gain) as two bf16 terms, k-tile-major (x_index)
+    const float *ss;    // [nwg][rows_max] partial sums of squares for rstd, or nullptr
+};
 
 // GEMM inputs are stored the way the stages consume them: [k-tile][term][row][32] bf16 with
 // `rows` = the rows of this pass, term 0 = hi, 1 = lo.  A range of k-tiles (all rows, both
@@ -313,6 +317,14 @@ __device__ __forceinline__ bool cand_better(float v, int i, float bv, int bi)
     return v > bv || (v == bv && i < bi);
 }
 
+struct GemmEpi {           // what the O / DN / AU epilogue produces besides h
+    const float *gain_xn;  // gain of the next GEMM input (xn), or nullptr
+    const float *gain_xh;  // gain of the LM-head input (xh, at the exit's head rows), or nullptr
+    float *ss_out;         // [nwg][rows_max] partial sums of h^2, or nullptr
+    float *ss_head;        // [nwg][rows_max] partial sums of squares of the LM-head input's rows (at the head rows), or nullptr
+    const float *bias;     // AD / AU: bias per output column
+    int xa_out;            // DN: also emit h itself as the adapters' input (xa)
+};
 
 // Epilogue of one chunk of gn n-tiles starting at n-tile nt_first: sum the streaming waves'
 // partial tiles (fixed order), apply the stage's element-wise tail.  All threads.
@@ -1398,9 +1410,88 @@ __device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds
 // Stage list of a segment: [EMBED] { QKV ATT O GU DN } x layers [HEAD]; one launch per stage.
 // The accept step runs inside the head's launch, in the workgroup that finishes last.
 
+struct StageDesc {
+    int type, kind, layer;
+};
 
+__device__ __forceinline__ StageDesc stage_decode(const PassArgs &a, int ph)
+{
+    StageDesc sd = {ST_NONE, 0, 0};
+    const int per_layer = 5;
+    int idx = ph - (a.do_embed ? 1 : 0);
+    if (idx < 0) {
+        sd.type = ST_EMBED;
+        return sd;
+    }
+    const int nl = a.layer_end - a.layer_begin;
+    if (idx < per_layer * nl) {
+        int li = idx / per_layer, r = idx - li * per_layer;
+        sd.layer = a.layer_begin + li;
+        if (r == 0) {
+            sd.type = ST_GEMM;
+            sd.kind = G_QKV;
+        } else if (r == 1) {
+            sd.type = ST_ATT;
+        } else {
+            sd.type = ST_GEMM;
+            sd.kind = G_O + (r - 2);
+        }
+        return sd;
+    }
+    idx -= per_layer * nl;
+    if (a.head_kind != HEAD_NONE) {  // [AD AU] [HEAD]
+        const int n_ad = a.adapter ? 2 : 0;
+        if (idx < n_ad) {
+            sd.type = ST_GEMM;
+            sd.kind = G_AD + idx;
+        } else if (idx == n_ad && a.head_stage) {
+            sd.type = ST_GEMM;
+            sd.kind = G_HEAD;
+        }
+    }
+    return sd;
+}
 
+__device__ __forceinline__ GemmIn gemm_input(const PassArgs &a, int kind)
+{
+    switch (kind) {
+    case G_QKV: return GemmIn{a.sc.xn, a.sc.ss_a};
+    case G_O: return GemmIn{a.sc.attn, nullptr};
+    case G_GU: return GemmIn{a.sc.xn, a.sc.ss_f};
+    case G_DN: return GemmIn{a.sc.u, nullptr};
+    case G_AD: return GemmIn{a.sc.xa, nullptr};
+    case G_AU: return GemmIn{a.sc.t, nullptr};
+    default: return GemmIn{a.sc.xh, a.sc.ss_h};
+    }
+}
 
+__device__ __forceinline__ GemmEpi gemm_epi(const PassArgs &a, int kind, int layer)
+{
+    const ModelDev &md = a.mdv;
+    GemmEpi ep = {nullptr, nullptr, nullptr, nullptr, nullptr, 0};
+    if (kind == G_O) {
+        ep.gain_xn = md.g_ffn + (size_t)layer * md.d;
+        ep.ss_out = a.sc.ss_f;
+    } else if (kind == G_DN) {
+        if (layer + 1 < md.L) ep.gain_xn = md.g_attn + (size_t)(layer + 1) * md.d;
+        if (layer + 1 == a.layer_end && a.head_kind != HEAD_NONE) {
+            if (a.adapter) {
+                ep.xa_out = 1;                 // the exit's adapters come first
+            } else {
+                ep.gain_xh = a.head_gain;      // the LM head's input rows and their sums of squares
+                ep.ss_head = a.sc.ss_h;
+            }
+        }
+        ep.ss_out = a.sc.ss_a;
+    } else if (kind == G_AD) {
+        ep.bias = a.ad_bdown;
+    } else if (kind == G_AU) {
+        ep.bias = a.ad_bup;
+        ep.gain_xh = a.head_gain;
+        ep.ss_head = a.sc.ss_h;
+    }
+    return ep;
+}
 
 // The GEMM stage a.stage of the stage list.  MT = 16-row tiles of the pass (rows <= 16 * MT).
 template <int MT>
@@ -1410,9 +1501,8 @@ __global__ void __launch_bounds__(WG_THREADS) ee_gemm_kernel(PassArgs a_by_value
     const PassArgs &a = warmed_arguments();
     EarlyLoads early;
     gemm_early<MT>(a.plan0, a.W0, early);
-    // kind, layer, input and epilogue outputs of the stage were worked out by the host: scalar set-up
-    // code is what a launch spends its first microseconds on, twelve waves each running it
-    gemm_stage_t<MT>(a, a.kind, a.layer, a.plan0, a.lay, a.W0, a.in, a.ep, lds, early);
+    const StageDesc st = stage_decode(a, a.stage);
+    gemm_stage_t<MT>(a, st.kind, st.layer, a.plan0, a.lay, a.W0, gemm_input(a, st.kind), gemm_epi(a, st.kind, st.layer), lds, early);
     if (a.fuse_accept) {
         // A head stage: the workgroup whose candidates arrive last also runs the accept step
         // (one launch less per head); the counter is left at zero.
@@ -1454,7 +1544,7 @@ __global__ void __launch_bounds__(WG_THREADS) ee_att_kernel(PassArgs a_by_value)
 {
     extern __shared__ __align__(16) char lds[];
     const PassArgs &a = warmed_arguments();
-    att_stage<HD>(a, a.layer, lds);
+    att_stage<HD>(a, stage_decode(a, a.stage).layer, lds);
 }
 
 // embedding
@@ -1462,7 +1552,7 @@ __global__ void __launch_bounds__(WG_THREADS) ee_misc_kernel(PassArgs a_by_value
 {
     extern __shared__ __align__(16) char lds[];
     const PassArgs &a = warmed_arguments();
-    embed_stage(a, lds);
+    if (stage_decode(a, a.stage).type == ST_EMBED) embed_stage(a, lds);
 }
 
 // ------------------------------------------------------------------ load-time kernels

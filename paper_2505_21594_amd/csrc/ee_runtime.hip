@@ -787,48 +787,6 @@ static int launch_code(const PassArgs &a, int ph)
     return -1;
 }
 
-// input and epilogue outputs of a GEMM stage (host side: the launch carries them)
-static GemmIn gemm_input(const PassArgs &a, int kind)
-{
-    switch (kind) {
-    case G_QKV: return GemmIn{a.sc.xn, a.sc.ss_a};
-    case G_O: return GemmIn{a.sc.attn, nullptr};
-    case G_GU: return GemmIn{a.sc.xn, a.sc.ss_f};
-    case G_DN: return GemmIn{a.sc.u, nullptr};
-    case G_AD: return GemmIn{a.sc.xa, nullptr};
-    case G_AU: return GemmIn{a.sc.t, nullptr};
-    default: return GemmIn{a.sc.xh, a.sc.ss_h};
-    }
-}
-
-static GemmEpi gemm_epi(const PassArgs &a, int kind, int layer)
-{
-    const ModelDev &md = a.mdv;
-    GemmEpi ep = {nullptr, nullptr, nullptr, nullptr, nullptr, 0};
-    if (kind == G_O) {
-        ep.gain_xn = md.g_ffn + (size_t)layer * md.d;
-        ep.ss_out = a.sc.ss_f;
-    } else if (kind == G_DN) {
-        if (layer + 1 < md.L) ep.gain_xn = md.g_attn + (size_t)(layer + 1) * md.d;
-        if (layer + 1 == a.layer_end && a.head_kind != HEAD_NONE) {
-            if (a.adapter) {
-                ep.xa_out = 1;                 // the exit's adapters come first
-            } else {
-                ep.gain_xh = a.head_gain;      // the LM head's input rows and their sums of squares
-                ep.ss_head = a.sc.ss_h;
-            }
-        }
-        ep.ss_out = a.sc.ss_a;
-    } else if (kind == G_AD) {
-        ep.bias = a.ad_bdown;
-    } else if (kind == G_AU) {
-        ep.bias = a.ad_bup;
-        ep.gain_xh = a.head_gain;
-        ep.ss_head = a.sc.ss_h;
-    }
-    return ep;
-}
-
 // Enqueues the stages of one segment, one launch each, on the leader's stream.
 static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
 {
@@ -840,13 +798,6 @@ static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
         if (code < 0) break;
         const bool gemm = code != EE_LAUNCH_EMBED && code != EE_LAUNCH_ATT;
         a.stage = ph;
-        {
-            const int idx = ph - (a.do_embed ? 1 : 0);
-            a.kind = gemm ? code : -1;
-            a.layer = (idx >= 0 && idx < per_layer * (a.layer_end - a.layer_begin)) ? a.layer_begin + idx / per_layer : 0;
-            a.in = gemm ? gemm_input(a, a.kind) : GemmIn{nullptr, nullptr};
-            a.ep = gemm ? gemm_epi(a, a.kind, a.layer) : GemmEpi{nullptr, nullptr, nullptr, nullptr, nullptr, 0};
-        }
         a.fuse_accept = (code == EE_LAUNCH_HEAD && !a.sm.on) ? 1 : 0;
         a.rows = code == EE_LAUNCH_HEAD ? a.head_rows : rows;   // the head launch carries the rows of all exits of its group
         pass_kernel_t k = gemm ? gemm_kernel(a.rows) : (code == EE_LAUNCH_ATT ? att_kernel(m->cfg.head_dim) : ee_misc_kernel);
