@@ -564,7 +564,7 @@ __device__ __forceinline__ void gemm_early(const GemmPlan &pl, const uint4 *__re
     wg_units(pl, blockIdx.x, nt0, n_local);
     if (n_local <= 0 || wave >= SWAVES) return;
     const int nl = min(GROUP_TILES, n_local);
-    const int last = __builtin_amdgcn_readfirstlane(max(wave_ksteps(pl.KT, wave) * nl - 1, 0));   // kept scalar: a vector value here makes every tile offset a loop over lanes
+    const int last = max(wave_ksteps(pl.KT, wave) * nl - 1, 0);
     const WRes wres = weight_resource(W);
     const int wstep = pl.nwg * SWAVES * 1024;
     const int woff = ((int)blockIdx.x * SWAVES + wave) * 1024;
@@ -624,7 +624,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
         const int lane_off = lane * 16;
         const int wstep = pl.nwg * SWAVES * 1024;  // bytes from one tile of the wave's sequence to the next
         const int woff = ((seq0 * pl.nwg + (int)blockIdx.x) * SWAVES + wave) * 1024;  // the group's first tile
-        const int last = __builtin_amdgcn_readfirstlane(max(S_w * NL - 1, 0));  // the group's last tile of this wave (look-ahead is clamped to it)
+        const int last = max(S_w * NL - 1, 0);     // the group's last tile of this wave (look-ahead is clamped to it)
         uint4 buf[R][NL];
 #pragma unroll
         for (int r = 0; r < R; ++r)
