@@ -1062,6 +1062,10 @@ __device__ __forceinline__ void att_stage(const PassArgs &a, int layer, char *ld
             }
             __syncthreads();
             if (*lastf) {
+                // (the split count goes through an opaque copy here: otherwise everything below that
+                // depends only on it -- sixteen clamped offsets, sixteen conditions -- is worked out
+                // at the start of the kernel, by every workgroup, before its first load)
+                const int n_splits = opaque(a.att_splits);
                 const float *base = a.sc.att_part + (size_t)unit * n_splits * ATT_ROWS * REC;
                 const size_t sp_stride = (size_t)ATT_ROWS * REC;
                 for (int t = tid; t < nr * HD; t += WG_THREADS) {
