@@ -120,7 +120,13 @@ const char *ee_last_error(void);
    format description), uploads it to GPU `device` and re-lays the weight
    matrices out in the tile order the kernels stream.  max_rows (1..EE_MAX_ROWS)
    is the largest number of rows a pass (or a prefill chunk) will carry; ee_model_load
-   uses 16.
+   uses 16.  With max_rows > 16 the output and down projections are kept in a second
+   tile order as well, in which groups of four workgroups share their output columns and
+   split K; launches of more than 16 rows use it (about a quarter more device memory for
+   the weights).  The environment variable EE_KSPLIT="<mask>:<log2 splits>" read here
+   overrides which GEMM kinds get that second order (bit 0 QKV, 1 output, 2 gate/up,
+   3 down, 4 LM head, 5 and 6 the adapters) and the number of splits (1 to 3): a tuning
+   and test knob, results are the same up to the summation order.
    Cold path; synchronous. */
 int ee_model_load(const char *path, int device, ee_model **out);
 int ee_model_load_ex(const char *path, int device, int max_rows, ee_model **out);
@@ -319,6 +325,12 @@ int ee_launch_times(ee_session *s, int32_t *codes, float *ms, int max_launches, 
 /* Debug: runs one v_mfma_f32_16x16x32_bf16 through the operand lane layout the
    kernels assume and compares with the plain 16x32 . 32x16 product. */
 int ee_debug_mfma_layout(int device);
+
+/* Debug: the kernels divide small integers by run-time values (rows, workgroups, head size)
+   with one reciprocal and one multiply.  Counts, on the device, the x in [0, 2 500 000]
+   (the range the model loader admits) for which that differs from x / d, for each of the n
+   divisors (host array, each >= 1, n <= 65536); *mismatches must come back 0. */
+int ee_debug_div_small(int device, const int32_t *divisors, int n, long long *mismatches);
 
 #ifdef __cplusplus
 }

@@ -17,6 +17,7 @@ constexpr int KV_PAGE = 16;              // positions per KV page
 constexpr int ATT_ROWS = 16;             // query rows of one attention item (one MFMA tile)
 constexpr int ATT_TILES = 8;             // KV pages (score tiles) a wave keeps in registers per item
 constexpr int ATT_MAX_SPLITS = 16;
+constexpr int KSPLIT_LOG2 = 2;           // many-row launches: workgroups (1 << this) that share n-tiles and split K (at most SWAVES)
 
 // Weight layout of one GEMM y = x . W^T, W[N][K] row-major in the model file.
 //
@@ -46,6 +47,12 @@ struct GemmPlan {
     int nwg;         // workgroups that take part in this stage kind: the fewest that keep the busiest one's
                      // share unchanged, so that all of them get (nearly) the same share; the rest idle.
                      // Half of the compute units already saturate HBM, uneven shares only lengthen the tail.
+    // K split over workgroups (many-row launches): 1 << ksl consecutive workgroups share the same
+    // n-tiles and take one slice of KTs k-tiles each (workgroup g: n-tiles of g >> ksl, slice
+    // g & (splits - 1)); their partial tiles meet in memory and the one that arrives last adds them
+    // up and runs the epilogue.  A workgroup then copies only its slice of the input into LDS and
+    // has 1 << ksl times the n-tiles per input block.  ksl = 0, KTs = KT: no split.
+    int ksl, KTs;
 };
 
 // LDS map of one GEMM launch, chosen on the host from the rows of the launch:
@@ -77,7 +84,7 @@ constexpr int NUM_XCD = 8;
 // every epilogue item.  One reciprocal (1 ulp) and one multiply give the exact quotient in this
 // range: (x + 0.5) / d is at least 0.5 / d away from an integer and the error of the product is
 // below (x + 0.5) / d * 1.8e-7, which is less than 0.5 / d for x < 2.7e6.
-constexpr int DIV_SMALL_MAX = 1 << 21;
+constexpr int DIV_SMALL_MAX = 2500000;
 __host__ __device__ inline int div_small(int x, int d)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -110,10 +117,6 @@ struct ModelDev {
     float eps, att_scale;
     int Kpad_d, Kpad_F;                  // K rounded up to 32
     int rows_max;
-    GemmPlan plan[G_KINDS];              // indexed by GemmKind (host side; a launch gets its own by value)
-    // tiled weights: one allocation per GEMM kind, layer l (adapters: stored exit l) at w[kind] + l * wstride[kind] (uint4 units)
-    const uint4 *w[G_KINDS];
-    long long wstride[G_KINDS];
     int A, Kpad_A;                       // hidden units of an exit head's adapters (all bottlenecks together; 0: none), rounded up to 32
     const float *g_attn, *g_ffn;         // [L][d]
     const float *g_final;
@@ -152,6 +155,8 @@ struct Scratch {
     float *att_part;     // [items][ATT_ROWS][hd+2] attention partials (only when the position range is split)
     int *att_count;      // [units] items of the unit that have delivered their partials; zero between launches
     int *head_count;     // workgroups of a head launch that have delivered their candidates; zero between launches
+    float *part;         // [K split][n-tile][rows][16] partial tiles of a launch whose K is split over workgroups
+    int *part_count;     // [nwg] splits of a group of workgroups that have delivered their partial tiles; zero between launches
     float *logits;       // [heads][rows_max][V] when logits are kept
     int2 *cand;          // [nwg][rows_max]      per-workgroup argmax candidates (value bits, index)
     float *cand_sum;     // [nwg][rows_max]      sum over the workgroup's columns of exp(logit - candidate value)

@@ -62,6 +62,7 @@ __device__ __forceinline__ WRes weight_resource(const uint4 *W)
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)p), hi = __builtin_amdgcn_readfirstlane((unsigned)(p >> 32));
     return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(((unsigned long long)hi << 32) | lo), 0, 0x7FFFFFFF, 0x00020000);
 }
+__device__ __forceinline__ WRes buffer_resource(const void *p) { return weight_resource(reinterpret_cast<const uint4 *>(p)); }
 __device__ __forceinline__ uint4 load_tile16(WRes r, int lane_off, int tile_off)
 {
     u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, tile_off, 0);
@@ -86,6 +87,18 @@ __device__ __forceinline__ void store_dev64(void *p, uint2 v)
 __device__ __forceinline__ void store_dev32(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// the same for 16 bytes at byte offset `off` of a buffer (weight_resource): device-scope cache policy (sc1)
+constexpr int CACHE_POLICY_DEVICE = 16;
+__device__ __forceinline__ void store_dev128(WRes r, int off, float4 v)
+{
+    __builtin_amdgcn_raw_buffer_store_b128((u32x4_t){__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)},
+                                           r, off, 0, CACHE_POLICY_DEVICE);
+}
+__device__ __forceinline__ float4 load_dev128(WRes r, int off)
+{
+    const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, CACHE_POLICY_DEVICE);
+    return make_float4(__uint_as_float(v[0]), __uint_as_float(v[1]), __uint_as_float(v[2]), __uint_as_float(v[3]));
 }
 __device__ __forceinline__ float load_dev32(const float *p)
 {
@@ -233,7 +246,7 @@ __device__ __forceinline__ Misc misc_views(const StageLds &ly, char *lds)
 __device__ __host__ inline void wg_units(const GemmPlan &pl, int g, int &nt0, int &n_local)
 {
     int u0 = 0, u1 = 0;
-    if (g < pl.nwg) unit_range(pl.U, pl.nwg, g, u0, u1);  // workgroups past the stage's count own nothing
+    if (g < pl.nwg) unit_range(pl.U, pl.nwg >> pl.ksl, g >> pl.ksl, u0, u1);  // workgroups past the stage's count own nothing
     nt0 = u0 * pl.tpu;
     n_local = (u1 - u0) * pl.tpu;
 }
@@ -326,10 +339,11 @@ struct GemmEpi {           // what the O / DN / AU epilogue produces besides h
     int xa_out;            // DN: also emit h itself as the adapters' input (xa)
 };
 
-// Epilogue of one chunk of gn n-tiles starting at n-tile nt_first: sum the streaming waves'
-// partial tiles (fixed order), apply the stage's element-wise tail.  All threads.
+// Epilogue of one chunk of gn n-tiles starting at n-tile nt_first: sum the nsum partial tiles in
+// the slot buffer (the streaming waves', or the K splits' when K is split over workgroups; fixed
+// order), apply the stage's element-wise tail.  All threads.
 __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int layer, const StageLds &ly, int nt_first,
-                                              int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds)
+                                              int gn, int rows, const GemmEpi &ep, const Misc &mi, char *lds, const int nsum)
 {
     const ModelDev &md = a.mdv;
     const float *slots = reinterpret_cast<const float *>(lds);
@@ -344,7 +358,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
             const float *su = sg + (size_t)rows * 16;
             float4 G = make_float4(0.f, 0.f, 0.f, 0.f), U = G;
 #pragma unroll 2
-            for (int w = 0; w < SWAVES; ++w) {
+            for (int w = 0; w < nsum; ++w) {
                 float4 x = *reinterpret_cast<const float4 *>(sg + w * wstride);
                 float4 y = *reinterpret_cast<const float4 *>(su + w * wstride);
                 G.x += x.x; G.y += x.y; G.z += x.z; G.w += x.w;
@@ -392,7 +406,7 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
         const float *sp = slots + ((size_t)ntg * rows + m) * 16 + qd * 4;
         float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll 4
-        for (int w = 0; w < SWAVES; ++w) {
+        for (int w = 0; w < nsum; ++w) {
             float4 x = *reinterpret_cast<const float4 *>(sp + w * wstride);
             S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
         }
@@ -539,6 +553,67 @@ __device__ __forceinline__ void gemm_epilogue(const PassArgs &a, int kind, int l
     }
 }
 
+// K split over workgroups: instead of the epilogue, one chunk of gn n-tiles of this workgroup's
+// partial sums (the streaming waves' tiles added up, fixed order) goes to memory, to
+// part[split][n-tile][row][16].  All threads.
+__device__ __forceinline__ void partial_store(const PassArgs &a, const GemmPlan &pl, const StageLds &ly, int nt_first, int gn,
+                                              int rows, const char *lds)
+{
+    const float *slots = reinterpret_cast<const float *>(lds);
+    const int tid = opaque(threadIdx.x);
+    const size_t wstride = (size_t)ly.chunk * rows * 16;
+    const int sp = blockIdx.x & ((1 << pl.ksl) - 1);
+    const WRes out = buffer_resource(a.sc.part + ((size_t)sp * pl.NT + nt_first) * rows * 16);
+    const int items = gn * rows * 4;            // (n-tile, row, quad of columns): the slot buffer's own order
+    for (int idx = tid; idx < items; idx += WG_THREADS) {
+        const float *p = slots + (size_t)idx * 4;
+        float4 S = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 4
+        for (int w = 0; w < SWAVES; ++w) {
+            float4 x = *reinterpret_cast<const float4 *>(p + w * wstride);
+            S.x += x.x; S.y += x.y; S.z += x.z; S.w += x.w;
+        }
+        store_dev128(out, idx * 16, S);
+    }
+}
+
+// K split over workgroups, after the workgroup's last group: count this split in its group's
+// counter; the workgroup that arrives last (the counter goes back to zero for the next launch)
+// fetches all splits' partial tiles, chunk by chunk, into the slot buffer in split order and
+// runs the epilogue on them.  The result does not depend on who arrives last; nothing waits.
+__device__ __forceinline__ void split_finish(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const StageLds &ly,
+                                             const GemmEpi &ep, const Misc &mi, char *lds, int nt0, int n_local)
+{
+    const int tid = opaque(threadIdx.x);
+    const int rows = a.rows, ks = 1 << pl.ksl;
+    wait_vmem();      // this workgroup's partial tiles are visible device-wide ...
+    __syncthreads();  // ... for every wave, before it is counted
+    if (tid == 0) {
+        int *cnt = a.sc.part_count + (blockIdx.x >> pl.ksl);
+        const int before = __hip_atomic_fetch_add(cnt, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *mi.lastf = before == ks - 1 ? 1 : 0;
+        if (*mi.lastf) __hip_atomic_store(cnt, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!*mi.lastf) return;
+    float *slots = reinterpret_cast<float *>(lds);
+    const size_t wstride = (size_t)ly.chunk * rows * 16;
+    const WRes part = buffer_resource(a.sc.part);
+    for (int c0 = 0; c0 < n_local; c0 += ly.chunk) {
+        const int gn = min(ly.chunk, n_local - c0);
+        const int per = gn * rows * 4;          // 16-byte items of one split's chunk
+        for (int idx = tid; idx < ks * per; idx += WG_THREADS) {
+            const int s = div_small(idx, per), rem = idx - s * per;
+            // (byte offsets stay far below 2^31: the buffer holds splits x n-tiles x rows x 64 bytes)
+            *reinterpret_cast<float4 *>(slots + s * wstride + (size_t)rem * 4) =
+                load_dev128(part, (int)((((size_t)s * pl.NT + nt0 + c0) * rows * 16 + (size_t)rem * 4) * sizeof(float)));
+        }
+        lds_barrier();
+        gemm_epilogue(a, kind, layer, ly, nt0 + c0, gn, rows, ep, mi, lds, ks);
+        lds_barrier();
+    }
+}
+
 // The streaming waves of a one-row-tile launch request the first EARLY_TILES tiles of their
 // sequence as soon as the launch's arguments are there, before the plan arithmetic and the jump
 // into the group's code (2 to 3 us on a cold instruction cache); the stage's first group takes
@@ -564,7 +639,7 @@ __device__ __forceinline__ void gemm_early(const GemmPlan &pl, const uint4 *__re
     wg_units(pl, blockIdx.x, nt0, n_local);
     if (n_local <= 0 || wave >= SWAVES) return;
     const int nl = min(GROUP_TILES, n_local);
-    const int last = max(wave_ksteps(pl.KT, wave) * nl - 1, 0);
+    const int last = max(wave_ksteps(pl.KTs, wave) * nl - 1, 0);
     const WRes wres = weight_resource(W);
     const int wstep = pl.nwg * SWAVES * 1024;
     const int woff = ((int)blockIdx.x * SWAVES + wave) * 1024;
@@ -609,7 +684,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
     const ModelDev &md = a.mdv;
     const int tid = opaque(threadIdx.x), lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rows = a.rows;
-    const int S_max = wave_ksteps(pl.KT, 0);      // k-steps of the busiest wave: everybody runs the loop this far
+    const int S_max = wave_ksteps(pl.KTs, 0);     // k-steps of the busiest wave: everybody runs the loop this far
     const int spb = ly.kbt / SWAVES;              // k-steps per input block
     f32x4_t acc[NL][MT];                          // streaming waves only
 
@@ -619,7 +694,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
         for (int nt = 0; nt < NL; ++nt)
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[nt][mt] = (f32x4_t){0.f, 0.f, 0.f, 0.f};
-        const int S_w = wave_ksteps(pl.KT, wave);
+        const int S_w = wave_ksteps(pl.KTs, wave);
         const WRes wres = weight_resource(W);
         const int lane_off = lane * 16;
         const int wstep = pl.nwg * SWAVES * 1024;  // bytes from one tile of the wave's sequence to the next
@@ -693,7 +768,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
         int next_buf = 0;                          // buffer of the ring the next requested block goes to (blocks are requested in order)
         auto request = [&](int j) __attribute__((always_inline)) {
             const int kt0 = j * ly.kbt;
-            cnt[j % 3] = stage_block(in.x, rows, kt0, min(ly.kbt, pl.KT - kt0), lds + next_buf * ly.xbuf_bytes, hwave, lane);
+            cnt[j % 3] = stage_block(in.x, rows, kt0, min(ly.kbt, pl.KTs - kt0), lds + next_buf * ly.xbuf_bytes, hwave, lane);
             next_buf = next_buf + 1 == ly.nbuf ? 0 : next_buf + 1;
         };
         for (; issued < max(ly.nbuf - 1, 1) && issued < ly.nkb; ++issued) request(issued);
@@ -744,7 +819,10 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
                 }
         }
         lds_barrier();
-        gemm_epilogue(a, kind, layer, ly, nt_first + c0, gn, rows, ep, mi, lds);
+        if (MT > 1 && pl.ksl)   // (K is split only for launches of more than one row tile)
+            partial_store(a, pl, ly, nt_first + c0, gn, rows, lds);
+        else
+            gemm_epilogue(a, kind, layer, ly, nt_first + c0, gn, rows, ep, mi, lds, SWAVES);
         lds_barrier();
     }
 }
@@ -752,7 +830,7 @@ __device__ __forceinline__ void gemm_group(const PassArgs &a, int kind, int laye
 // One GEMM stage of this workgroup: its n-tiles in groups of up to GROUP_TILES.
 template <int MT>
 __device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int layer, const GemmPlan &pl, const StageLds &ly,
-                             const uint4 *__restrict__ W, const GemmIn &in, const GemmEpi &ep, char *lds, const EarlyLoads &early)
+                             const uint4 *__restrict__ W, const GemmIn &in_all, const GemmEpi &ep, char *lds, const EarlyLoads &early)
 {
     const ModelDev &md = a.mdv;
     const int tid = opaque(threadIdx.x);
@@ -768,7 +846,9 @@ __device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int la
         mi.rowss[tid] = 0.f;
     }
     if (n_local > 0) {
-        const int S0 = wave_ksteps(pl.KT, 0);
+        const int S0 = wave_ksteps(pl.KTs, 0);
+        // K split over workgroups: this workgroup's slice of the input (k-tile-major: a contiguous range)
+        const GemmIn in = {MT > 1 ? in_all.x + (size_t)(blockIdx.x & ((1 << pl.ksl) - 1)) * pl.KTs * (2 * rows * 32) : in_all.x, in_all.ss};
         int seq = 0;  // tiles of a wave's sequence before the group (waves with fewer k-steps leave their slots unused)
         for (int g0 = 0; g0 < n_local; g0 += GROUP_TILES) {
             const int nl = min(GROUP_TILES, n_local - g0);
@@ -781,13 +861,31 @@ __device__ __forceinline__ void gemm_stage_t(const PassArgs &a, int kind, int la
 #undef EE_GROUP
             seq += S0 * nl;
         }
+        if (MT > 1 && pl.ksl) split_finish(a, kind, layer, pl, ly, ep, mi, lds, nt0, n_local);
     }
     // what the workgroup hands to the following launch
-    if (ep.ss_out && tid < rows) as_global_mut(ep.ss_out)[(size_t)blockIdx.x * md.rows_max + tid] = mi.rowss[tid];
-    if (ep.ss_head && tid < rows) as_global_mut(ep.ss_head)[(size_t)blockIdx.x * md.rows_max + a.head_row0 + tid] = mi.rowss[tid];
-    if (kind == G_HEAD && tid < rows) {  // device-scope stores: the accept step may run in another workgroup of this launch
-        store_dev64(a.sc.cand + (size_t)blockIdx.x * md.rows_max + tid, make_uint2(__float_as_uint(mi.bestv[tid]), (unsigned)mi.besti[tid]));
-        store_dev32(a.sc.cand_sum + (size_t)blockIdx.x * md.rows_max + tid, mi.sume[tid]);
+    auto hand_over = [&](int slot, bool mine) __attribute__((always_inline)) {
+        const float ss = mine ? mi.rowss[tid] : 0.f;
+        if (ep.ss_out) as_global_mut(ep.ss_out)[(size_t)slot * md.rows_max + tid] = ss;
+        if (ep.ss_head) as_global_mut(ep.ss_head)[(size_t)slot * md.rows_max + a.head_row0 + tid] = ss;
+        if (kind == G_HEAD) {  // device-scope stores: the accept step may run in another workgroup of this launch
+            store_dev64(a.sc.cand + (size_t)slot * md.rows_max + tid,
+                        make_uint2(__float_as_uint(mine ? mi.bestv[tid] : -INFINITY), (unsigned)(mine ? mi.besti[tid] : 0x7FFFFFFF)));
+            store_dev32(a.sc.cand_sum + (size_t)slot * md.rows_max + tid, mine ? mi.sume[tid] : 0.f);
+        }
+    };
+    if (tid < rows) {
+        if (MT > 1 && pl.ksl && n_local > 0) {
+            // K split: the group's result was worked out by whichever of its workgroups arrived last; it
+            // fills the slots of the whole group, the result in the first, so that what the following
+            // launch adds up (in slot order) does not depend on who that was
+            if (*mi.lastf) {
+                const int ks = 1 << pl.ksl, first = (int)blockIdx.x & ~(ks - 1);
+                for (int j = 0; j < ks; ++j) hand_over(first + j, j == 0);
+            }
+        } else {
+            hand_over((int)blockIdx.x, true);
+        }
     }
 }
 
@@ -1589,16 +1687,17 @@ __global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__r
     wg_units(pl, g, nt0, n_local);
     if (n_local == 0) return;
     const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6, nsub = blockDim.x >> 6;
-    const int S0 = wave_ksteps(pl.KT, 0);
+    const int S0 = wave_ksteps(pl.KTs, 0);
+    const int kt_first = (g & ((1 << pl.ksl) - 1)) * pl.KTs;   // K split over workgroups: this workgroup's slice
     for (int w = sub; w < SWAVES; w += nsub) {
-        const int S_w = wave_ksteps(pl.KT, w);
+        const int S_w = wave_ksteps(pl.KTs, w);
         int seq = 0;
         for (int g0 = 0; g0 < n_local; g0 += GROUP_TILES) {
             const int nl = min(GROUP_TILES, n_local - g0);
             for (int s = 0; s < S_w; ++s)
                 for (int nt = 0; nt < nl; ++nt) {
                     int n = (nt0 + g0 + nt) * 16 + (lane & 15);
-                    int k0 = (w + SWAVES * s) * 32 + (lane >> 4) * 8;
+                    int k0 = (kt_first + w + SWAVES * s) * 32 + (lane >> 4) * 8;
                     uint16_t v[8];
                     int row = n < pl.N ? perm_row(perm, n, d, hd, F) : -1;
 #pragma unroll
@@ -1617,6 +1716,18 @@ __global__ void tile_weights_kernel(const uint16_t *__restrict__ src, uint4 *__r
             seq += S0 * nl;
         }
     }
+}
+
+// counts the x in [0, x_max] with div_small(x, d) != x / d, for every divisor of the list
+__global__ void div_small_check_kernel(const int *__restrict__ divisors, int n_div, int x_max, unsigned long long *bad)
+{
+    unsigned long long mine = 0;
+    for (int j = blockIdx.y; j < n_div; j += gridDim.y) {
+        const int d = divisors[j];
+        for (long long x = (long long)blockIdx.x * blockDim.x + threadIdx.x; x <= x_max; x += (long long)gridDim.x * blockDim.x)
+            mine += div_small((int)x, d) != (int)x / d ? 1 : 0;
+    }
+    if (mine) atomicAdd(bad, mine);
 }
 
 __global__ void bf16_to_f32_kernel(const uint16_t *__restrict__ src, float *__restrict__ dst, int n)

@@ -48,6 +48,13 @@ struct ee_model {
     int nwg;
     size_t lds_budget;           // dynamic LDS bytes each launch asks for
     ModelDev host_md;            // the descriptor the launches carry by value
+    // Weight-stream plans and tiled weights per GEMM kind (a launch gets its plan and weights by
+    // value): [0] every workgroup streams whole rows of K, [1] K split over groups of workgroups
+    // (launches of more than 16 rows; only the kinds where it pays have one, nwg = 0 otherwise).
+    // One allocation per kind and variant, layer l (adapters: stored exit l) at w + l * wstride (uint4 units).
+    GemmPlan plan[2][G_KINDS];
+    const uint4 *w[2][G_KINDS];
+    long long wstride[2][G_KINDS];
     std::vector<void *> allocs;  // every device allocation of the model
     const float *g_exit[EE_MAX_EXITS];
     // exit-head adapters (per stored exit): biases of the hidden units and the summed output biases
@@ -127,7 +134,8 @@ static int plan_max_local(const GemmPlan &p)
     return mx;
 }
 
-static GemmPlan make_plan(int N, int K, int tpu, int nwg_max)
+// ksl > 0: K split over groups of 1 << ksl workgroups where the k-tiles divide evenly (otherwise the plan comes back unsplit)
+static GemmPlan make_plan(int N, int K, int tpu, int nwg_max, int ksl = 0)
 {
     GemmPlan p;
     memset(&p, 0, sizeof p);
@@ -138,11 +146,17 @@ static GemmPlan make_plan(int N, int K, int tpu, int nwg_max)
     p.KT = (K + 31) / 32;
     p.tpu = tpu;
     p.U = p.NT / tpu;
-    // the fewest workgroups that do not raise the busiest one's share
-    const int most = (p.U + nwg_max - 1) / nwg_max;
-    p.nwg = std::min(nwg_max, (p.U + most - 1) / most);
+    p.KTs = p.KT;
+    if (ksl > 0 && p.KT % (1 << ksl) == 0 && (nwg_max >> ksl) >= 1) {
+        p.ksl = ksl;
+        p.KTs = p.KT >> ksl;
+    }
+    // the fewest (groups of) workgroups that do not raise the busiest one's share
+    const int groups_max = nwg_max >> p.ksl;
+    const int most = (p.U + groups_max - 1) / groups_max;
+    p.nwg = std::min(groups_max, (p.U + most - 1) / most) << p.ksl;
     // every wave's sequence has room for the busiest wave's k-steps of every n-tile
-    p.steps = wave_ksteps(p.KT, 0) * plan_max_local(p);
+    p.steps = wave_ksteps(p.KTs, 0) * plan_max_local(p);
     return p;
 }
 
@@ -153,7 +167,7 @@ static bool plan_lds(const GemmPlan &p, int rows, size_t lds_total, StageLds &ly
     if (lds_total < misc + 4096) return false;
     const size_t avail = (lds_total - misc) / 256 * 256;
     const size_t tile_bytes = (size_t)rows * 128;           // one k-tile of the input: two terms, all rows
-    const int KT8 = (p.KT + SWAVES - 1) / SWAVES * SWAVES;
+    const int KT8 = (p.KTs + SWAVES - 1) / SWAVES * SWAVES;   // the k-tiles one workgroup streams
     memset(&ly, 0, sizeof ly);
     if ((size_t)KT8 * tile_bytes <= avail) {
         ly.kbt = KT8;
@@ -166,7 +180,7 @@ static bool plan_lds(const GemmPlan &p, int rows, size_t lds_total, StageLds &ly
         // blocks of one k-step per wave: a block is read faster than its copy arrives; a third
         // buffer lets the copy run two blocks ahead
         if (ly.kbt == SWAVES && avail / 3 / tile_bytes >= (size_t)SWAVES) ly.nbuf = 3;
-        ly.nkb = (p.KT + ly.kbt - 1) / ly.kbt;
+        ly.nkb = (p.KTs + ly.kbt - 1) / ly.kbt;
         if (ly.nkb < ly.nbuf) ly.nbuf = std::max(ly.nkb, 1);
     }
     ly.xbuf_bytes = (int)((size_t)ly.kbt * tile_bytes);
@@ -382,31 +396,61 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, device) == hipSuccess && optin > 0)
             lds_cap = std::max(lds_cap, (size_t)optin);
     }
-    md.plan[G_QKV] = make_plan(3 * c.d_model, c.d_model, 1, m->nwg);
-    md.plan[G_O] = make_plan(c.d_model, c.d_model, 1, m->nwg);
-    md.plan[G_GU] = make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg);
-    md.plan[G_DN] = make_plan(c.d_model, c.d_ffn, 1, m->nwg);
-    md.plan[G_HEAD] = make_plan(c.vocab, c.d_model, 1, m->nwg);
-    md.plan[G_AD] = make_plan(A ? (int)A : 16, c.d_model, 1, m->nwg);
-    md.plan[G_AU] = make_plan(c.d_model, A ? (int)A : 32, 1, m->nwg);
-    m->lds_budget = lds_cap / 256 * 256;   // the whole block: more than half of it also keeps a compute unit to one workgroup
-    for (int k = 0; k < G_KINDS; ++k) {
-        StageLds ly;
-        if (!plan_lds(md.plan[k], max_rows, m->lds_budget, ly)) {
-            ee_model_free(m);
-            return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
+    auto plan_of = [&](int kind, int ksl) {
+        switch (kind) {
+        case G_QKV: return make_plan(3 * c.d_model, c.d_model, 1, m->nwg, ksl);
+        case G_O: return make_plan(c.d_model, c.d_model, 1, m->nwg, ksl);
+        case G_GU: return make_plan(2 * c.d_ffn, c.d_model, 2, m->nwg, ksl);
+        case G_DN: return make_plan(c.d_model, c.d_ffn, 1, m->nwg, ksl);
+        case G_HEAD: return make_plan(c.vocab, c.d_model, 1, m->nwg, ksl);
+        case G_AD: return make_plan(A ? (int)A : 16, c.d_model, 1, m->nwg, ksl);
+        default: return make_plan(c.d_model, A ? (int)A : 32, 1, m->nwg, ksl);
         }
-        // the kernels' exact small-integer division (div_small) covers the unit arithmetic of this plan
-        if ((long long)md.plan[k].U * md.plan[k].nwg > DIV_SMALL_MAX || md.plan[k].N > DIV_SMALL_MAX) {
-            ee_model_free(m);
-            return fail(EE_EFORMAT, "ee_model_load: a weight matrix with %d rows is beyond what the kernels' index arithmetic covers", md.plan[k].N);
+    };
+    memset(m->plan, 0, sizeof m->plan);
+    memset(m->w, 0, sizeof m->w);
+    memset(m->wstride, 0, sizeof m->wstride);
+    for (int k = 0; k < G_KINDS; ++k) m->plan[0][k] = plan_of(k, 0);
+    if (max_rows > 16) {
+        // Launches of more than 16 rows: K split four ways for the projections whose input is as large
+        // as, or larger than, a workgroup's share of the weights (see GemmPlan).  Those weights are
+        // kept in both tile orders; launches of up to 16 rows keep using the unsplit one.
+        unsigned kinds = (1u << G_O) | (1u << G_DN);
+        int ksl = KSPLIT_LOG2;
+        if (const char *e = getenv("EE_KSPLIT")) {
+            if (sscanf(e, "%u:%d", &kinds, &ksl) != 2 || ksl < 1 || (1 << ksl) > SWAVES || kinds >= (1u << G_KINDS)) {
+                ee_model_free(m);
+                return fail(EE_EINVAL, "ee_model_load: EE_KSPLIT=\"%s\" is not <kind mask>:<log2 splits, 1..3>", e);
+            }
         }
-        // tile offsets inside a stage are 32-bit byte offsets
-        if ((long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 1024 >= (1LL << 31)) {
-            ee_model_free(m);
-            return fail(EE_EFORMAT, "ee_model_load: a weight matrix of %d x %d exceeds the 2 GiB a stage can address", md.plan[k].N, md.plan[k].K);
-        }
+        for (int k = 0; k < G_KINDS; ++k)
+            if ((kinds >> k) & 1u) {
+                const GemmPlan p = plan_of(k, ksl);
+                if (p.ksl > 0) m->plan[1][k] = p;
+            }
     }
+    m->lds_budget = lds_cap / 256 * 256;   // the whole block: more than half of it also keeps a compute unit to one workgroup
+    for (int v = 0; v < 2; ++v)
+        for (int k = 0; k < G_KINDS; ++k) {
+            const GemmPlan &pl = m->plan[v][k];
+            if (pl.nwg == 0) continue;
+            StageLds ly;
+            if (!plan_lds(pl, max_rows, m->lds_budget, ly)) {
+                ee_model_free(m);
+                return fail(EE_EDEVICE, "ee_model_load: max_rows %d needs more LDS than the device's %zu bytes", max_rows, lds_cap);
+            }
+            // the kernels' exact small-integer division (div_small) covers the unit arithmetic of this plan
+            if ((long long)pl.U * pl.nwg > DIV_SMALL_MAX || pl.N > DIV_SMALL_MAX) {
+                ee_model_free(m);
+                return fail(EE_EFORMAT, "ee_model_load: a weight matrix with %d rows is beyond what the kernels' index arithmetic covers", pl.N);
+            }
+            // tile offsets inside a stage are 32-bit byte offsets
+            if ((long long)pl.steps * pl.nwg * SWAVES * 1024 >= (1LL << 31)) {
+                ee_model_free(m);
+                return fail(EE_EFORMAT, "ee_model_load: a weight matrix of %d x %d exceeds the 2 GiB a stage can address", pl.N, pl.K);
+            }
+            m->wstride[v][k] = (long long)pl.steps * pl.nwg * SWAVES * 64;
+        }
     {
         const size_t att = (size_t)WAVES * ATT_ROWS * (c.head_dim + 2) * sizeof(float) + 16;  // wave partials + the "last item of the unit" flag
         const size_t emb = (size_t)max_rows * (((c.d_model + m->nwg - 1) / m->nwg + 3) / 4 + 1) * sizeof(float);
@@ -447,22 +491,30 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     if (hipMemcpy(dev_emb, emb, V * d * 2, hipMemcpyHostToDevice) != hipSuccess) return bail(fail(EE_EDEVICE, "upload of the embedding table failed"));
     md.emb = dev_emb;
 
-    // tiled weights: one allocation per GEMM kind, layers at a fixed stride.  Zero-filled: tile slots no wave's
+    // tiled weights: one allocation per GEMM kind and variant, layers at a fixed stride.  Zero-filled: tile slots no wave's
     // sequence reaches (a wave without k-steps, the shorter sequences' tails) are still loaded by the clamped
     // look-ahead and multiplied with zeros, so they must hold finite values.
-    for (int k = 0; k < G_KINDS; ++k) md.wstride[k] = (long long)md.plan[k].steps * md.plan[k].nwg * SWAVES * 64;
-    const long long s_head = md.wstride[G_HEAD];
-    md.wstride[G_HEAD] = 0;
-    (void)s_head;
-    const long long s_qkv = md.wstride[G_QKV], s_o = md.wstride[G_O], s_gu = md.wstride[G_GU], s_dn = md.wstride[G_DN];
-    uint4 *wqkv = nullptr, *wo = nullptr, *wgu = nullptr, *wdn = nullptr, *wlm = nullptr;
     float *g_attn = nullptr, *g_ffn = nullptr, *g_final_d = nullptr;
     const size_t Lz = (size_t)c.n_layers;
-    if ((rc = dev_alloc(m->allocs, &wqkv, Lz * s_qkv, true)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wo, Lz * s_o, true)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wgu, Lz * s_gu, true)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wdn, Lz * s_dn, true)) != EE_OK) return bail(rc);
-    if ((rc = dev_alloc(m->allocs, &wlm, (size_t)md.plan[G_HEAD].steps * md.plan[G_HEAD].nwg * SWAVES * 64, true)) != EE_OK) return bail(rc);
+    uint4 *wdev[2][G_KINDS];
+    memset(wdev, 0, sizeof wdev);
+    for (int v = 0; v < 2; ++v)
+        for (int k = 0; k < G_KINDS; ++k) {
+            if (m->plan[v][k].nwg == 0 || ((k == G_AD || k == G_AU) && !A)) continue;
+            const size_t slices = k == G_HEAD ? 1 : ((k == G_AD || k == G_AU) ? (size_t)c.n_exits : Lz);
+            if ((rc = dev_alloc(m->allocs, &wdev[v][k], std::max<size_t>(slices, 1) * (size_t)m->wstride[v][k], true)) != EE_OK) return bail(rc);
+            m->w[v][k] = wdev[v][k];
+        }
+    // every variant of a kind from the same upload
+    auto tile_all = [&](int kind, int perm, const uint16_t *const *srcs, int n_src, size_t elems_each, size_t slice) {
+        for (int v = 0; v < 2; ++v) {
+            if (!wdev[v][kind]) continue;
+            const int r = upload_tiled(m, m->plan[v][kind], perm, srcs, v == 0 ? n_src : 0, elems_each, tmp,
+                                       wdev[v][kind] + slice * (size_t)m->wstride[v][kind]);
+            if (r != EE_OK) return r;
+        }
+        return (int)EE_OK;
+    };
     if ((rc = dev_alloc(m->allocs, &g_attn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_ffn, Lz * d, false)) != EE_OK) return bail(rc);
     if ((rc = dev_alloc(m->allocs, &g_final_d, d, false)) != EE_OK) return bail(rc);
@@ -471,16 +523,16 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         const uint16_t *qkv[3] = {s.wq, s.wk, s.wv};
         const uint16_t *gu[2] = {s.wg, s.wu};
         const uint16_t *so[1] = {s.wo}, *sd[1] = {s.wd};
-        if ((rc = upload_tiled(m, md.plan[G_QKV], PERM_QKV, qkv, 3, d * d, tmp, wqkv + (size_t)l * s_qkv)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.plan[G_O], PERM_NONE, so, 1, d * d, tmp, wo + (size_t)l * s_o)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.plan[G_GU], PERM_GU, gu, 2, F * d, tmp, wgu + (size_t)l * s_gu)) != EE_OK) return bail(rc);
-        if ((rc = upload_tiled(m, md.plan[G_DN], PERM_NONE, sd, 1, d * F, tmp, wdn + (size_t)l * s_dn)) != EE_OK) return bail(rc);
+        if ((rc = tile_all(G_QKV, PERM_QKV, qkv, 3, d * d, (size_t)l)) != EE_OK) return bail(rc);
+        if ((rc = tile_all(G_O, PERM_NONE, so, 1, d * d, (size_t)l)) != EE_OK) return bail(rc);
+        if ((rc = tile_all(G_GU, PERM_GU, gu, 2, F * d, (size_t)l)) != EE_OK) return bail(rc);
+        if ((rc = tile_all(G_DN, PERM_NONE, sd, 1, d * F, (size_t)l)) != EE_OK) return bail(rc);
         if ((rc = upload_gain(s.g_attn, c.d_model, tmp, g_attn + (size_t)l * d)) != EE_OK) return bail(rc);
         if ((rc = upload_gain(s.g_ffn, c.d_model, tmp, g_ffn + (size_t)l * d)) != EE_OK) return bail(rc);
     }
     {
         const uint16_t *lm[1] = {w_lm};
-        if ((rc = upload_tiled(m, md.plan[G_HEAD], PERM_NONE, lm, 1, V * d, tmp, wlm)) != EE_OK) return bail(rc);
+        if ((rc = tile_all(G_HEAD, PERM_NONE, lm, 1, V * d, 0)) != EE_OK) return bail(rc);
         if ((rc = upload_gain(g_final, c.d_model, tmp, g_final_d)) != EE_OK) return bail(rc);
         for (int i = 0; i < c.n_exits; ++i) {
             float *ge = nullptr;
@@ -491,14 +543,10 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
     }
     if (A) {
         // adapters: weights in tile order per stored exit; biases as fp32, the bottlenecks' output biases summed in order
-        const long long s_ad = md.wstride[G_AD], s_au = md.wstride[G_AU];
-        uint4 *wad = nullptr, *wau = nullptr;
-        if ((rc = dev_alloc(m->allocs, &wad, (size_t)c.n_exits * s_ad, true)) != EE_OK) return bail(rc);
-        if ((rc = dev_alloc(m->allocs, &wau, (size_t)c.n_exits * s_au, true)) != EE_OK) return bail(rc);
         for (int i = 0; i < c.n_exits; ++i) {
             const uint16_t *sd_[1] = {ads[(size_t)i].down}, *su_[1] = {ads[(size_t)i].up};
-            if ((rc = upload_tiled(m, md.plan[G_AD], PERM_NONE, sd_, 1, A * d, tmp, wad + (size_t)i * s_ad)) != EE_OK) return bail(rc);
-            if ((rc = upload_tiled(m, md.plan[G_AU], PERM_NONE, su_, 1, d * A, tmp, wau + (size_t)i * s_au)) != EE_OK) return bail(rc);
+            if ((rc = tile_all(G_AD, PERM_NONE, sd_, 1, A * d, (size_t)i)) != EE_OK) return bail(rc);
+            if ((rc = tile_all(G_AU, PERM_NONE, su_, 1, d * A, (size_t)i)) != EE_OK) return bail(rc);
             float *bd = nullptr, *bu = nullptr;
             if ((rc = dev_alloc(m->allocs, &bd, A, false)) != EE_OK) return bail(rc);
             if ((rc = dev_alloc(m->allocs, &bu, d, false)) != EE_OK) return bail(rc);
@@ -520,14 +568,7 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
             m->ad_bdown[i] = bd;
             m->ad_bup[i] = bu;
         }
-        md.w[G_AD] = wad;
-        md.w[G_AU] = wau;
     }
-    md.w[G_QKV] = wqkv;
-    md.w[G_O] = wo;
-    md.w[G_GU] = wgu;
-    md.w[G_DN] = wdn;
-    md.w[G_HEAD] = wlm;
     md.g_attn = g_attn;
     md.g_ffn = g_ffn;
     md.g_final = g_final_d;
@@ -710,6 +751,16 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
         S_TRY(dev_alloc(s->allocs, &s->dev_sample, n));
         S_TRY(dev_alloc(s->allocs, &s->dev_sample_out, 2 * EE_MAX_ROWS + 1));
     }
+    {
+        // partial tiles of the K-split launches: [split][n-tile][row][16] floats for the largest split kind
+        size_t part = 0;
+        for (int k = 0; k < G_KINDS; ++k)
+            if (m->plan[1][k].nwg > 0) part = std::max(part, ((size_t)m->plan[1][k].NT << m->plan[1][k].ksl) * rows_max * 16);
+        if (part) {
+            S_TRY(dev_alloc(s->allocs, &sc.part, part));
+            S_TRY(dev_alloc(s->allocs, &sc.part_count, (size_t)m->nwg));
+        }
+    }
     S_TRY(dev_alloc(s->allocs, &sc.cand, (size_t)m->nwg * rows_max));
     S_TRY(dev_alloc(s->allocs, &sc.cand_sum, (size_t)m->nwg * rows_max));
     S_HIP(hipDeviceSynchronize());
@@ -806,8 +857,10 @@ static int launch_segment(ee_session *lead, PassArgs &a, int adapter_slot)
                           "launch codes of GEMM stages are their GemmKind");
             const int idx = ph - (a.do_embed ? 1 : 0);
             const int slice = code == EE_LAUNCH_HEAD ? 0 : (code >= EE_LAUNCH_ADAPTER_DOWN ? adapter_slot : a.layer_begin + idx / per_layer);
-            a.plan0 = m->host_md.plan[code];
-            a.W0 = m->host_md.w[code] + (size_t)slice * m->host_md.wstride[code];
+            // more than 16 rows: the K-split variant of the kind, where the model has one and the scratch its buffers
+            const int v = (a.rows > 16 && m->plan[1][code].nwg > 0 && a.sc.part) ? 1 : 0;
+            a.plan0 = m->plan[v][code];
+            a.W0 = m->w[v][code] + (size_t)slice * m->wstride[v][code];
             if (!plan_lds(a.plan0, a.rows, m->lds_budget, a.lay)) return fail(EE_EDEVICE, "no LDS layout for %d rows", a.rows);
         }
         const bool timed = (lead->flags & EE_TIME_LAUNCHES) && a.mode == 0;
@@ -1568,6 +1621,27 @@ extern "C" int ee_device_synchronize(int device)
 // Fills A[16][32] and B[32][16] with small integers, runs one MFMA through the
 // lane layout the kernels assume and compares with the plain product.
 // Returns EE_OK when every element agrees.
+extern "C" int ee_debug_div_small(int device, const int32_t *divisors, int n, long long *mismatches)
+{
+    if (!divisors || !mismatches || n < 1 || n > 65536) return fail(EE_EINVAL, "ee_debug_div_small: bad argument");
+    for (int i = 0; i < n; ++i)
+        if (divisors[i] < 1) return fail(EE_EINVAL, "ee_debug_div_small: divisor %d", divisors[i]);
+    HIP_TRY(hipSetDevice(device));
+    int *dd = nullptr;
+    unsigned long long *dbad = nullptr, bad = 0;
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&dd), (size_t)n * sizeof(int)));
+    HIP_TRY(hipMalloc(reinterpret_cast<void **>(&dbad), sizeof bad));
+    HIP_TRY(hipMemcpy(dd, divisors, (size_t)n * sizeof(int), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemset(dbad, 0, sizeof bad));
+    hipLaunchKernelGGL(div_small_check_kernel, dim3(256, std::min(n, 256)), dim3(256), 0, 0, dd, n, DIV_SMALL_MAX, dbad);
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipMemcpy(&bad, dbad, sizeof bad, hipMemcpyDeviceToHost));
+    hipFree(dd);
+    hipFree(dbad);
+    *mismatches = (long long)bad;
+    return EE_OK;
+}
+
 extern "C" int ee_debug_mfma_layout(int device)
 {
     HIP_TRY(hipSetDevice(device));

@@ -45,6 +45,14 @@ def test_mfma_lane_layout():
     ee.ee_debug_mfma_layout(0)
 
 
+def test_reciprocal_division_is_exact():
+    """The kernels' x / d by reciprocal and multiply, over the whole range the loader admits
+    (every x up to 2.5 million), for every divisor up to 4096 and the sizes that occur as divisors
+    (rows * 4, workgroups, model and head widths, vocabulary)."""
+    divisors = list(range(1, 4097)) + [5120, 11008, 13824, 32000, 65536, 140000, 1 << 20, 2499999, 2500000, 2500001, 1 << 30]
+    assert ee.ee_debug_div_small(divisors) == 0
+
+
 def _one_round(g, o, prompt, drafts, exits, flags=0, what="", options=()):
     gs = g.session(len(prompt) + 64, max_gamma=15, flags=ee.KEEP_LOGITS | flags)
     os_ = o.session(len(prompt) + 64)
@@ -399,6 +407,63 @@ def test_batch_shapes(model_dir, B, gamma, max_rows):
     finally:
         for s in sess:
             s.free()
+        g.free()
+
+
+@pytest.mark.parametrize("ksl,B,gamma", [(2, 6, 4), (1, 3, 15), (3, 6, 4), (2, 16, 2)])
+def test_k_split_over_workgroups(model_dir, monkeypatch, ksl, B, gamma):
+    """Launches of more than 16 rows with K split over groups of 2, 4 and 8 workgroups, forced for
+    every GEMM kind (QKV, O, gate/up, down, adapters, LM head: each epilogue runs on the partial
+    tiles of the splits), two and three row tiles, a prefill chunk of more than 16 rows included;
+    twice the same pass gives bit-identical results (the sums do not depend on which workgroup
+    arrives last)."""
+    cfg = eegen.ModelConfig(n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=640, vocab=1024,
+                            exit_layers=(1, 3), n_adapters=2, adapter_width=64)
+    p = f"{model_dir}/gpu_ksplit.bin"
+    eegen.write_model(p, cfg, 91, gains="uniform", std=0.05)
+    monkeypatch.setenv("EE_KSPLIT", f"127:{ksl}")
+    g = ee.Model(p, max_rows=48)
+    o = eo.Model(p)
+    exits = [1, 3]
+    sess, osess = [], []
+    try:
+        for b in range(B):
+            toks = eegen.prompt_tokens(410, 19 + 3 * b, o.vocab, session=b)
+            gs = g.session(128, max_gamma=gamma, flags=ee.KEEP_LOGITS if b == 0 else 0)
+            os_ = o.session(128)
+            fo, margin = oracle_prefill(os_, toks)
+            check_first_token(gs, gs.ee_prefill(toks), fo, margin, f"k split session {b}")
+            sess.append(gs)
+            osess.append(os_)
+        for rnd in range(2):
+            drafts = [eegen.prompt_tokens(411 + rnd, gamma, o.vocab, session=b) for b in range(B)]
+            again = None
+            if rnd == 0:     # the same pass twice, without committing the first time
+                lens = [s_.ee_kv_len() for s_ in sess]
+                pend = [s_.ee_pending() for s_ in sess]
+                ee.ee_verify_batch(sess, drafts, exits)
+                for s_ in sess:
+                    s_.ee_wait_final()
+                again = [sess[b].final_result() for b in range(B)]
+                for b in range(B):
+                    sess[b].ee_kv_truncate(lens[b])
+                    sess[b].ee_set_pending(pend[b])
+            ee.ee_verify_batch(sess, drafts, exits)
+            for b in range(B):
+                sess[b].ee_wait_final()
+                ro = osess[b].verify(drafts[b], exits, want_logits=True)
+                rg = sess[b].final_result()
+                if again is not None:
+                    assert np.array_equal(rg.final_tokens, again[b].final_tokens) and np.array_equal(rg.exit_tokens, again[b].exit_tokens)
+                    assert np.array_equal(rg.exit_conf.view(np.uint32), again[b].exit_conf.view(np.uint32))
+                exempt, _ = check_pass(ro, rg, None, drafts[b], f"k split {1 << ksl} B={B} round {rnd} session {b}")
+                if exempt and (rg.accept_len != ro.accept_len or rg.next_token != ro.next_token):
+                    sess[b].ee_kv_truncate(osess[b].kv_len)
+                    sess[b].ee_set_pending(osess[b].pending)
+                assert sess[b].ee_kv_len() == osess[b].kv_len and sess[b].ee_pending() == osess[b].pending
+    finally:
+        for s_ in sess:
+            s_.free()
         g.free()
 
 
