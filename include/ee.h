@@ -123,13 +123,19 @@ const char *ee_last_error(void);
    uses 16.  With max_rows > 16 the output and down projections are kept in a second
    tile order as well, in which groups of four workgroups share their output columns and
    split K; launches of more than 16 rows use it (about a quarter more device memory for
-   the weights).  The environment variable EE_KSPLIT="<mask>:<log2 splits>" read here
-   overrides which GEMM kinds get that second order (bit 0 QKV, 1 output, 2 gate/up,
-   3 down, 4 LM head, 5 and 6 the adapters) and the number of splits (1 to 3): a tuning
-   and test knob, results are the same up to the summation order.
+   the weights).
    Cold path; synchronous. */
 int ee_model_load(const char *path, int device, ee_model **out);
 int ee_model_load_ex(const char *path, int device, int max_rows, ee_model **out);
+
+/* Tuning and test knob, process-wide, for models loaded after the call with max_rows > 16:
+   which GEMM kinds get the K-split tile order (kind_mask: bit 0 QKV, 1 output projection,
+   2 gate/up, 3 down projection, 4 LM head, 5 and 6 the adapters; default output and down)
+   and into how many workgroups K is split (2^log2_splits, 1 <= log2_splits <= 3; default 2).
+   A kind whose K is not a multiple of 32 * 2^log2_splits stays unsplit.  Results are the
+   same up to the order of the fp32 sums.  Not synchronised with concurrent loads.
+   EE_EINVAL for values outside these ranges. */
+int ee_tune_k_split(unsigned kind_mask, int log2_splits);
 int ee_model_free(ee_model *m);
 int ee_model_info(const ee_model *m, ee_model_config *out);
 

@@ -36,7 +36,7 @@ EXPORTS = [
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
     "ee_verify_batch", "ee_verify_static", "ee_verify_sampled", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
-    "ee_debug_logits", "ee_debug_mfma_layout", "ee_debug_div_small", "ee_device_synchronize", "ee_session_option",
+    "ee_debug_logits", "ee_debug_mfma_layout", "ee_debug_div_small", "ee_tune_k_split", "ee_device_synchronize", "ee_session_option",
     "ee_launch_times", "ee_debug_copy", "ee_exit_pop", "ee_exit_order", "ee_latency_model",
 ]
 
@@ -124,6 +124,7 @@ def load_library():
     lib.ee_pending.argtypes = [vp, i32p]
     lib.ee_debug_logits.argtypes = [vp, ci, vp]
     lib.ee_debug_mfma_layout.argtypes = [ci]
+    lib.ee_tune_k_split.argtypes = [ctypes.c_uint, ci]
     lib.ee_debug_div_small.argtypes = [ci, ctypes.POINTER(ctypes.c_int32), ci, ctypes.POINTER(ctypes.c_longlong)]
     lib.ee_device_synchronize.argtypes = [ci]
     lib.ee_session_option.argtypes = [vp, ci, ci]
@@ -159,6 +160,10 @@ def ee_device_synchronize(device: int = 0) -> None:
 
 def ee_debug_mfma_layout(device: int = 0) -> None:
     _check(load_library().ee_debug_mfma_layout(device))
+
+
+def ee_tune_k_split(kind_mask: int, log2_splits: int) -> None:
+    _check(load_library().ee_tune_k_split(kind_mask, log2_splits))
 
 
 def ee_debug_div_small(divisors, device: int = 0) -> int:

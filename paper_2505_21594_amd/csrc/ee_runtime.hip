@@ -244,6 +244,19 @@ static int upload_gain(const uint16_t *src, int d, uint16_t *tmp, float *dst)
     return EE_OK;
 }
 
+// which GEMM kinds get a K-split tile order in models loaded for more than 16 rows, and the splits (ee_tune_k_split)
+static unsigned g_ksplit_kinds = (1u << G_O) | (1u << G_DN);
+static int g_ksplit_log2 = KSPLIT_LOG2;
+
+extern "C" int ee_tune_k_split(unsigned kind_mask, int log2_splits)
+{
+    if (log2_splits < 1 || (1 << log2_splits) > SWAVES || kind_mask >= (1u << G_KINDS))
+        return fail(EE_EINVAL, "ee_tune_k_split: mask %u, log2 splits %d (mask below %u, 1 <= log2 splits <= 3)", kind_mask, log2_splits, 1u << G_KINDS);
+    g_ksplit_kinds = kind_mask;
+    g_ksplit_log2 = log2_splits;
+    return EE_OK;
+}
+
 extern "C" int ee_model_free(ee_model *m)
 {
     if (!m) return EE_OK;
@@ -415,14 +428,8 @@ extern "C" int ee_model_load_ex(const char *path, int device, int max_rows, ee_m
         // Launches of more than 16 rows: K split four ways for the projections whose input is as large
         // as, or larger than, a workgroup's share of the weights (see GemmPlan).  Those weights are
         // kept in both tile orders; launches of up to 16 rows keep using the unsplit one.
-        unsigned kinds = (1u << G_O) | (1u << G_DN);
-        int ksl = KSPLIT_LOG2;
-        if (const char *e = getenv("EE_KSPLIT")) {
-            if (sscanf(e, "%u:%d", &kinds, &ksl) != 2 || ksl < 1 || (1 << ksl) > SWAVES || kinds >= (1u << G_KINDS)) {
-                ee_model_free(m);
-                return fail(EE_EINVAL, "ee_model_load: EE_KSPLIT=\"%s\" is not <kind mask>:<log2 splits, 1..3>", e);
-            }
-        }
+        const unsigned kinds = g_ksplit_kinds;
+        const int ksl = g_ksplit_log2;
         for (int k = 0; k < G_KINDS; ++k)
             if ((kinds >> k) & 1u) {
                 const GemmPlan p = plan_of(k, ksl);

@@ -73,3 +73,16 @@ def test_null_handles():
     assert lib.ee_verify(None, None, 1, None, 0, None) == ee.EE_EINVAL
     assert lib.ee_session_free(None) == ee.EE_OK
     assert lib.ee_model_free(None) == ee.EE_OK
+
+
+def test_k_split_tuning_values_are_checked():
+    lib = ee.load_library()
+    for mask, log2 in ((0b1010, 0), (0b1010, 4), (1 << 7, 2), (0b1010, -1)):
+        assert lib.ee_tune_k_split(mask, log2) == ee.EE_EINVAL
+        assert b"ee_tune_k_split" in lib.ee_last_error()
+    for mask, log2 in ((0, 1), (127, 3), (0b1010, 2)):     # ends on the default
+        assert lib.ee_tune_k_split(mask, log2) == ee.EE_OK
+    d = (ctypes.c_int32 * 2)(3, 0)
+    bad = ctypes.c_longlong(0)
+    assert lib.ee_debug_div_small(0, d, 2, ctypes.byref(bad)) == ee.EE_EINVAL      # a divisor below 1: refused on the host
+    assert lib.ee_debug_div_small(0, None, 2, ctypes.byref(bad)) == ee.EE_EINVAL

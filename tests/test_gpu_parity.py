@@ -411,7 +411,7 @@ def test_batch_shapes(model_dir, B, gamma, max_rows):
 
 
 @pytest.mark.parametrize("ksl,B,gamma", [(2, 6, 4), (1, 3, 15), (3, 6, 4), (2, 16, 2)])
-def test_k_split_over_workgroups(model_dir, monkeypatch, ksl, B, gamma):
+def test_k_split_over_workgroups(model_dir, ksl, B, gamma):
     """Launches of more than 16 rows with K split over groups of 2, 4 and 8 workgroups, forced for
     every GEMM kind (QKV, O, gate/up, down, adapters, LM head: each epilogue runs on the partial
     tiles of the splits), two and three row tiles, a prefill chunk of more than 16 rows included;
@@ -421,8 +421,11 @@ def test_k_split_over_workgroups(model_dir, monkeypatch, ksl, B, gamma):
                             exit_layers=(1, 3), n_adapters=2, adapter_width=64)
     p = f"{model_dir}/gpu_ksplit.bin"
     eegen.write_model(p, cfg, 91, gains="uniform", std=0.05)
-    monkeypatch.setenv("EE_KSPLIT", f"127:{ksl}")
-    g = ee.Model(p, max_rows=48)
+    ee.ee_tune_k_split(127, ksl)
+    try:
+        g = ee.Model(p, max_rows=48)
+    finally:
+        ee.ee_tune_k_split(0b1010, 2)   # back to the default: output and down projection, four splits
     o = eo.Model(p)
     exits = [1, 3]
     sess, osess = [], []
