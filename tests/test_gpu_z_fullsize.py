@@ -196,10 +196,53 @@ def test_llama13b_gamma5_ctx1024(capsys):
             _rounds(capsys, "13B g5 ctx1024", g, o, cfg, prompt, 5, [20], 0.3, 8, 20250524)
         finally:
             g.free()
+        try:
+            _batch_13b(capsys, path, o, cfg)
+        finally:
             o.close()
     finally:
         if os.path.exists(path):
             os.remove(path)   # 26 GB of /dev/shm
+
+
+def _batch_13b(capsys, path, o, cfg):
+    """Four sessions of six rows in one pass on the 13B shape (24 rows: two row tiles; output and
+    down projection with K split over workgroups, 320 units over 64 groups of four), short prompts,
+    three rounds with commit, every session's logits compared."""
+    gamma, exits, B, seed, rounds = 5, [20], 4, 20250525, 3
+    g = ee.Model(path, max_rows=B * (gamma + 1))
+    gss, oss = [], []
+    t0 = time.time()
+    try:
+        for b in range(B):
+            txt = eegen.prompt_tokens(seed, 24 + 5 * b, cfg.vocab, session=b)
+            gs = g.session(128, max_gamma=gamma, flags=ee.KEEP_LOGITS if b == 0 else 0)
+            os_ = o.session(128)
+            first_o, margin = oracle_prefill(os_, txt)
+            check_first_token(gs, gs.ee_prefill(txt), first_o, margin, f"13B batch session {b}")
+            gss.append(gs)
+            oss.append(os_)
+        worst = 0.0
+        for r in range(rounds):
+            drafts = [eegen.corrupt_drafts(oracle_greedy(oss[b], gamma), 0.3, cfg.vocab, seed, r, session=b) for b in range(B)]
+            ee.ee_verify_batch(gss, drafts, exits)
+            for gs in gss:
+                gs.ee_wait_final()
+            for b in range(B):
+                ro = oss[b].verify(drafts[b], exits, commit=True, want_logits=True)
+                rg = gss[b].final_result()
+                exempt, err = check_pass(ro, rg, gpu_logits(gss[b], len(exits)), drafts[b], f"13B batch round {r} session {b}")
+                worst = max(worst, err)
+                if rg.accept_len != ro.accept_len or rg.next_token != ro.next_token:
+                    assert exempt
+                    gss[b].ee_kv_truncate(oss[b].kv_len)
+                    gss[b].ee_set_pending(oss[b].pending)
+                assert gss[b].ee_kv_len() == oss[b].kv_len and gss[b].ee_pending() == oss[b].pending
+            _say(capsys, f"[13B b4] round {r + 1}/{rounds}: worst logits err {worst:.3g}, {time.time() - t0:.0f}s")
+    finally:
+        for gs in gss:
+            gs.free()
+        g.free()
 
 
 @pytest.mark.timeout(600)
