@@ -208,7 +208,11 @@ int ee_verify_static(ee_session *s, const int32_t *draft_tokens, int gamma, cons
      draft_probs  [gamma][vocab] fp32, row i = the distribution draft i+1 was drawn from;
      u            [gamma] in [0,1);   v  [gamma+1] in [0,1);   temperature > 0.
    The cumulative sums are taken in 40-bit fixed point (exact, order-free), the probabilities
-   in fp32.  One session per pass, created with EE_SAMPLING; gamma <= its max_gamma. */
+   in fp32.  Sessions created with EE_SAMPLING; gamma <= their max_gamma.
+   ee_verify_sampled_batch is ee_verify_batch with samplings[i] for sessions[i] (each session
+   its own distributions, numbers and temperature; every head of every session decides by the
+   same rule).  The draft distributions travel to the device with the call: gamma * vocab
+   floats per session. */
 typedef struct ee_sampling {
     const float *draft_probs;
     const float *u;
@@ -217,6 +221,9 @@ typedef struct ee_sampling {
 } ee_sampling;
 int ee_verify_sampled(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers,
                       int n_exits, const ee_sampling *sampling, const ee_verify_result **out);
+int ee_verify_sampled_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts,
+                            int gamma, const int32_t *exit_layers, int n_exits,
+                            const ee_sampling *samplings, const ee_verify_result **outs);
 
 int ee_wait_exit(ee_session *s, int exit_idx);   /* blocks until exit exit_idx is published */
 int ee_query_exit(ee_session *s, int exit_idx);  /* EE_OK or EE_NOT_READY                   */

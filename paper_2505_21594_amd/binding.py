@@ -36,7 +36,7 @@ EXPORTS = [
     "ee_session_create", "ee_session_free", "ee_prefill", "ee_prefill_embeds", "ee_verify",
     "ee_verify_batch", "ee_verify_static", "ee_verify_sampled", "ee_wait_exit", "ee_query_exit", "ee_wait_final", "ee_query_final",
     "ee_pass_time_ms", "ee_kv_truncate", "ee_set_pending", "ee_kv_len", "ee_pending",
-    "ee_debug_logits", "ee_debug_mfma_layout", "ee_debug_div_small", "ee_tune_k_split", "ee_device_synchronize", "ee_session_option",
+    "ee_verify_sampled_batch", "ee_debug_logits", "ee_debug_mfma_layout", "ee_debug_div_small", "ee_tune_k_split", "ee_device_synchronize", "ee_session_option",
     "ee_launch_times", "ee_debug_copy", "ee_exit_pop", "ee_exit_order", "ee_latency_model",
 ]
 
@@ -113,6 +113,7 @@ def load_library():
     lib.ee_verify_static.argtypes = [vp, i32p, ci, i32p, ci, P(P(VerifyResultC))]
     lib.ee_verify_sampled.argtypes = [vp, i32p, ci, i32p, ci, P(SamplingC), P(P(VerifyResultC))]
     lib.ee_verify_batch.argtypes = [P(vp), ci, P(i32p), ci, i32p, ci, P(P(VerifyResultC))]
+    lib.ee_verify_sampled_batch.argtypes = [P(vp), ci, P(i32p), ci, i32p, ci, P(SamplingC), P(P(VerifyResultC))]
     lib.ee_wait_exit.argtypes = [vp, ci]
     lib.ee_query_exit.argtypes = [vp, ci]
     lib.ee_wait_final.argtypes = [vp]
@@ -156,6 +157,35 @@ def _p(a: np.ndarray):
 
 def ee_device_synchronize(device: int = 0) -> None:
     _check(load_library().ee_device_synchronize(device))
+
+
+def ee_verify_sampled_batch(sessions: List[Session], drafts: List[Sequence[int]], draft_probs, u, v, temperatures,
+                            exit_layers: Sequence[int] = ()) -> None:
+    """ee_verify_batch with each session's draft distributions [gamma][vocab], uniform numbers
+    u [gamma], v [gamma+1] and temperature (lists, one entry per session)."""
+    lib = load_library()
+    n = len(sessions)
+    hs = (ctypes.c_void_p * n)(*[s._h for s in sessions])
+    ds = [_i32(d) for d in drafts]
+    gamma = ds[0].size
+    assert all(d.size == gamma for d in ds)
+    dp = (ctypes.POINTER(ctypes.c_int32) * n)(*[_p(d) for d in ds])
+    fp = ctypes.POINTER(ctypes.c_float)
+    keep = []
+    sms = (SamplingC * n)()
+    for i in range(n):
+        pr = np.ascontiguousarray(draft_probs[i], dtype=np.float32)
+        uu = np.ascontiguousarray(u[i], dtype=np.float32)
+        vv = np.ascontiguousarray(v[i], dtype=np.float32)
+        if pr.shape != (gamma, sessions[i].model.vocab) or uu.size != gamma or vv.size != gamma + 1:
+            raise ValueError("draft_probs [gamma][vocab], u [gamma], v [gamma+1] expected for every session")
+        keep += [pr, uu, vv]
+        sms[i] = SamplingC(pr.ctypes.data_as(fp), uu.ctypes.data_as(fp), vv.ctypes.data_as(fp), float(temperatures[i]))
+    ex = _i32(exit_layers)
+    outs = (ctypes.POINTER(VerifyResultC) * n)()
+    _check(lib.ee_verify_sampled_batch(hs, n, dp, gamma, _p(ex), ex.size, sms, outs))
+    for i, s in enumerate(sessions):
+        s._res, s._n_exits, s._gamma = outs[i], ex.size, gamma
 
 
 def ee_debug_mfma_layout(device: int = 0) -> None:

@@ -164,11 +164,11 @@ struct Scratch {
 
 enum HeadKind { HEAD_NONE = 0, HEAD_EXIT = 1, HEAD_FINAL = 2, HEAD_PREFILL = 3 };
 
-// Probabilistic verification (one session per pass): inputs and per-row decisions.
+// Probabilistic verification: inputs and per-row decisions.
 struct SampleDev {
-    const float *probs;  // [gamma][V]  the draft model's distributions
-    const float *uv;     // [gamma] keep tests' uniform numbers, then [gamma+1] the rows' sampling numbers
-    float inv_T;         // 1 / temperature
+    const float *probs;  // [session][gamma][V]  the draft model's distributions
+    const float *uv;     // per session 2 gamma + 2 floats: [gamma] the keep tests' uniform numbers, [gamma+1] the rows'
+                         // sampling numbers, 1 / temperature
     int on;              // 1: the pass decides by the draft probabilities instead of by exact match
     int *tok;            // [head rows]  token a row emits if the round ends there
     int *kept;           // [head rows]  1: the row's draft passes its test

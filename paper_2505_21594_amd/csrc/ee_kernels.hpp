@@ -1288,8 +1288,9 @@ __device__ __forceinline__ void accept_stage(const PassArgs &a, char *lds)
                 int *ts = tok + (hj * a.n_sess + s) * M;
                 unsigned kept = 0;
                 for (int i = 0; i < M; ++i) {
-                    ts[i] = __hip_atomic_load(a.sm.tok + hj * M + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (i < gamma && __hip_atomic_load(a.sm.kept + hj * M + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) kept |= 1u << i;
+                    const int r = (hj * a.n_sess + s) * M + i;   // the row of the head launch
+                    ts[i] = __hip_atomic_load(a.sm.tok + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (i < gamma && __hip_atomic_load(a.sm.kept + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) kept |= 1u << i;
                 }
                 delta = __builtin_ctz(~kept);   // drafts kept before the first one that is not (bit gamma is never set)
             } else {
@@ -1379,15 +1380,18 @@ __device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds
 {
     static_assert(WAVES * 8 * 2 + WAVES * 4 + 16 <= SAMPLE_LDS_BYTES && EE_MAX_ROWS * 8 <= SAMPLE_LDS_BYTES, "LDS of the sampling launch");
     const int V = a.mdv.V, M = a.M, gamma = M - 1;
-    const int hj = div_small(r, M), i = r - hj * M;
+    const int per_head = a.n_sess * M;                          // the launch's rows: head after head, session after session
+    const int hj = div_small(r, per_head), rr = r - hj * per_head;
+    const int ses = div_small(rr, M), i = rr - ses * M;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     u64 *wtot = reinterpret_cast<u64 *>(lds);                   // [WAVES] the waves' totals (target terms)
     u64 *rtot = wtot + WAVES;                                   // [WAVES] the same for the residual weights
     float *wmax = reinterpret_cast<float *>(rtot + WAVES);      // [WAVES]
     int *found = reinterpret_cast<int *>(wmax + WAVES);
-    const EE_GLOBAL float *z = as_global(a.sc.logits) + ((size_t)(a.head_idx + hj) * a.mdv.rows_max + i) * V;
-    const EE_GLOBAL float *p = as_global(a.sm.probs) + (size_t)min(i, gamma - 1) * V;
-    const float inv_T = a.sm.inv_T;
+    const EE_GLOBAL float *z = as_global(a.sc.logits) + ((size_t)(a.head_idx + hj) * a.mdv.rows_max + rr) * V;
+    const EE_GLOBAL float *p = as_global(a.sm.probs) + ((size_t)ses * gamma + min(i, gamma - 1)) * V;
+    const EE_GLOBAL float *uv = as_global(a.sm.uv) + (size_t)ses * (2 * gamma + 2);   // the session's u, v and 1 / temperature
+    const float inv_T = uv[2 * gamma + 1];
     const int S = ((V + WAVES - 1) / WAVES + 63) & ~63;         // tokens per wave, whole blocks of 64
     const int t0 = min(V, wave * S), t1 = min(V, t0 + S);
     constexpr int CHUNK = SAMPLE_CH * 64;
@@ -1429,9 +1433,9 @@ __device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds
     bool residual = false;
     int kept = 0;
     if (i < gamma) {
-        const int x = as_global(a.sess0.drafts)[i];
+        const int x = as_global(EE_SESS(a, ses, drafts))[i];
         const float qx = target_term(z[x], zmax, inv_T) * inv_Z;
-        kept = as_global(a.sm.uv)[i] * p[x] < qx ? 1 : 0;
+        kept = uv[i] * p[x] < qx ? 1 : 0;
         u64 rp = 0;
         for (int c0 = t0; c0 < t1; c0 += CHUNK) {
             load_chunk(z, c0, t1, lane, -INFINITY, zc);
@@ -1452,7 +1456,7 @@ __device__ __forceinline__ void sample_stage(const PassArgs &a, int r, char *lds
         }
     }
     // the first token whose cumulative weight exceeds the target; v < 1, so target < w_total
-    const double vd = (double)as_global(a.sm.uv)[gamma + i];
+    const double vd = (double)uv[gamma + i];
     u64 target = (u64)(vd * (double)w_total);
     if (target >= w_total) target = w_total - 1;
     u64 before = 0;                                              // cumulative weight of the waves before this one

@@ -753,7 +753,8 @@ extern "C" int ee_session_create(const ee_model *m, int max_ctx, int max_gamma, 
     if (flags & (EE_KEEP_LOGITS | EE_SAMPLING))
         S_TRY(dev_alloc(s->allocs, &sc.logits, (size_t)(EE_MAX_EXITS + 1) * rows_max * c.vocab));
     if (flags & EE_SAMPLING) {
-        const size_t n = (size_t)max_gamma * c.vocab + 2 * (size_t)max_gamma + 1;
+        // room for the draft distributions of every row a pass led by this session can carry
+        const size_t n = (size_t)rows_max * c.vocab + (size_t)EE_MAX_BATCH * (2 * EE_MAX_M + 2);
         S_HIP(hipHostMalloc(reinterpret_cast<void **>(&s->host_sample), n * sizeof(float), hipHostMallocDefault));
         S_TRY(dev_alloc(s->allocs, &s->dev_sample, n));
         S_TRY(dev_alloc(s->allocs, &s->dev_sample_out, 2 * EE_MAX_ROWS + 1));
@@ -1168,18 +1169,21 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
             return fail(EE_EINVAL, "ee_verify_batch: sessions mix EE_NO_AUTOCOMMIT settings");
     }
     if (n_sessions * M > c.max_rows) return fail(EE_EINVAL, "ee_verify: %d rows exceed the model's max_rows %d", n_sessions * M, c.max_rows);
-    if (sp) {
-        if (n_sessions != 1 || static_scratch) return fail(EE_EINVAL, "ee_verify_sampled: one session per pass");
-        if (!(lead->flags & EE_SAMPLING)) return fail(EE_ESTATE, "ee_verify_sampled: the session was created without EE_SAMPLING");
-        if (!sp->draft_probs || !sp->u || !sp->v) return fail(EE_EINVAL, "ee_verify_sampled: null draft_probs, u or v");
-        if (!(sp->temperature > 0.f) || !std::isfinite(sp->temperature)) return fail(EE_EINVAL, "ee_verify_sampled: temperature must be positive");
-        for (int i = 0; i < gamma; ++i)
-            if (!(sp->u[i] >= 0.f && sp->u[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: u[%d] not in [0,1)", i);
-        for (int i = 0; i <= gamma; ++i)
-            if (!(sp->v[i] >= 0.f && sp->v[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: v[%d] not in [0,1)", i);
-        for (int i = 0; i < gamma; ++i) {   // the drafts' own probabilities; the full rows are the caller's responsibility
-            const float px = sp->draft_probs[(size_t)i * c.vocab + drafts[0][i]];
-            if (!(px >= 0.f && px <= 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: draft_probs[%d][draft] = %g is not a probability", i, (double)px);
+    if (sp) {   // sp[b]: session b's draft distributions and uniform numbers
+        if (static_scratch) return fail(EE_EINVAL, "ee_verify_sampled: not with the static scratch");
+        for (int b = 0; b < n_sessions; ++b) {
+            const ee_sampling &q = sp[b];
+            if (!(sessions[b]->flags & EE_SAMPLING)) return fail(EE_ESTATE, "ee_verify_sampled: session %d was created without EE_SAMPLING", b);
+            if (!q.draft_probs || !q.u || !q.v) return fail(EE_EINVAL, "ee_verify_sampled: null draft_probs, u or v");
+            if (!(q.temperature > 0.f) || !std::isfinite(q.temperature)) return fail(EE_EINVAL, "ee_verify_sampled: temperature must be positive");
+            for (int i = 0; i < gamma; ++i)
+                if (!(q.u[i] >= 0.f && q.u[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: u[%d] not in [0,1)", i);
+            for (int i = 0; i <= gamma; ++i)
+                if (!(q.v[i] >= 0.f && q.v[i] < 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: v[%d] not in [0,1)", i);
+            for (int i = 0; i < gamma; ++i) {   // the drafts' own probabilities; the full rows are the caller's responsibility
+                const float px = q.draft_probs[(size_t)i * c.vocab + drafts[b][i]];
+                if (!(px >= 0.f && px <= 1.f)) return fail(EE_EINVAL, "ee_verify_sampled: draft_probs[%d][draft] = %g is not a probability", i, (double)px);
+            }
         }
     }
     const float *gains[EE_MAX_EXITS];
@@ -1224,14 +1228,18 @@ static int verify_impl(ee_session *const *sessions, int n_sessions, const int32_
     a.mode = 0;
     a.commit = (lead->flags & EE_NO_AUTOCOMMIT) ? 0 : 1;
     if (sp) {
-        const size_t V = (size_t)c.vocab, n = (size_t)gamma * V + 2 * (size_t)gamma + 1;
-        memcpy(lead->host_sample, sp->draft_probs, (size_t)gamma * V * sizeof(float));
-        memcpy(lead->host_sample + (size_t)gamma * V, sp->u, (size_t)gamma * sizeof(float));
-        memcpy(lead->host_sample + (size_t)gamma * V + gamma, sp->v, (size_t)(gamma + 1) * sizeof(float));
-        HIP_TRY(hipMemcpyAsync(lead->dev_sample, lead->host_sample, n * sizeof(float), hipMemcpyHostToDevice, lead->run_stream));
+        // [session][gamma][V] distributions, then per session u, v and 1 / temperature (SampleDev)
+        const size_t V = (size_t)c.vocab, np = (size_t)n_sessions * gamma * V, blk = 2 * (size_t)gamma + 2;
+        for (int b = 0; b < n_sessions; ++b) {
+            memcpy(lead->host_sample + (size_t)b * gamma * V, sp[b].draft_probs, (size_t)gamma * V * sizeof(float));
+            float *uv = lead->host_sample + np + (size_t)b * blk;
+            memcpy(uv, sp[b].u, (size_t)gamma * sizeof(float));
+            memcpy(uv + gamma, sp[b].v, (size_t)(gamma + 1) * sizeof(float));
+            uv[2 * gamma + 1] = 1.0f / sp[b].temperature;
+        }
+        HIP_TRY(hipMemcpyAsync(lead->dev_sample, lead->host_sample, (np + (size_t)n_sessions * blk) * sizeof(float), hipMemcpyHostToDevice, lead->run_stream));
         a.sm.probs = lead->dev_sample;
-        a.sm.uv = lead->dev_sample + (size_t)gamma * V;
-        a.sm.inv_T = 1.0f / sp->temperature;
+        a.sm.uv = lead->dev_sample + np;
         a.sm.on = 1;
         a.sm.tok = lead->dev_sample_out;
         a.sm.kept = lead->dev_sample_out + EE_MAX_ROWS;
@@ -1319,6 +1327,14 @@ extern "C" int ee_verify_sampled(ee_session *s, const int32_t *draft_tokens, int
     int rc = verify_impl(ss, 1, dd, gamma, exit_layers, n_exits, oo, false, sampling);
     if (rc == EE_OK && out) *out = oo[0];
     return rc;
+}
+
+extern "C" int ee_verify_sampled_batch(ee_session *const *sessions, int n_sessions, const int32_t *const *drafts, int gamma,
+                                       const int32_t *exit_layers, int n_exits, const ee_sampling *samplings,
+                                       const ee_verify_result **outs)
+{
+    if (!samplings) return fail(EE_EINVAL, "ee_verify_sampled_batch: null sampling arguments");
+    return verify_impl(sessions, n_sessions, drafts, gamma, exit_layers, n_exits, outs, false, samplings);
 }
 
 extern "C" int ee_verify_static(ee_session *s, const int32_t *draft_tokens, int gamma, const int32_t *exit_layers, int n_exits,

@@ -6,7 +6,7 @@ import pytest
 import eegen
 import paper_2505_21594_amd as ee
 from oracle import oracle as eo
-from tests.parity import check_first_token, check_pass, gpu_logits, oracle_greedy, oracle_prefill, sampled_chain
+from tests.parity import check_first_token, check_pass, check_sampled_pass, gpu_logits, oracle_greedy, oracle_prefill, sampled_chain
 
 pytestmark = pytest.mark.gpu
 
@@ -682,6 +682,61 @@ def test_sampled_verification_mid(mid_pair):
     exempt_rounds, bound, kept, more = sampled_chain(g, o, prompt, gamma, [1, 2], rounds, 0.2, seed=22, what="sampled mid")
     print(f"sampled mid: bound {bound} of {rounds * 3 * (gamma + 2)}, exempt rounds {exempt_rounds}, drafts kept {kept}, more than exact match {more}")
     assert bound >= 0.8 * rounds * 3 * (gamma + 2), (bound, exempt_rounds)
+
+
+@pytest.mark.parametrize("B,gamma,max_rows", [(3, 4, 16), (5, 4, 25), (4, 7, 32)])
+def test_sampled_verification_batch(model_dir, B, gamma, max_rows):
+    """Probabilistic verification for several sessions in one pass (one, two row tiles): each
+    session with its own draft distributions, uniform numbers and temperature; every session's
+    heads against the oracle's sampler, several rounds with commit."""
+    p = f"{model_dir}/gpu_tiny_sampled_batch.bin"
+    eegen.write_model(p, eegen.TINY, 77, gains="uniform")
+    g = ee.Model(p, max_rows=max_rows)
+    o = eo.Model(p)
+    temps = [1.0, 0.3, 0.1, 0.7, 0.05][:B]
+    sess, osess, hists = [], [], []
+    try:
+        for b in range(B):
+            toks = eegen.prompt_tokens(430, 21 + 4 * b, o.vocab, session=b)
+            gs = g.session(128, max_gamma=gamma, flags=ee.KEEP_LOGITS | ee.SAMPLING)
+            os_ = o.session(128)
+            fo, margin = oracle_prefill(os_, toks)
+            check_first_token(gs, gs.ee_prefill(toks), fo, margin, f"sampled batch session {b}")
+            sess.append(gs)
+            osess.append(os_)
+            hists.append(list(toks) + [fo])
+        bound, total = 0, 0
+        for rnd in range(4):
+            gen = [eegen.draft_distributions(oracle_greedy(osess[b], gamma), o.vocab, 431, rnd, session=b) for b in range(B)]
+            probs, drafts, u, v = ([x[i] for x in gen] for i in range(4))
+            ros = [osess[b].verify(drafts[b], TINY_EXITS, commit=False, want_logits=True) for b in range(B)]
+            ee.ee_verify_sampled_batch(sess, drafts, probs, u, v, temps, TINY_EXITS)
+            for b in range(B):
+                sess[b].ee_wait_final()
+                rg = sess[b].final_result()
+                exempt, err, n_bound, fin = check_sampled_pass(ros[b], rg, gpu_logits(sess[b], len(TINY_EXITS)), drafts[b], probs[b], u[b], v[b],
+                                                             temps[b], f"sampled batch B={B} round {rnd} session {b}")
+                bound += n_bound
+                total += (len(TINY_EXITS) + 1) * (gamma + 2)
+                osess[b].commit_rows(fin.accept_len, fin.next_token)
+                hists[b] += [int(t) for t in drafts[b][:fin.accept_len]] + [int(fin.next_token)]
+                if rg.accept_len != fin.accept_len or rg.next_token != fin.next_token:
+                    assert exempt
+                    sess[b].ee_prefill(hists[b], flags=ee.HOLD_LAST)
+                assert sess[b].ee_kv_len() == osess[b].kv_len and sess[b].ee_pending() == osess[b].pending
+        assert bound >= 0.75 * total, (bound, total)
+        # a session without EE_SAMPLING in the batch is refused
+        plain = g.session(64, max_gamma=gamma)
+        plain.ee_prefill(eegen.prompt_tokens(432, 8, o.vocab))
+        if (B + 1) * (gamma + 1) <= max_rows:
+            with pytest.raises(ee.EEError) as ei:
+                ee.ee_verify_sampled_batch(sess + [plain], drafts + [drafts[0]], probs + [probs[0]], u + [u[0]], v + [v[0]], temps + [1.0], TINY_EXITS)
+            assert ei.value.code == ee.EE_ESTATE
+        plain.free()
+    finally:
+        for s_ in sess:
+            s_.free()
+        g.free()
 
 
 def test_sampled_verification_special_cases(tiny_pair):
